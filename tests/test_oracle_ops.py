@@ -1,0 +1,395 @@
+"""Pins for the per-operator CPU oracle: closed forms, library special cases,
+brute force on tiny maps, invariants.  None of these re-types the oracle's own
+formula in vectorised form: the brute-force checkers are scalar Python loops
+over the textbook definition, the library checks call torch's CPU routines."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import fise_oracle as fo
+from paper_2305_17423_amd import workloads as wl
+
+
+def nchw(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.float64))).permute(0, 3, 1, 2)
+
+
+def nhwc(t):
+    return t.permute(0, 2, 3, 1).contiguous().numpy()
+
+
+def oihw(w):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(w, np.float64))).permute(0, 3, 1, 2)
+
+
+# ---------------------------------------------------------------- rounding
+def test_bf16_round_matches_library_and_ties():
+    rng = np.random.default_rng(1)
+    a = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    lib = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(fo.round_store(a, "bf16"), lib)
+    # ties go to the even 8-bit significand: 1 + 2^-8 -> 1 ; 1 + 3*2^-8 -> 1 + 2^-6
+    assert fo.round_store(1.0 + 2.0 ** -8, "bf16") == 1.0
+    assert fo.round_store(1.0 + 3 * 2.0 ** -8, "bf16") == 1.0 + 2.0 ** -6
+    assert fo.round_store(-(1.0 + 3 * 2.0 ** -8), "bf16") == -(1.0 + 2.0 ** -6)
+    # a float64 just above the tie must round up even though float32 would land on the tie first
+    assert fo.round_store(1.0 + 2.0 ** -8 + 2.0 ** -40, "bf16") == 1.0 + 2.0 ** -7
+    assert fo.round_store(0.0, "bf16") == 0.0
+
+
+# ---------------------------------------------------------------- detect / tiles
+def test_detect_closed_forms():
+    B, H, W, C = 2, 8, 8, 4
+    x = wl.normal(np.random.default_rng(2), (B, H, W, C))
+    pix, tm, idx = fo.mask_detect(x, x, 0.0, 4)
+    assert pix.sum() == 0 and tm.sum() == 0 and idx.size == 0          # identical maps: empty (strict >)
+    y = x.copy(); y[1, 5, 2, 3] += 0.8                                    # one element changed by delta
+    thr_hit = 0.8 / (B * C)
+    d = fo.pixel_diff(x, y)
+    assert np.count_nonzero(d) == 1 and abs(d[5, 2] - thr_hit) < 1e-6
+    pix, tm, idx = fo.mask_detect(x, y, thr_hit * 0.99, 4)
+    assert pix.sum() == 1 and pix[5, 2] == 1 and list(idx) == [1 * 2 + 0]
+    pix, _, idx = fo.mask_detect(x, y, thr_hit * 1.01, 4)
+    assert pix.sum() == 0 and idx.size == 0
+    # equality is not active: delta chosen so the mean is exactly the threshold
+    z = np.zeros((1, 4, 4, 2), np.float32); z2 = z.copy(); z2[0, 1, 1, :] = 0.25
+    pix, _, _ = fo.mask_detect(z, z2, 0.25, 2)
+    assert pix.sum() == 0
+    pix, _, _ = fo.mask_detect(z, z2, np.nextafter(np.float32(0.25), np.float32(0)), 2)
+    assert pix.sum() == 1
+
+
+def test_detect_is_mean_abs_diff_vs_scalar_loop():
+    rng = np.random.default_rng(3)
+    a = wl.normal(rng, (2, 4, 6, 3)); b = wl.normal(rng, (2, 4, 6, 3))
+    d = fo.pixel_diff(a, b)
+    for y in range(4):
+        for x in range(6):
+            s = np.float32(0)
+            for bb in range(2):
+                for c in range(3):
+                    s = np.float32(s + np.float32(abs(np.float32(b[bb, y, x, c] - a[bb, y, x, c]))))
+            assert d[y, x] == np.float32(s / np.float32(6))
+    # and close to the float64 mean
+    np.testing.assert_allclose(d, np.abs(b.astype(np.float64) - a).mean(axis=(0, 3)), rtol=1e-6)
+
+
+def test_tiles_bruteforce_all_masks():
+    H = W = 6; t = 2
+    for bits in range(2 ** 9):
+        tm_want = np.array([(bits >> i) & 1 for i in range(9)], np.uint8).reshape(3, 3)
+        pix = np.kron(tm_want, np.ones((t, t), np.uint8))
+        tm, idx = fo.tiles_from_pixels(pix, t)
+        np.testing.assert_array_equal(tm, tm_want)
+        assert list(idx) == [i for i in range(9) if (bits >> i) & 1]
+        ys, xs = fo.active_pixels(idx, t, W)
+        assert ys.size == int(pix.sum())
+        got = np.zeros_like(pix); got[ys, xs] = 1
+        np.testing.assert_array_equal(got, pix)                          # gather/scatter identity
+    # a single pixel activates exactly its tile
+    for y in range(6):
+        for x in range(6):
+            p = np.zeros((6, 6), np.uint8); p[y, x] = 1
+            _, idx = fo.tiles_from_pixels(p, 2)
+            assert list(idx) == [(y // 2) * 3 + x // 2]
+
+
+def test_active_pixel_order():
+    ys, xs = fo.active_pixels(np.array([1, 2], np.int32), 2, 4)          # 2x2 tile grid on a 4x4 map
+    assert list(zip(ys, xs)) == [(0, 2), (0, 3), (1, 2), (1, 3), (2, 0), (2, 1), (3, 0), (3, 1)]
+
+
+def test_mask_downsample_is_or_pool():
+    rng = np.random.default_rng(4)
+    m = (rng.random((8, 8)) < 0.2).astype(np.uint8)
+    want = F.max_pool2d(torch.from_numpy(m.astype(np.float32))[None, None], 2)[0, 0].numpy().astype(np.uint8)
+    np.testing.assert_array_equal(fo.mask_downsample(m), want)
+    # pooling a union of t-tiles gives the same tile list with tile edge t/2
+    pix = np.kron((rng.random((4, 4)) < 0.3).astype(np.uint8), np.ones((4, 4), np.uint8))
+    _, i0 = fo.tiles_from_pixels(pix, 4)
+    _, i1 = fo.tiles_from_pixels(fo.mask_downsample(pix), 2)
+    np.testing.assert_array_equal(i0, i1)
+
+
+# ---------------------------------------------------------------- GroupNorm + SiLU
+def test_gn_silu_full_mask_fresh_equals_library():
+    rng = np.random.default_rng(5)
+    B, H, W, C, G = 2, 8, 8, 16, 4
+    x = wl.normal(rng, (B, H, W, C), 2.0, mean=0.5)
+    g = wl.normal(rng, (C,), 0.3, mean=1.0); bt = wl.normal(rng, (C,), 0.3)
+    mean, rstd = fo.gn_stats(x, G, 1e-5)
+    y = np.zeros((B, H, W, C))
+    fo.masked_gn_silu(x, mean, rstd, g, bt, G, fo.full_index(H, W, 4), 4, y, "f64")
+    want = F.silu(F.group_norm(nchw(x), G, torch.from_numpy(g).double(), torch.from_numpy(bt).double(), 1e-5))
+    np.testing.assert_allclose(y, nhwc(want), rtol=0, atol=2e-6)        # stats are float32-stored
+    # unit gamma, zero beta, no SiLU: per-group mean 0 / var 1
+    u = (x.astype(np.float64).reshape(B, H * W, G, C // G) - mean[:, None, :, None]) * rstd[:, None, :, None]
+    np.testing.assert_allclose(u.mean(axis=(1, 3)), 0, atol=1e-6)
+    np.testing.assert_allclose(u.var(axis=(1, 3)), 1, atol=1e-4)
+
+
+def test_gn_silu_masked_touches_only_active_and_uses_given_stats():
+    rng = np.random.default_rng(6)
+    B, H, W, C, G = 2, 8, 8, 8, 2
+    x = wl.normal(rng, (B, H, W, C)); g = np.ones(C, np.float32); bt = np.zeros(C, np.float32)
+    mean = rng.standard_normal((B, G)); rstd = rng.uniform(0.5, 2, (B, G))
+    cache = rng.standard_normal((B, H, W, C)); y = cache.copy()
+    idx = np.array([1, 2], np.int32)
+    fo.masked_gn_silu(x, mean, rstd, g, bt, G, idx, 4, y, "f64")
+    act = np.zeros((H, W), bool); ys, xs = fo.active_pixels(idx, 4, W); act[ys, xs] = True
+    np.testing.assert_array_equal(y[:, ~act], cache[:, ~act])
+    b, yy, xx, c = 1, ys[3], xs[3], 5
+    u = (float(x[b, yy, xx, c]) - mean[b, c // 4]) * rstd[b, c // 4]
+    assert abs(y[b, yy, xx, c] - u / (1 + math.exp(-u))) < 1e-12
+    y2 = cache.copy()
+    fo.masked_gn_silu(x, mean, rstd, g, bt, G, np.zeros(0, np.int32), 4, y2, "f64")
+    np.testing.assert_array_equal(y2, cache)                             # empty mask
+
+
+def test_layernorm_gelu_geglu_vs_library():
+    rng = np.random.default_rng(7)
+    a = rng.standard_normal((2, 5, 12)); g = rng.standard_normal(12); b = rng.standard_normal(12)
+    want = F.layer_norm(torch.from_numpy(a), (12,), torch.from_numpy(g), torch.from_numpy(b), 1e-5).numpy()
+    np.testing.assert_allclose(fo.layernorm(a, g, b), want, atol=1e-12)
+    np.testing.assert_allclose(fo.gelu(a), F.gelu(torch.from_numpy(a)).numpy(), atol=1e-12)
+    v = fo.geglu(a)
+    np.testing.assert_allclose(v, a[..., :6] * F.gelu(torch.from_numpy(a[..., 6:])).numpy(), atol=1e-12)
+    assert fo.gelu(np.array([0.0]))[0] == 0 and abs(fo.gelu(np.array([10.0]))[0] - 10) < 1e-12
+
+
+# ---------------------------------------------------------------- convolution
+def _naive_conv_at(x, w, bias, b, y, xq, co, stride=1, upsample=False):
+    """Scalar textbook convolution at one output element (zero padding k//2)."""
+    B, Hi, Wi, Ci = x.shape
+    k = w.shape[1]; pad = k // 2
+    s = float(bias[co])
+    for ky in range(k):
+        for kx in range(k):
+            if upsample:
+                uy, ux = y + ky - pad, xq + kx - pad
+                if not (0 <= uy < 2 * Hi and 0 <= ux < 2 * Wi):
+                    continue
+                iy, ix = uy // 2, ux // 2
+            else:
+                iy, ix = y * stride + ky - pad, xq * stride + kx - pad
+                if not (0 <= iy < Hi and 0 <= ix < Wi):
+                    continue
+            for ci in range(Ci):
+                s += float(w[co, ky, kx, ci]) * float(x[b, iy, ix, ci])
+    return s
+
+
+@pytest.mark.parametrize("k,stride,ups", [(3, 1, False), (1, 1, False), (3, 2, False), (3, 1, True)])
+def test_conv_full_mask_equals_library(k, stride, ups):
+    rng = np.random.default_rng(8)
+    B, H, W, Ci, Co = 2, 8, 8, 5, 7
+    x = wl.normal(rng, (B, H, W, Ci)); w = wl.normal(rng, (Co, k, k, Ci), 0.2); bias = wl.normal(rng, (Co,))
+    Ho = 2 * H if ups else H // stride
+    y = np.zeros((B, Ho, Ho, Co))
+    fo.masked_conv(x, w, bias, fo.full_index(Ho, Ho, 2), 2, y, "f64", stride=stride, upsample=ups)
+    xin = nchw(x)
+    if ups:
+        xin = F.interpolate(xin, scale_factor=2, mode="nearest")
+    want = F.conv2d(xin, oihw(w), torch.from_numpy(bias).double(), stride=stride, padding=k // 2)
+    np.testing.assert_allclose(y, nhwc(want), atol=1e-12)
+
+
+def test_conv_bruteforce_every_tile_mask_tiny():
+    rng = np.random.default_rng(9)
+    B, H, W, Ci, Co, t = 1, 6, 6, 2, 3, 2
+    x_old = wl.normal(rng, (B, H, W, Ci)); w = wl.normal(rng, (Co, 3, 3, Ci), 0.5); bias = wl.normal(rng, (Co,))
+    x_new = wl.normal(rng, (B, H, W, Ci))
+    cache = rng.standard_normal((B, H, W, Co))
+    for bits in range(2 ** 9):
+        idx = np.array([i for i in range(9) if (bits >> i) & 1], np.int32)
+        y = cache.copy()
+        fo.masked_conv(x_new, w, bias, idx, t, y, "f64")
+        act = np.zeros((H, W), bool); ys, xs = fo.active_pixels(idx, t, W); act[ys, xs] = True
+        np.testing.assert_array_equal(y[0][~act], cache[0][~act])
+        if bits in (0b000010000, 0b101000101, 0b111111111, 0b100000000):     # scalar check on a few masks
+            for yy, xx in zip(ys, xs):
+                for co in range(Co):
+                    assert abs(y[0, yy, xx, co] - _naive_conv_at(x_new, w, bias, 0, yy, xx, co)) < 1e-12
+        else:                                                                   # library check on the rest
+            want = nhwc(F.conv2d(nchw(x_new), oihw(w), torch.from_numpy(bias).double(), padding=1))
+            np.testing.assert_allclose(y[0][act], want[0][act], atol=1e-12)
+
+
+@pytest.mark.parametrize("stride,ups", [(2, False), (1, True)])
+def test_conv_resample_scalar(stride, ups):
+    rng = np.random.default_rng(10)
+    B, H, W, Ci, Co = 2, 4, 4, 3, 2
+    x = wl.normal(rng, (B, H, W, Ci)); w = wl.normal(rng, (Co, 3, 3, Ci)); bias = wl.normal(rng, (Co,))
+    Ho = 2 * H if ups else H // stride
+    t = 2 if ups else 1
+    idx = np.array([0, 3], np.int32)
+    y = np.full((B, Ho, Ho, Co), 7.0)
+    fo.masked_conv(x, w, bias, idx, t, y, "f64", stride=stride, upsample=ups)
+    ys, xs = fo.active_pixels(idx, t, Ho)
+    act = np.zeros((Ho, Ho), bool); act[ys, xs] = True
+    assert (y[:, ~act] == 7.0).all()
+    for b in range(B):
+        for yy, xx in zip(ys, xs):
+            for co in range(Co):
+                assert abs(y[b, yy, xx, co] - _naive_conv_at(x, w, bias, b, yy, xx, co, stride, ups)) < 1e-12
+
+
+def test_conv_concat_sources_and_epilogue():
+    rng = np.random.default_rng(11)
+    B, H, W = 2, 4, 4
+    a = wl.normal(rng, (B, H, W, 3)); s = wl.normal(rng, (B, H, W, 2)); w = wl.normal(rng, (4, 3, 3, 5))
+    bias = wl.normal(rng, (4,)); temb = wl.normal(rng, (B, 4)); res = wl.normal(rng, (B, H, W, 4))
+    y1 = np.zeros((B, H, W, 4)); y2 = np.zeros((B, H, W, 4))
+    full = fo.full_index(H, W, 2)
+    fo.masked_conv([a, s], w, bias, full, 2, y1, "f64", temb=temb, residual=res)
+    fo.masked_conv(np.concatenate([a, s], -1), w, bias, full, 2, y2, "f64")
+    np.testing.assert_allclose(y1, y2 + temb[:, None, None, :] + res, atol=1e-12)
+
+
+def test_conv_fused_gn_equals_gn_then_conv_library():
+    rng = np.random.default_rng(12)
+    B, H, W, C, G = 2, 8, 8, 8, 4
+    x = wl.normal(rng, (B, H, W, C), 1.5); w = wl.normal(rng, (6, 3, 3, C), 0.2); bias = wl.normal(rng, (6,))
+    g = wl.normal(rng, (C,), 0.2, mean=1.0); bt = wl.normal(rng, (C,), 0.2)
+    mean, rstd = fo.gn_stats(x, G, 1e-5)
+    y = np.zeros((B, H, W, 6))
+    fo.masked_conv(x, w, bias, fo.full_index(H, W, 4), 4, y, "f64",
+                   gn=dict(mean=mean, rstd=rstd, gamma=g, beta=bt, groups=G))
+    a = F.silu(F.group_norm(nchw(x), G, torch.from_numpy(g).double(), torch.from_numpy(bt).double(), 1e-5))
+    want = F.conv2d(a, oihw(w), torch.from_numpy(bias).double(), padding=1)   # zero padding AFTER the activation
+    np.testing.assert_allclose(y, nhwc(want), atol=1e-5)
+
+
+def test_conv_masked_equals_dense_at_active_cache_elsewhere_locality_idempotence():
+    """Config-1-shaped case (smaller): perturb a rectangle, detect, masked conv."""
+    rng = np.random.default_rng(1001)
+    B, H, W, C, t = 1, 16, 16, 8, 4
+    x_old = wl.normal(rng, (B, H, W, C)); w = wl.normal(rng, (C, 3, 3, C), 1 / math.sqrt(9 * C)); bias = np.zeros(C, np.float32)
+    rect = wl.rect_pixels(rng, H, W, 5, 5)
+    x_new = wl.perturb(rng, x_old, rect)
+    full = fo.full_index(H, W, t)
+    cache = np.zeros((B, H, W, C)); fo.masked_conv(x_old, w, bias, full, t, cache, "f32")
+    dense_new = np.zeros((B, H, W, C)); fo.masked_conv(x_new, w, bias, full, t, dense_new, "f32")
+    pix, tm, idx = fo.mask_detect(x_old, x_new, 0.1, t)
+    np.testing.assert_array_equal(pix, rect)                            # N(0,1) noise over 8 channels: far from 0.1
+    y = cache.copy(); fo.masked_conv(x_new, w, bias, idx, t, y, "f32")
+    act = np.kron(tm, np.ones((t, t), np.uint8)).astype(bool)
+    np.testing.assert_array_equal(y[0][act], dense_new[0][act])          # masked == dense at active
+    np.testing.assert_array_equal(y[0][~act], cache[0][~act])            # cache elsewhere, bitwise
+    # locality: masked and dense-of-new differ only inside dilate(rect, 1) minus the active tiles
+    dil = F.max_pool2d(torch.from_numpy(rect.astype(np.float32))[None, None], 3, 1, 1)[0, 0].numpy().astype(bool)
+    differs = (y[0] != dense_new[0]).any(axis=-1)
+    assert not (differs & ~(dil & ~act)).any()
+    y2 = y.copy(); fo.masked_conv(x_new, w, bias, idx, t, y2, "f32")
+    np.testing.assert_array_equal(y2, y)                                 # idempotent
+    y3 = cache.copy(); fo.masked_conv(x_new, w, bias, np.zeros(0, np.int32), t, y3, "f32")
+    np.testing.assert_array_equal(y3, cache)                             # empty mask -> cache
+    # tile-size independence for a mask that is a union of 4x4 tiles
+    _, idx2 = fo.tiles_from_pixels(act.astype(np.uint8), 2)
+    y4 = cache.copy(); fo.masked_conv(x_new, w, bias, idx2, 2, y4, "f32")
+    np.testing.assert_array_equal(y4, y)
+
+
+# ---------------------------------------------------------------- attention
+def test_attention_equals_library_sdpa():
+    rng = np.random.default_rng(13)
+    B, M, N, C, heads = 2, 7, 19, 24, 4
+    q = rng.standard_normal((B, M, C)); K = rng.standard_normal((B, N, C)); V = rng.standard_normal((B, N, C))
+    def split(t):
+        return torch.from_numpy(t).reshape(B, t.shape[1], heads, C // heads).permute(0, 2, 1, 3)
+    want = F.scaled_dot_product_attention(split(q), split(K), split(V)).permute(0, 2, 1, 3).reshape(B, M, C).numpy()
+    np.testing.assert_allclose(fo.attention_active(q, K, V, heads), want, atol=1e-12)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(14)
+    B, M, N, C, heads = 1, 5, 9, 8, 2
+    q = rng.standard_normal((B, M, C)); K = rng.standard_normal((B, N, C)); V = rng.standard_normal((B, N, C))
+    Vc = np.broadcast_to(rng.standard_normal((1, 1, C)), (B, N, C))
+    np.testing.assert_allclose(fo.attention_active(q, K, Vc, heads), np.broadcast_to(Vc[:, :1], (B, M, C)), atol=1e-12)
+    np.testing.assert_allclose(fo.attention_active(q, K[:, :1], V[:, :1], heads), np.broadcast_to(V[:, :1], (B, M, C)), atol=1e-12)
+    Ke = np.broadcast_to(K[:, :1], (B, N, C))
+    np.testing.assert_allclose(fo.attention_active(q, Ke, V, heads), np.broadcast_to(V.mean(1, keepdims=True), (B, M, C)), atol=1e-12)
+    perm = rng.permutation(N)
+    np.testing.assert_allclose(fo.attention_active(q, K[:, perm], V[:, perm], heads), fo.attention_active(q, K, V, heads), atol=1e-12)
+    # a dominant key wins: scale matters (1/sqrt(d)), head h only sees its channels
+    K2 = np.zeros((1, 2, 8)); V2 = np.zeros((1, 2, 8)); q2 = np.zeros((1, 1, 8))
+    q2[0, 0, :4] = 1.0; K2[0, 1, :4] = 1.0; V2[0, 0, :] = 1.0; V2[0, 1, :] = 3.0
+    o = fo.attention_active(q2, K2, V2, 2)
+    p1 = math.exp(4 / 2.0) / (1 + math.exp(4 / 2.0))                   # q.k = 4, d = 4 -> logit 2
+    np.testing.assert_allclose(o[0, 0, :4], 1 + 2 * p1, atol=1e-12)
+    np.testing.assert_allclose(o[0, 0, 4:], 2.0, atol=1e-12)            # second head: equal logits
+
+
+def test_masked_attention_block_refreshes_kv_and_matches_dense_rows():
+    rng = np.random.default_rng(15)
+    B, H, W, C, heads, t = 2, 4, 4, 8, 2, 2
+    x_old = wl.normal(rng, (B, H, W, C)); x_new = x_old.copy()
+    idx = np.array([1, 2], np.int32)
+    ys, xs = fo.active_pixels(idx, t, W)
+    x_new[:, ys, xs, :] += rng.standard_normal((B, ys.size, C)).astype(np.float32)
+    g = np.ones(C); b0 = np.zeros(C)
+    wq, wk, wv, wo = (rng.standard_normal((C, C)) * 0.3 for _ in range(4)); bo = rng.standard_normal(C)
+    full = fo.full_index(H, W, t)
+    def dense(x):
+        Kc = np.zeros((B, H * W, C)); Vc = np.zeros((B, H * W, C)); y = np.zeros((B, H, W, C))
+        fo.masked_attention_block(x, g, b0, wq, wk, wv, wo, bo, heads, Kc, Vc, None, None, full, t, y, "f64")
+        return y, Kc, Vc
+    y_old, K_old, V_old = dense(x_old)
+    y_new, K_new, V_new = dense(x_new)
+    y, Kc, Vc = y_old.copy(), K_old.copy(), V_old.copy()
+    fo.masked_attention_block(x_new, g, b0, wq, wk, wv, wo, bo, heads, Kc, Vc, None, None, idx, t, y, "f64")
+    np.testing.assert_allclose(Kc, K_new, atol=1e-12); np.testing.assert_allclose(Vc, V_new, atol=1e-12)
+    act = np.zeros((H, W), bool); act[ys, xs] = True
+    np.testing.assert_allclose(y[:, act], y_new[:, act], atol=1e-12)      # active rows == dense of updated input
+    np.testing.assert_array_equal(y[:, ~act], y_old[:, ~act])             # the rest stays cached
+    # library cross-check of the dense block
+    n = F.layer_norm(torch.from_numpy(x_new.reshape(B, H * W, C).astype(np.float64)), (C,))
+    qh, kh, vh = (( n @ torch.from_numpy(m).T).reshape(B, H * W, heads, C // heads).permute(0, 2, 1, 3) for m in (wq, wk, wv))
+    o = F.scaled_dot_product_attention(qh, kh, vh).permute(0, 2, 1, 3).reshape(B, H * W, C)
+    want = torch.from_numpy(x_new.reshape(B, H * W, C).astype(np.float64)) + o @ torch.from_numpy(wo).T + torch.from_numpy(bo)
+    np.testing.assert_allclose(y_new.reshape(B, H * W, C), want.numpy(), atol=1e-10)
+
+
+# ---------------------------------------------------------------- Otsu / APSC
+def test_otsu_objective_is_between_class_variance_and_two_cluster_case():
+    rng = np.random.default_rng(16)
+    d = fo.normalize_minmax(np.concatenate([rng.uniform(0, 0.2, 300), rng.uniform(0.7, 1.0, 100)]).reshape(20, 20))
+    assert d.min() == 0 and d.max() == 1
+    v = d.reshape(-1)
+    for eps in (0.1, 0.3, 0.5, 0.9):
+        A, Bc = v[v < eps], v[v >= eps]
+        w0, w1 = A.size / v.size, Bc.size / v.size
+        # textbook identity: w0 w1 (mu0 - mu1)^2 = total variance - within-class variance
+        within = w0 * A.var() + w1 * Bc.var()
+        assert abs(fo.otsu_objective(d, eps) - (v.var() - within)) < 1e-12
+    eps, mask = fo.otsu_threshold(d)
+    assert 0.2 < eps <= 0.7 + 1 / 256 and mask.sum() == 100           # splits the two clusters exactly
+    assert fo.otsu_objective(d, 0.0) == 0 and fo.otsu_objective(d, 1.5) == 0
+
+
+def test_apsc_bruteforce():
+    rng = np.random.default_rng(17)
+    pix = wl.ellipse_pixels(rng, 32, 32, 0.1)
+    h, w, c = fo.apsc_block_size(pix)
+    best = None
+    for hh, ww in itertools.product((2, 4, 8, 16, 32), repeat=2):
+        n = 0
+        for by in range(32 // hh):
+            for bx in range(32 // ww):
+                n += int(pix[by * hh:(by + 1) * hh, bx * ww:(bx + 1) * ww].any())
+        cost = (hh + 2) * (ww + 2) * n
+        if best is None or cost < best[0]:
+            best = (cost, hh, ww)
+    assert (c, h, w) == best
+    # full mask: gathered-halo overhead falls with block size -> largest block wins
+    assert fo.apsc_block_size(np.ones((32, 32), np.uint8))[:2] == (32, 32)
+    # single pixel: the smallest block wins
+    p = np.zeros((32, 32), np.uint8); p[5, 9] = 1
+    assert fo.apsc_block_size(p)[:2] == (2, 2)
+    # as printed, blocks smaller than the kernel have non-positive cost and are skipped
+    assert fo.apsc_block_size(p, as_written=True)[:2] == (4, 4)
