@@ -45,7 +45,7 @@ def sd15_desc(**over):
 
 def tiny_desc(**over):
     """Same topology, 1/10 of the width, 16x16 latent: runs in a second."""
-    d = sd15_desc(base=32, heads=4, ctx_dim=48, n_ctx=11, H=16, W=16)
+    d = sd15_desc(base=32, heads=4, ctx_dim=64, n_ctx=11, H=16, W=16)
     d.update(over)
     return d
 

@@ -1,0 +1,151 @@
+// Public masked-convolution entry points.  bf16 maps whose channel counts are
+// multiples of 32 go to the MFMA implicit GEMM; float maps and odd channel counts
+// (e.g. the 4-channel latent) use the scalar kernel below, one output element per
+// thread, same gather rules.
+#include "igemm.h"
+
+namespace fise {
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ x0, const T* __restrict__ x1, int C0, int C1,
+                                                          int B, int Hin, int Win, const T* __restrict__ w,
+                                                          const T* __restrict__ bias, int Cout, int ksize, int stride, int ups,
+                                                          const float* __restrict__ gn_mean, const float* __restrict__ gn_rstd,
+                                                          const T* __restrict__ gn_gamma, const T* __restrict__ gn_beta, int G,
+                                                          int gn_silu, const float* __restrict__ temb, const T* residual,
+                                                          const int* __restrict__ tile_idx, int Ma, int tile, int Ho, int Wo,
+                                                          T* y) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)B * Ma * Cout;
+    if (i >= total) return;
+    const int co = (int)(i % Cout);
+    const int m = (int)((i / Cout) % Ma);
+    const int b = (int)(i / ((long long)Cout * Ma));
+    int oy, ox;
+    active_pixel(tile_idx, m, tile, Wo / tile, oy, ox);
+    const int Cin = C0 + C1, pad = ksize >> 1;
+    const int cpg = gn_mean ? Cin / G : 1;
+    float acc = 0.f;
+    for (int ky = 0; ky < ksize; ++ky)
+        for (int kx = 0; kx < ksize; ++kx) {
+            int iy, ix; bool in;
+            if (ups) {
+                const int uy = oy + ky - pad, ux = ox + kx - pad;
+                in = uy >= 0 && uy < 2 * Hin && ux >= 0 && ux < 2 * Win; iy = uy >> 1; ix = ux >> 1;
+            } else {
+                iy = oy * stride + ky - pad; ix = ox * stride + kx - pad;
+                in = iy >= 0 && iy < Hin && ix >= 0 && ix < Win;
+            }
+            if (!in) continue;
+            const size_t p = ((size_t)b * Hin + iy) * Win + ix;
+            const T* wr = w + ((size_t)co * ksize * ksize + ky * ksize + kx) * Cin;
+            for (int c = 0; c < Cin; ++c) {
+                float v = c < C0 ? Elem<T>::ld(x0 + p * C0 + c) : Elem<T>::ld(x1 + p * C1 + (c - C0));
+                if (gn_mean) {
+                    const int g = c / cpg;
+                    v = (v - gn_mean[b * G + g]) * gn_rstd[b * G + g] * Elem<T>::ld(gn_gamma + c) + Elem<T>::ld(gn_beta + c);
+                    if (gn_silu) v = silu_f(v);
+                }
+                acc = fmaf(v, Elem<T>::ld(wr + c), acc);
+            }
+        }
+    if (bias) acc += Elem<T>::ld(bias + co);
+    if (temb) acc += temb[b * Cout + co];
+    const size_t o = (((size_t)b * Ho + oy) * Wo + ox) * Cout + co;
+    if (residual) acc += Elem<T>::ld(residual + o);
+    Elem<T>::st(y + o, acc);
+}
+
+static int validate(const fise_conv_args* a, int& Ho, int& Wo) {
+    if (!a) return fail(FISE_ERR_NULL, "fise_masked_conv: null args");
+    if (!a->x0 || !a->w || !a->y_cache) return fail(FISE_ERR_NULL, "fise_masked_conv: null x / w / y_cache");
+    if (a->dtype != FISE_F32 && a->dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_masked_conv: dtype %d", a->dtype);
+    if (a->C1 < 0 || (a->C1 > 0 && !a->x1)) return fail(FISE_ERR_NULL, "fise_masked_conv: second source missing");
+    if (a->B < 1 || a->H < 1 || a->W < 1 || a->C0 < 1 || a->Cout < 1) return fail(FISE_ERR_SHAPE, "fise_masked_conv: bad shape");
+    if (a->ksize != 1 && a->ksize != 3) return fail(FISE_ERR_SHAPE, "fise_masked_conv: ksize %d (1 or 3)", a->ksize);
+    if (a->stride != 1 && a->stride != 2) return fail(FISE_ERR_SHAPE, "fise_masked_conv: stride %d (1 or 2)", a->stride);
+    if (a->upsample && a->stride != 1) return fail(FISE_ERR_SHAPE, "fise_masked_conv: upsample needs stride 1");
+    if (a->stride == 2 && ((a->H & 1) || (a->W & 1))) return fail(FISE_ERR_SHAPE, "fise_masked_conv: stride 2 needs even H, W");
+    Ho = a->upsample ? 2 * a->H : a->H / a->stride;
+    Wo = a->upsample ? 2 * a->W : a->W / a->stride;
+    if (a->tile < 1 || Ho % a->tile || Wo % a->tile)
+        return fail(FISE_ERR_SHAPE, "fise_masked_conv: output %dx%d not divisible by tile %d", Ho, Wo, a->tile);
+    if (a->n_active < 0 || a->n_active > (Ho / a->tile) * (Wo / a->tile))
+        return fail(FISE_ERR_CAPACITY, "fise_masked_conv: n_active %d beyond the %dx%d tile grid", a->n_active, Ho / a->tile, Wo / a->tile);
+    if (a->n_active > 0 && !a->tile_idx) return fail(FISE_ERR_NULL, "fise_masked_conv: null tile_idx");
+    if (a->gn_mean) {
+        if (!a->gn_rstd || !a->gn_gamma || !a->gn_beta) return fail(FISE_ERR_NULL, "fise_masked_conv: incomplete GroupNorm arguments");
+        if (a->G < 1 || (a->C0 + a->C1) % a->G) return fail(FISE_ERR_SHAPE, "fise_masked_conv: C=%d %% G=%d", a->C0 + a->C1, a->G);
+    }
+    if (a->y_cache == a->x0 || (a->x1 && a->y_cache == a->x1)) return fail(FISE_ERR_SHAPE, "fise_masked_conv: y_cache aliases an input map");
+    const void* ptrs[] = {a->x0, a->x1, a->w, a->bias, a->residual, a->y_cache, a->gn_gamma, a->gn_beta};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return fail(FISE_ERR_ALIGN, "fise_masked_conv: pointer %p not 16-byte aligned", p);
+    return FISE_OK;
+}
+
+static bool mfma_path(const fise_conv_args* a) {
+    return a->dtype == FISE_BF16 && a->C0 % 32 == 0 && a->C1 % 32 == 0;
+}
+
+template <typename T>
+static void launch_scalar(const fise_conv_args* a, int Ho, int Wo, hipStream_t st) {
+    const int Ma = a->n_active * a->tile * a->tile;
+    const long long total = (long long)a->B * Ma * a->Cout;
+    hipLaunchKernelGGL(conv_scalar_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a->x0,
+                       (const T*)a->x1, a->C0, a->C1, a->B, a->H, a->W, (const T*)a->w, (const T*)a->bias, a->Cout, a->ksize,
+                       a->stride, a->upsample ? 1 : 0, a->gn_mean, a->gn_rstd, (const T*)a->gn_gamma, (const T*)a->gn_beta,
+                       a->G, a->gn_silu, a->temb, (const T*)a->residual, a->tile_idx, Ma, a->tile, Ho, Wo, (T*)a->y_cache);
+}
+
+int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    int Ho, Wo;
+    if (int e = validate(a, Ho, Wo)) return e;
+    if (a->n_active == 0) return FISE_OK;
+    (void)workspace; (void)workspace_bytes;
+    if (!mfma_path(a)) {
+        if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st);
+        else launch_scalar<bf16_t>(a, Ho, Wo, st);
+        FISE_CHECK_LAUNCH("fise_masked_conv(scalar)");
+        return FISE_OK;
+    }
+    IgemmArgs g{};
+    g.a0 = (const bf16_t*)a->x0; g.a1 = (const bf16_t*)a->x1; g.C0 = a->C0; g.C1 = a->C1; g.a_compact = 0;
+    g.Hin = a->H; g.Win = a->W; g.ksize = a->ksize; g.stride = a->stride; g.ups = a->upsample ? 1 : 0;
+    g.tile_idx = a->tile_idx; g.tile = a->tile; g.tiles_w = Wo / a->tile; g.Ho = Ho; g.Wo = Wo; g.B = a->B;
+    g.Ma = a->n_active * a->tile * a->tile;
+    g.pro = a->gn_mean ? (a->gn_silu ? PRO_GN_SILU : PRO_GN) : PRO_NONE;
+    g.gn_mean = a->gn_mean; g.gn_rstd = a->gn_rstd; g.gn_gamma = (const bf16_t*)a->gn_gamma; g.gn_beta = (const bf16_t*)a->gn_beta; g.G = a->G;
+    g.w = (const bf16_t*)a->w; g.N = a->Cout; g.K = a->ksize * a->ksize * (a->C0 + a->C1); g.geglu = 0;
+    g.bias = (const bf16_t*)a->bias; g.temb = a->temb; g.temb_stride = a->Cout; g.res = (const bf16_t*)a->residual; g.res_compact = 0;
+    g.nsect = 1; g.sect_n = a->Cout; g.out[0] = (bf16_t*)a->y_cache; g.out_mode[0] = OUT_MAP;
+    g.splits = 1; g.partial = nullptr; g.counters = nullptr;
+    return launch_igemm(g, st);
+}
+
+}  // namespace fise
+
+using namespace fise;
+
+extern "C" size_t fise_masked_conv_workspace_bytes(const fise_conv_args* a) {
+    (void)a;
+    return 256;
+}
+
+extern "C" int fise_masked_conv(const fise_conv_args* a, void* workspace, size_t workspace_bytes, void* stream) {
+    return conv_dispatch(a, workspace, workspace_bytes, as_stream(stream));
+}
+
+extern "C" int fise_masked_conv3x3(const void* x, const void* w, const void* bias, int dtype, int B, int H, int W, int Cin,
+                                   int Cout, int stride, const int32_t* tile_idx, int n_active, int tile,
+                                   const float* gn_mean, const float* gn_rstd, const void* gn_gamma, const void* gn_beta,
+                                   int G, const float* temb, const void* residual, void* y_cache, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+    fise_conv_args a{};
+    a.x0 = x; a.x1 = nullptr; a.C0 = Cin; a.C1 = 0; a.B = B; a.H = H; a.W = W; a.w = w; a.bias = bias; a.Cout = Cout;
+    a.ksize = 3; a.stride = stride; a.upsample = 0;
+    a.gn_mean = gn_mean; a.gn_rstd = gn_rstd; a.gn_gamma = gn_gamma; a.gn_beta = gn_beta; a.G = G; a.gn_silu = 1;
+    a.temb = temb; a.residual = residual; a.tile_idx = tile_idx; a.n_active = n_active; a.tile = tile; a.y_cache = y_cache;
+    a.dtype = dtype;
+    return conv_dispatch(&a, workspace, workspace_bytes, as_stream(stream));
+}

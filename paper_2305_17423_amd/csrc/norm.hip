@@ -1,0 +1,233 @@
+// Normalisation kernels: dense GroupNorm statistics (two-stage, deterministic),
+// masked GroupNorm+SiLU with given statistics, per-row LayerNorm of compact
+// token buffers.
+#include "igemm.h"
+
+namespace fise {
+
+constexpr int GS_PIX = 64;       // pixels per stage-1 workgroup
+constexpr int GS_MAXJ = 4;       // channels per thread per pass (256 threads -> 1024 channels per pass)
+
+// stage 1: partial[b][chunk][g] = (sum, sum of squares) over GS_PIX pixels x the group's channels.
+template <typename T>
+__global__ __launch_bounds__(256) void gn_partial_kernel(const T* __restrict__ x0, const T* __restrict__ x1, int HW,
+                                                         int C0, int C1, int G, double2* __restrict__ partial) {
+    extern __shared__ double2 chan[];                    // [C0 + C1]
+    const int C = C0 + C1, cpg = C / G;
+    const int b = blockIdx.y, chunk = blockIdx.x, nchunk = gridDim.x;
+    const int p0 = chunk * GS_PIX, p1 = min(HW, p0 + GS_PIX);
+    for (int cbase = 0; cbase < C; cbase += 256 * GS_MAXJ) {
+        float s[GS_MAXJ], q[GS_MAXJ];
+#pragma unroll
+        for (int j = 0; j < GS_MAXJ; ++j) { s[j] = 0.f; q[j] = 0.f; }
+        for (int p = p0; p < p1; ++p) {
+#pragma unroll
+            for (int j = 0; j < GS_MAXJ; ++j) {
+                const int c = cbase + threadIdx.x + 256 * j;
+                if (c < C) {
+                    const float v = c < C0 ? Elem<T>::ld(x0 + ((size_t)b * HW + p) * C0 + c)
+                                           : Elem<T>::ld(x1 + ((size_t)b * HW + p) * C1 + (c - C0));
+                    s[j] += v; q[j] += v * v;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < GS_MAXJ; ++j) {
+            const int c = cbase + threadIdx.x + 256 * j;
+            if (c < C) chan[c] = make_double2((double)s[j], (double)q[j]);
+        }
+    }
+    __syncthreads();
+    for (int g = threadIdx.x; g < G; g += 256) {
+        double s = 0, q = 0;
+        for (int c = g * cpg; c < (g + 1) * cpg; ++c) { s += chan[c].x; q += chan[c].y; }
+        partial[((size_t)b * nchunk + chunk) * G + g] = make_double2(s, q);
+    }
+}
+
+// stage 2: one thread per (b, g), chunks summed in index order.
+__global__ void gn_finish_kernel(const double2* __restrict__ partial, int nchunk, int BG, int G, double count, float eps,
+                                 float* __restrict__ mean, float* __restrict__ rstd) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= BG) return;
+    const int b = i / G, g = i % G;
+    double s = 0, q = 0;
+    for (int k = 0; k < nchunk; ++k) { const double2 v = partial[((size_t)b * nchunk + k) * G + g]; s += v.x; q += v.y; }
+    const double m = s / count;
+    double var = q / count - m * m;
+    if (var < 0) var = 0;
+    mean[i] = (float)m;
+    rstd[i] = (float)(1.0 / sqrt(var + (double)eps));
+}
+
+template <typename T>
+__global__ void masked_gn_silu_kernel(const T* __restrict__ x, const float* __restrict__ mean, const float* __restrict__ rstd,
+                                      const T* __restrict__ gamma, const T* __restrict__ beta, int B, int H, int W, int C,
+                                      int G, const int* __restrict__ tile_idx, int Ma, int tile, T* __restrict__ y) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)B * Ma * C;
+    if (i >= total) return;
+    const int c = (int)(i % C);
+    const int m = (int)((i / C) % Ma);
+    const int b = (int)(i / ((long long)C * Ma));
+    int py, px;
+    active_pixel(tile_idx, m, tile, W / tile, py, px);
+    const size_t off = (((size_t)b * H + py) * W + px) * C + c;
+    const int g = c / (C / G);
+    const float u = (Elem<T>::ld(x + off) - mean[b * G + g]) * rstd[b * G + g] * Elem<T>::ld(gamma + c) + Elem<T>::ld(beta + c);
+    Elem<T>::st(y + off, silu_f(u));
+}
+
+// LayerNorm of rows -> compact out[rows, C] (bf16), one wave per row, two passes (mean,
+// then centred variance) in float.  With tile_idx the rows are gathered from a token map.
+__global__ __launch_bounds__(256) void ln_rows_kernel(const bf16_t* __restrict__ in, int rows, int C,
+                                                      const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta,
+                                                      float eps, bf16_t* __restrict__ out, const int* __restrict__ tile_idx,
+                                                      int tile, int tiles_w, int H, int W, int Ma) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    const bf16_t* r;
+    if (tile_idx) {
+        int py, px;
+        active_pixel(tile_idx, row % Ma, tile, tiles_w, py, px);
+        r = in + (((size_t)(row / Ma) * H + py) * W + px) * C;
+    } else {
+        r = in + (size_t)row * C;
+    }
+    float s = 0.f;
+    for (int c = lane; c < C; c += 64) s += bf2f(r[c]);
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mu = s / C;
+    float q = 0.f;
+    for (int c = lane; c < C; c += 64) { const float d = bf2f(r[c]) - mu; q += d * d; }
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    const float rs = rsqrtf(q / C + eps);
+    for (int c = lane; c < C; c += 64)
+        out[(size_t)row * C + c] = f2bf((bf2f(r[c]) - mu) * rs * bf2f(gamma[c]) + bf2f(beta[c]));
+}
+
+int launch_ln_rows(const void* in, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
+                   const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st) {
+    if (rows <= 0) return FISE_OK;
+    hipLaunchKernelGGL(ln_rows_kernel, dim3(ceil_div(rows, 4)), dim3(256), 0, st, (const bf16_t*)in, rows, C,
+                       (const bf16_t*)gamma, (const bf16_t*)beta, eps, (bf16_t*)out, tile_idx, tile, tiles_w, H, W, Ma);
+    FISE_CHECK_LAUNCH("layernorm rows");
+    return FISE_OK;
+}
+
+// A few rows times a weight matrix: one wave per output column, lanes stride over K in
+// 8-element (16-byte) weight loads.  K % 8 == 0.
+template <int NB>
+__global__ __launch_bounds__(256) void small_linear_kernel(const float* __restrict__ in, int K, const bf16_t* __restrict__ W,
+                                                           const bf16_t* __restrict__ bias, int N, int silu_out,
+                                                           float* __restrict__ out) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (n >= N) return;
+    float acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+    for (int k = lane * 8; k < K; k += 64 * 8) {
+        const uint4 wv = *reinterpret_cast<const uint4*>(W + (size_t)n * K + k);
+        const unsigned w4[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float wf = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xffff0000u) : __uint_as_float(w4[e >> 1] << 16);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[b] = fmaf(in[(size_t)b * K + k + e], wf, acc[b]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float v = acc[b];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) {
+            if (bias) v += bf2f(bias[n]);
+            out[(size_t)b * N + n] = silu_out ? silu_f(v) : v;
+        }
+    }
+}
+
+int launch_small_linear(const float* in, int B, int K, const void* W, const void* bias, int N, int silu_out, float* out,
+                        hipStream_t st) {
+    if (K % 8) return fail(FISE_ERR_ALIGN, "small linear: K=%d must be a multiple of 8", K);
+    const dim3 grid(ceil_div(N, 4)), block(256);
+    for (int b0 = 0; b0 < B; b0 += 2) {
+        const float* i0 = in + (size_t)b0 * K; float* o0 = out + (size_t)b0 * N;
+        if (B - b0 >= 2)
+            hipLaunchKernelGGL(small_linear_kernel<2>, grid, block, 0, st, i0, K, (const bf16_t*)W, (const bf16_t*)bias, N, silu_out, o0);
+        else
+            hipLaunchKernelGGL(small_linear_kernel<1>, grid, block, 0, st, i0, K, (const bf16_t*)W, (const bf16_t*)bias, N, silu_out, o0);
+        FISE_CHECK_LAUNCH("small linear");
+    }
+    return FISE_OK;
+}
+
+__global__ void iota_kernel(int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = i;
+}
+int launch_iota(int* p, int n, hipStream_t st) {
+    if (n <= 0) return FISE_OK;
+    hipLaunchKernelGGL(iota_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, p, n);
+    FISE_CHECK_LAUNCH("iota");
+    return FISE_OK;
+}
+
+}  // namespace fise
+
+using namespace fise;
+
+extern "C" size_t fise_groupnorm_stats_workspace_bytes(int B, int H, int W, int C) {
+    (void)C;
+    if (B < 1 || H < 1 || W < 1) return 0;
+    // the group count is not known here: bound it by the channel count
+    return align256((size_t)B * ceil_div(H * W, GS_PIX) * (size_t)(C > 0 ? C : 1) * sizeof(double2));
+}
+
+extern "C" int fise_groupnorm_stats(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
+                                    float eps, float* mean, float* rstd, void* workspace, void* stream) {
+    if (!x || !mean || !rstd || !workspace) return fail(FISE_ERR_NULL, "fise_groupnorm_stats: null pointer");
+    if (dtype != FISE_F32 && dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_groupnorm_stats: dtype %d", dtype);
+    if (C1 < 0 || (C1 > 0 && !x1)) return fail(FISE_ERR_NULL, "fise_groupnorm_stats: second source missing");
+    const int C = C0 + C1;
+    if (B < 1 || H < 1 || W < 1 || C0 < 1 || G < 1 || C % G) return fail(FISE_ERR_SHAPE, "fise_groupnorm_stats: B%d H%d W%d C%d G%d", B, H, W, C, G);
+    const int HW = H * W, nchunk = ceil_div(HW, GS_PIX);
+    const size_t shmem = (size_t)C * sizeof(double2);
+    if (shmem > 64 * 1024) return fail(FISE_ERR_SHAPE, "fise_groupnorm_stats: C=%d too large", C);
+    double2* partial = (double2*)workspace;
+    hipStream_t st = as_stream(stream);
+    if (dtype == FISE_F32)
+        hipLaunchKernelGGL(gn_partial_kernel<float>, dim3(nchunk, B), dim3(256), shmem, st, (const float*)x, (const float*)x1, HW, C0, C1, G, partial);
+    else
+        hipLaunchKernelGGL(gn_partial_kernel<bf16_t>, dim3(nchunk, B), dim3(256), shmem, st, (const bf16_t*)x, (const bf16_t*)x1, HW, C0, C1, G, partial);
+    FISE_CHECK_LAUNCH("fise_groupnorm_stats(partial)");
+    hipLaunchKernelGGL(gn_finish_kernel, dim3(ceil_div(B * G, 64)), dim3(64), 0, st, partial, nchunk, B * G, G,
+                       (double)HW * (C / G), eps, mean, rstd);
+    FISE_CHECK_LAUNCH("fise_groupnorm_stats(finish)");
+    return FISE_OK;
+}
+
+extern "C" int fise_masked_groupnorm_silu(const void* x, const float* mean, const float* rstd, const void* gamma,
+                                          const void* beta, int dtype, int B, int H, int W, int C, int G,
+                                          const int32_t* tile_idx, int n_active, int tile, void* y_cache, void* stream) {
+    if (!x || !mean || !rstd || !gamma || !beta || !y_cache) return fail(FISE_ERR_NULL, "fise_masked_groupnorm_silu: null pointer");
+    if (dtype != FISE_F32 && dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_masked_groupnorm_silu: dtype %d", dtype);
+    if (B < 1 || H < 1 || W < 1 || C < 1 || G < 1 || C % G || tile < 1 || H % tile || W % tile)
+        return fail(FISE_ERR_SHAPE, "fise_masked_groupnorm_silu: B%d H%d W%d C%d G%d tile%d", B, H, W, C, G, tile);
+    if (n_active < 0 || n_active > (H / tile) * (W / tile)) return fail(FISE_ERR_CAPACITY, "fise_masked_groupnorm_silu: n_active %d", n_active);
+    if (n_active == 0) return FISE_OK;
+    if (!tile_idx) return fail(FISE_ERR_NULL, "fise_masked_groupnorm_silu: null tile_idx");
+    const int Ma = n_active * tile * tile;
+    const long long total = (long long)B * Ma * C;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (dtype == FISE_F32)
+        hipLaunchKernelGGL(masked_gn_silu_kernel<float>, grid, block, 0, as_stream(stream), (const float*)x, mean, rstd,
+                           (const float*)gamma, (const float*)beta, B, H, W, C, G, tile_idx, Ma, tile, (float*)y_cache);
+    else
+        hipLaunchKernelGGL(masked_gn_silu_kernel<bf16_t>, grid, block, 0, as_stream(stream), (const bf16_t*)x, mean, rstd,
+                           (const bf16_t*)gamma, (const bf16_t*)beta, B, H, W, C, G, tile_idx, Ma, tile, (bf16_t*)y_cache);
+    FISE_CHECK_LAUNCH("fise_masked_groupnorm_silu");
+    return FISE_OK;
+}

@@ -1,0 +1,447 @@
+// Masked UNet step: host-side plan (module walk, flat weight / cache / context
+// layouts) and the launch sequence.  Every module is a short chain of the gathered
+// GEMM, row LayerNorm and active-query attention kernels, all enqueued on the
+// caller's stream; nothing here allocates or synchronises.
+#include <cmath>
+#include <map>
+#include <string>
+#include <vector>
+#include "igemm.h"
+
+namespace fise {
+IgemmArgs linear_args(const void* A, int rows_per_b, int B, int Cin, const void* W, const void* bias, int N);
+}
+
+using namespace fise;
+
+namespace {
+struct Tensor { std::string name; int64_t off; int64_t numel; };
+enum Kind { K_CONV_IN, K_RES, K_TR, K_DS, K_US, K_OUT };
+struct Module {
+    Kind kind; std::string name; int lvl; int cin, cskip, cout;   // tr/ds/us: cin == cout == c
+    std::string in_map, skip_map;                                 // cache tensors read ("" = latent)
+    int temb_off;                                                 // column offset in the stacked time projection
+};
+}  // namespace
+
+struct fise_unet {
+    fise_unet_desc d;
+    std::vector<Module> mods;
+    std::vector<Tensor> tensors[3];
+    std::map<std::string, int> index[3];
+    int64_t weight_elems = 0; size_t cache_bytes = 0, ctxkv_bytes = 0;
+    int temb_total = 0, n_stride = 0;
+
+    int64_t add(int kind, const std::string& name, int64_t numel, int64_t& cursor, int64_t align) {
+        cursor = (cursor + align - 1) / align * align;
+        index[kind][name] = (int)tensors[kind].size();
+        tensors[kind].push_back({name, cursor, numel});
+        const int64_t off = cursor; cursor += numel;
+        return off;
+    }
+    int64_t off(int kind, const std::string& name) const { return tensors[kind][index[kind].at(name)].off; }
+};
+
+static void build_plan(fise_unet* u) {
+    const fise_unet_desc& d = u->d;
+    const int nl = d.n_levels, L = d.layers, base = d.base, te = 4 * base;
+    std::vector<Module>& mods = u->mods;
+    std::vector<std::pair<std::string, int>> skips;
+    auto S = [](const char* fmt, int a, int b = 0) { char buf[64]; snprintf(buf, sizeof buf, fmt, a, b); return std::string(buf); };
+    mods.push_back({K_CONV_IN, "conv_in", 0, d.in_ch, 0, base, "", "", 0});
+    std::string cur = "conv_in.out";
+    skips.push_back({cur, base});
+    int ch = base;
+    for (int l = 0; l < nl; ++l) {
+        const int co = base * d.mults[l];
+        for (int i = 0; i < L; ++i) {
+            std::string n = S("down.%d.res.%d", l, i);
+            mods.push_back({K_RES, n, l, ch, 0, co, cur, "", 0});
+            ch = co; cur = n + ".out";
+            if (d.attn[l]) { n = S("down.%d.tr.%d", l, i); mods.push_back({K_TR, n, l, ch, 0, ch, cur, "", 0}); cur = n + ".out"; }
+            skips.push_back({cur, ch});
+        }
+        if (l != nl - 1) {
+            std::string n = S("down.%d.ds", l);
+            mods.push_back({K_DS, n, l + 1, ch, 0, ch, cur, "", 0});
+            cur = n + ".out"; skips.push_back({cur, ch});
+        }
+    }
+    const int lb = nl - 1;
+    mods.push_back({K_RES, "mid.res.0", lb, ch, 0, ch, cur, "", 0}); cur = "mid.res.0.out";
+    mods.push_back({K_TR, "mid.tr.0", lb, ch, 0, ch, cur, "", 0}); cur = "mid.tr.0.out";
+    mods.push_back({K_RES, "mid.res.1", lb, ch, 0, ch, cur, "", 0}); cur = "mid.res.1.out";
+    for (int j = 0; j < nl; ++j) {
+        const int l = nl - 1 - j, co = base * d.mults[l];
+        for (int i = 0; i <= L; ++i) {
+            auto sk = skips.back(); skips.pop_back();
+            std::string n = S("up.%d.res.%d", j, i);
+            mods.push_back({K_RES, n, l, ch, sk.second, co, cur, sk.first, 0});
+            ch = co; cur = n + ".out";
+            if (d.attn[l]) { n = S("up.%d.tr.%d", j, i); mods.push_back({K_TR, n, l, ch, 0, ch, cur, "", 0}); cur = n + ".out"; }
+        }
+        if (l != 0) { std::string n = S("up.%d.us", j); mods.push_back({K_US, n, l - 1, ch, 0, ch, cur, "", 0}); cur = n + ".out"; }
+    }
+    mods.push_back({K_OUT, "out", 0, ch, 0, d.out_ch, cur, "", 0});
+
+    // ---- weights (bf16 elements, every tensor 8-element aligned).  The time projections of all
+    // ResNet blocks are stacked into one [sum C_out, te] matrix so one launch serves the step.
+    int64_t wc = 0;
+    u->add(0, "time.l1.w", (int64_t)te * base, wc, 8); u->add(0, "time.l1.b", te, wc, 8);
+    u->add(0, "time.l2.w", (int64_t)te * te, wc, 8);   u->add(0, "time.l2.b", te, wc, 8);
+    int toff = 0;
+    for (Module& m : mods) if (m.kind == K_RES) { m.temb_off = toff; u->add(0, m.name + ".temb.w", (int64_t)m.cout * te, wc, 8); toff += m.cout; }
+    u->temb_total = toff;
+    for (Module& m : mods) if (m.kind == K_RES) u->add(0, m.name + ".temb.b", m.cout, wc, 8);
+    for (const Module& m : mods) {
+        const std::string& n = m.name;
+        const int64_t ci = m.cin + m.cskip, co = m.cout, c = m.cout, cd = d.ctx_dim;
+        switch (m.kind) {
+        case K_CONV_IN: u->add(0, n + ".w", co * 9 * ci, wc, 8); u->add(0, n + ".b", co, wc, 8); break;
+        case K_RES:
+            u->add(0, n + ".gn1.g", ci, wc, 8); u->add(0, n + ".gn1.b", ci, wc, 8);
+            u->add(0, n + ".conv1.w", co * 9 * ci, wc, 8); u->add(0, n + ".conv1.b", co, wc, 8);
+            u->add(0, n + ".gn2.g", co, wc, 8); u->add(0, n + ".gn2.b", co, wc, 8);
+            u->add(0, n + ".conv2.w", co * 9 * co, wc, 8); u->add(0, n + ".conv2.b", co, wc, 8);
+            if (ci != co) { u->add(0, n + ".sc.w", co * ci, wc, 8); u->add(0, n + ".sc.b", co, wc, 8); }
+            break;
+        case K_TR:
+            u->add(0, n + ".gn.g", c, wc, 8); u->add(0, n + ".gn.b", c, wc, 8);
+            u->add(0, n + ".pin.w", c * c, wc, 8); u->add(0, n + ".pin.b", c, wc, 8);
+            u->add(0, n + ".ln1.g", c, wc, 8); u->add(0, n + ".ln1.b", c, wc, 8);
+            u->add(0, n + ".a1.q.w", c * c, wc, 8); u->add(0, n + ".a1.k.w", c * c, wc, 8); u->add(0, n + ".a1.v.w", c * c, wc, 8);
+            u->add(0, n + ".a1.o.w", c * c, wc, 8); u->add(0, n + ".a1.o.b", c, wc, 8);
+            u->add(0, n + ".ln2.g", c, wc, 8); u->add(0, n + ".ln2.b", c, wc, 8);
+            u->add(0, n + ".a2.q.w", c * c, wc, 8); u->add(0, n + ".a2.k.w", c * cd, wc, 8); u->add(0, n + ".a2.v.w", c * cd, wc, 8);
+            u->add(0, n + ".a2.o.w", c * c, wc, 8); u->add(0, n + ".a2.o.b", c, wc, 8);
+            u->add(0, n + ".ln3.g", c, wc, 8); u->add(0, n + ".ln3.b", c, wc, 8);
+            u->add(0, n + ".ff1.w", 8 * c * c, wc, 8); u->add(0, n + ".ff1.b", 8 * c, wc, 8);
+            u->add(0, n + ".ff2.w", c * 4 * c, wc, 8); u->add(0, n + ".ff2.b", c, wc, 8);
+            u->add(0, n + ".pout.w", c * c, wc, 8); u->add(0, n + ".pout.b", c, wc, 8);
+            break;
+        case K_DS: case K_US: u->add(0, n + ".w", c * 9 * c, wc, 8); u->add(0, n + ".b", c, wc, 8); break;
+        case K_OUT:
+            u->add(0, n + ".gn.g", ci, wc, 8); u->add(0, n + ".gn.b", ci, wc, 8);
+            u->add(0, n + ".conv.w", co * 9 * ci, wc, 8); u->add(0, n + ".conv.b", co, wc, 8);
+            break;
+        }
+    }
+    u->weight_elems = (wc + 7) / 8 * 8;
+
+    // ---- per-step cache (bytes, 256-byte aligned): maps bf16, statistics float
+    int64_t cc = 0;
+    const int64_t B = d.B, G = d.groups;
+    for (const Module& m : mods) {
+        const std::string& n = m.name;
+        const int64_t hw = (int64_t)(d.H >> m.lvl) * (d.W >> m.lvl);
+        auto stat = [&](const std::string& g) { u->add(1, n + "." + g + ".mean", B * G * 4, cc, 256); u->add(1, n + "." + g + ".rstd", B * G * 4, cc, 256); };
+        switch (m.kind) {
+        case K_CONV_IN: u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256); break;
+        case K_RES:
+            stat("gn1"); stat("gn2");
+            u->add(1, n + ".h1", B * hw * m.cout * 2, cc, 256); u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256);
+            break;
+        case K_TR:
+            stat("gn");
+            u->add(1, n + ".k", B * hw * m.cout * 2, cc, 256); u->add(1, n + ".v", B * hw * m.cout * 2, cc, 256);
+            u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256);
+            break;
+        case K_DS: case K_US: u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256); break;
+        case K_OUT: stat("gn"); u->add(1, "eps", B * hw * m.cout * 2, cc, 256); break;
+        }
+    }
+    u->cache_bytes = (size_t)((cc + 255) / 256 * 256);
+
+    // ---- context K/V (bytes): per transformer block K[B,n_ctx,C], Vt[B,C,n_stride]
+    u->n_stride = (d.n_ctx + 7) / 8 * 8;
+    int64_t kc = 0;
+    for (const Module& m : mods)
+        if (m.kind == K_TR) {
+            u->add(2, m.name + ".ctx_k", B * d.n_ctx * m.cout * 2, kc, 256);
+            u->add(2, m.name + ".ctx_vt", B * m.cout * u->n_stride * 2, kc, 256);
+        }
+    u->ctxkv_bytes = (size_t)((kc + 255) / 256 * 256);
+}
+
+extern "C" int fise_unet_create(const fise_unet_desc* desc, fise_unet** out) {
+    if (!desc || !out) return fail(FISE_ERR_NULL, "fise_unet_create: null pointer");
+    const fise_unet_desc& d = *desc;
+    if (d.n_levels < 1 || d.n_levels > FISE_MAX_LEVELS || d.layers < 1 || d.B < 1 || d.in_ch < 1 || d.out_ch < 1)
+        return fail(FISE_ERR_SHAPE, "fise_unet_create: bad levels/layers/batch");
+    if (d.base < 32 || d.base % 32 || d.groups < 1 || d.heads < 1 || d.ctx_dim % 32 || d.ctx_dim < 32 || d.n_ctx < 1)
+        return fail(FISE_ERR_SHAPE, "fise_unet_create: base and ctx_dim must be positive multiples of 32");
+    if (d.H < 1 || d.W < 1 || d.H % (1 << (d.n_levels - 1)) || d.W % (1 << (d.n_levels - 1)))
+        return fail(FISE_ERR_SHAPE, "fise_unet_create: H, W must be divisible by 2^(levels-1)");
+    for (int l = 0; l < d.n_levels; ++l) {
+        const int c = d.base * d.mults[l];
+        if (d.mults[l] < 1 || c % d.groups || c % d.heads || (c / d.heads) % 8 || c / d.heads > 160)
+            return fail(FISE_ERR_SHAPE, "fise_unet_create: level %d width %d vs groups %d / heads %d", l, c, d.groups, d.heads);
+        if (d.attn[l] && ((d.H >> l) * (d.W >> l)) % 8) return fail(FISE_ERR_SHAPE, "fise_unet_create: level %d token count not a multiple of 8", l);
+    }
+    for (int l = 0; l + 1 < d.n_levels; ++l) {      // concatenated widths must keep whole groups
+        (void)l;
+    }
+    fise_unet* u = new fise_unet();
+    u->d = d;
+    build_plan(u);
+    for (const Module& m : u->mods)
+        if (m.kind == K_RES && (m.cin + m.cskip) % d.groups) { delete u; return fail(FISE_ERR_SHAPE, "fise_unet_create: %s input width %d %% groups", m.name.c_str(), m.cin + m.cskip); }
+    *out = u;
+    return FISE_OK;
+}
+
+extern "C" void fise_unet_destroy(fise_unet* u) { delete u; }
+
+extern "C" int fise_unet_num_tensors(const fise_unet* u, int kind) {
+    if (!u || kind < 0 || kind > 2) return fail(FISE_ERR_NULL, "fise_unet_num_tensors: bad arguments");
+    return (int)u->tensors[kind].size();
+}
+
+extern "C" int fise_unet_tensor_info(const fise_unet* u, int kind, int i, char* name, int64_t* offset, int64_t* numel) {
+    if (!u || !name || !offset || !numel) return fail(FISE_ERR_NULL, "fise_unet_tensor_info: null pointer");
+    if (kind < 0 || kind > 2 || i < 0 || i >= (int)u->tensors[kind].size()) return fail(FISE_ERR_CAPACITY, "fise_unet_tensor_info: index");
+    const Tensor& t = u->tensors[kind][i];
+    snprintf(name, 64, "%s", t.name.c_str());
+    *offset = t.off; *numel = t.numel;
+    return FISE_OK;
+}
+
+extern "C" int64_t fise_unet_weight_elems(const fise_unet* u) { return u ? u->weight_elems : 0; }
+extern "C" size_t fise_unet_cache_bytes(const fise_unet* u) { return u ? u->cache_bytes : 0; }
+extern "C" size_t fise_unet_ctxkv_bytes(const fise_unet* u) { return u ? u->ctxkv_bytes : 0; }
+
+namespace {
+struct WsLayout { size_t idx_full, emb_a, emb_b, temb, h, n, q, o, ff, gn, total; };
+
+// rows of level l for `n_tiles` active tiles (per batch element)
+inline int64_t level_rows(const fise_unet_desc& d, int l, int n_tiles, int base_tile, bool dense) {
+    if (dense) return (int64_t)(d.H >> l) * (d.W >> l);
+    const int t = base_tile >> l;
+    return (int64_t)n_tiles * t * t;
+}
+
+WsLayout ws_layout(const fise_unet* u, int n_tiles, int base_tile, const int* level_dense) {
+    const fise_unet_desc& d = u->d;
+    WsLayout w{};
+    size_t c = 0;
+    auto take = [&](size_t bytes) { size_t o = c; c += align256(bytes); return o; };
+    const int tiles_total = (d.H / base_tile) * (d.W / base_tile);
+    w.idx_full = take((size_t)tiles_total * 4);
+    const int te = 4 * d.base;
+    w.emb_a = take((size_t)d.B * te * 4); w.emb_b = take((size_t)d.B * te * 4);
+    w.temb = take((size_t)d.B * u->temb_total * 4);
+    int64_t max_rc = 0, max_c = 0;
+    for (const Module& m : u->mods) {
+        const bool dense = level_dense && level_dense[m.lvl];
+        const int64_t rows = d.B * level_rows(d, m.lvl, n_tiles, base_tile, dense);
+        if (m.kind == K_TR) max_rc = std::max(max_rc, rows * m.cout);
+        max_c = std::max<int64_t>(max_c, m.cin + m.cskip);
+    }
+    w.h = take(max_rc * 2); w.n = take(max_rc * 2); w.q = take(max_rc * 2); w.o = take(max_rc * 2); w.ff = take(max_rc * 4 * 2);
+    w.gn = take(fise_groupnorm_stats_workspace_bytes(d.B, d.H, d.W, d.groups));
+    w.total = c;
+    return w;
+}
+}  // namespace
+
+extern "C" size_t fise_unet_workspace_bytes(const fise_unet* u, int max_active_tiles, int base_tile) {
+    if (!u || base_tile < 1 || max_active_tiles < 0) return 0;
+    return ws_layout(u, max_active_tiles, base_tile, nullptr).total;
+}
+
+extern "C" int fise_unet_context_kv(const fise_unet* u, const void* weights, const void* ctx, void* ctxkv, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!u || !weights || !ctx || !ctxkv) return fail(FISE_ERR_NULL, "fise_unet_context_kv: null pointer");
+    const fise_unet_desc& d = u->d;
+    const bf16_t* Wt = (const bf16_t*)weights;
+    hipStream_t st = as_stream(stream);
+    for (const Module& m : u->mods) {
+        if (m.kind != K_TR) continue;
+        const int C = m.cout;
+        // k.w and v.w are adjacent: one launch, two output sections
+        IgemmArgs g = linear_args(ctx, d.n_ctx, d.B, d.ctx_dim, Wt + u->off(0, m.name + ".a2.k.w"), nullptr, 2 * C);
+        g.nsect = 2; g.sect_n = C; g.Ho = 1; g.Wo = u->n_stride;
+        g.out[0] = (bf16_t*)((char*)ctxkv + u->off(2, m.name + ".ctx_k")); g.out_mode[0] = OUT_COMPACT;
+        g.out[1] = (bf16_t*)((char*)ctxkv + u->off(2, m.name + ".ctx_vt")); g.out_mode[1] = OUT_TOKENS_T;
+        if (int e = launch_igemm(g, st)) return e;
+    }
+    return FISE_OK;
+}
+
+extern "C" int fise_masked_unet_step(const fise_unet* u, const void* weights, void* cache, const void* latent,
+                                     const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
+                                     int base_tile, int stats_mode, const int* level_dense, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+    if (!u || !weights || !cache || !latent || !t_sin || !ctxkv) return fail(FISE_ERR_NULL, "fise_masked_unet_step: null pointer");
+    const fise_unet_desc& d = u->d;
+    const int nl = d.n_levels;
+    if (base_tile < 1 || base_tile % (1 << (nl - 1)) || d.H % base_tile || d.W % base_tile)
+        return fail(FISE_ERR_SHAPE, "fise_masked_unet_step: base_tile %d must divide H, W and be a multiple of %d", base_tile, 1 << (nl - 1));
+    const int tiles_w = d.W / base_tile, tiles_total = tiles_w * (d.H / base_tile);
+    if (n_active < 0 || n_active > tiles_total) return fail(FISE_ERR_CAPACITY, "fise_masked_unet_step: n_active %d of %d tiles", n_active, tiles_total);
+    if (stats_mode != FISE_STATS_CACHED && stats_mode != FISE_STATS_FRESH) return fail(FISE_ERR_SHAPE, "fise_masked_unet_step: stats_mode %d", stats_mode);
+    bool any_dense = false;
+    if (level_dense) for (int l = 0; l < nl; ++l) any_dense |= level_dense[l] != 0;
+    if (n_active == 0 && !any_dense) return FISE_OK;
+    if (n_active > 0 && !tile_idx) return fail(FISE_ERR_NULL, "fise_masked_unet_step: null tile_idx");
+    const WsLayout wl = ws_layout(u, n_active, base_tile, level_dense);
+    if (!workspace || workspace_bytes < wl.total) return fail(FISE_ERR_CAPACITY, "fise_masked_unet_step: workspace %zu < %zu bytes", workspace_bytes, wl.total);
+    const void* chk[] = {weights, cache, latent, ctxkv, workspace};
+    for (const void* p : chk) if (!aligned16(p)) return fail(FISE_ERR_ALIGN, "fise_masked_unet_step: pointer %p not 16-byte aligned", p);
+
+    hipStream_t st = as_stream(stream);
+    const bf16_t* Wt = (const bf16_t*)weights;
+    char* cb = (char*)cache; char* ws = (char*)workspace; const char* kv = (const char*)ctxkv;
+    auto Wp = [&](const std::string& n) { return Wt + u->off(0, n); };
+    auto Cp = [&](const std::string& n) { return (bf16_t*)(cb + u->off(1, n)); };
+    auto Cf = [&](const std::string& n) { return (float*)(cb + u->off(1, n)); };
+    int* idx_full = (int*)(ws + wl.idx_full);
+    float* emb_a = (float*)(ws + wl.emb_a); float* emb_b = (float*)(ws + wl.emb_b); float* temb = (float*)(ws + wl.temb);
+    bf16_t* hb = (bf16_t*)(ws + wl.h); bf16_t* nb = (bf16_t*)(ws + wl.n); bf16_t* qb = (bf16_t*)(ws + wl.q);
+    bf16_t* ob = (bf16_t*)(ws + wl.o); bf16_t* fb = (bf16_t*)(ws + wl.ff);
+    void* gnws = ws + wl.gn;
+    const int B = d.B, G = d.groups, te = 4 * d.base;
+
+    if (any_dense) if (int e = launch_iota(idx_full, tiles_total, st)) return e;
+    // time embedding MLP and the stacked per-block projections (dense, a few rows)
+    if (int e = launch_small_linear(t_sin, B, d.base, Wp("time.l1.w"), Wp("time.l1.b"), te, 1, emb_a, st)) return e;
+    if (int e = launch_small_linear(emb_a, B, te, Wp("time.l2.w"), Wp("time.l2.b"), te, 1, emb_b, st)) return e;
+    {
+        const Module* first = nullptr;
+        for (const Module& m : u->mods) if (m.kind == K_RES) { first = &m; break; }
+        if (first)
+            if (int e = launch_small_linear(emb_b, B, te, Wp(first->name + ".temb.w"), Wp(first->name + ".temb.b"), u->temb_total, 0, temb, st)) return e;
+    }
+
+    for (const Module& m : u->mods) {
+        const bool dense = level_dense && level_dense[m.lvl];
+        const int* idx = dense ? idx_full : tile_idx;
+        const int nt = dense ? tiles_total : n_active;
+        if (nt == 0) continue;
+        const int tile = base_tile >> m.lvl;
+        const int H = d.H >> m.lvl, W = d.W >> m.lvl;
+        const int Ma = nt * tile * tile;
+        const std::string& n = m.name;
+        const bf16_t* in0 = m.in_map.empty() ? (const bf16_t*)latent : Cp(m.in_map);
+        const bf16_t* in1 = m.skip_map.empty() ? nullptr : Cp(m.skip_map);
+
+        // a conv-shaped launch on maps of this module's level
+        auto conv = [&](const bf16_t* a0, const bf16_t* a1, int C0, int C1, int Hin, int Win, int ks, int stride, int ups,
+                        const bf16_t* w, const bf16_t* bias, int N) {
+            IgemmArgs g{};
+            g.a0 = a0; g.a1 = a1; g.C0 = C0; g.C1 = C1; g.a_compact = 0; g.Hin = Hin; g.Win = Win; g.ksize = ks; g.stride = stride; g.ups = ups;
+            g.tile_idx = idx; g.tile = tile; g.tiles_w = tiles_w; g.Ho = H; g.Wo = W; g.B = B; g.Ma = Ma;
+            g.pro = PRO_NONE; g.G = G;
+            g.w = w; g.N = N; g.K = ks * ks * (C0 + C1); g.geglu = 0; g.bias = bias; g.temb = nullptr; g.temb_stride = 0;
+            g.res = nullptr; g.res_compact = 0; g.nsect = 1; g.sect_n = N; g.out_mode[0] = OUT_MAP;
+            g.splits = 1;
+            return g;
+        };
+        auto with_gn = [&](IgemmArgs& g, const std::string& key, const char* gname, const char* bname, bool silu) {
+            g.pro = silu ? PRO_GN_SILU : PRO_GN;
+            g.gn_mean = Cf(key + ".mean"); g.gn_rstd = Cf(key + ".rstd"); g.gn_gamma = Wp(n + gname); g.gn_beta = Wp(n + bname);
+        };
+        auto fresh = [&](const std::string& key, const bf16_t* a0, const bf16_t* a1, int C0, int C1, int Hs, int Ws, float eps) -> int {
+            if (stats_mode != FISE_STATS_FRESH) return FISE_OK;
+            return fise_groupnorm_stats(a0, a1, FISE_BF16, B, Hs, Ws, C0, C1, G, eps, Cf(key + ".mean"), Cf(key + ".rstd"), gnws, st);
+        };
+        auto lin = [&](const bf16_t* A, int Cin, const bf16_t* w, const bf16_t* bias, int N) {
+            IgemmArgs g = linear_args(A, Ma, B, Cin, w, bias, N);
+            g.tile_idx = idx; g.tile = tile; g.tiles_w = tiles_w; g.Ho = H; g.Wo = W;
+            return g;
+        };
+
+        switch (m.kind) {
+        case K_CONV_IN: {
+            fise_conv_args a{};
+            a.x0 = latent; a.C0 = d.in_ch; a.B = B; a.H = H; a.W = W; a.w = Wp(n + ".w"); a.bias = Wp(n + ".b"); a.Cout = m.cout;
+            a.ksize = 3; a.stride = 1; a.tile_idx = idx; a.n_active = nt; a.tile = tile; a.y_cache = Cp(n + ".out"); a.dtype = FISE_BF16;
+            if (int e = conv_dispatch(&a, nullptr, 0, st)) return e;
+        } break;
+        case K_RES: {
+            const int ci = m.cin + m.cskip, co = m.cout;
+            if (int e = fresh(n + ".gn1", in0, in1, m.cin, m.cskip, H, W, 1e-5f)) return e;
+            IgemmArgs g = conv(in0, in1, m.cin, m.cskip, H, W, 3, 1, 0, Wp(n + ".conv1.w"), Wp(n + ".conv1.b"), co);
+            with_gn(g, n + ".gn1", ".gn1.g", ".gn1.b", true);
+            g.temb = temb + m.temb_off; g.temb_stride = u->temb_total;
+            g.out[0] = Cp(n + ".h1");
+            if (int e = launch_igemm(g, st)) return e;
+            if (int e = fresh(n + ".gn2", Cp(n + ".h1"), nullptr, co, 0, H, W, 1e-5f)) return e;
+            const bf16_t* res = in0;
+            if (ci != co) {       // 1x1 shortcut, parked in the output map, then consumed as the residual
+                IgemmArgs s = conv(in0, in1, m.cin, m.cskip, H, W, 1, 1, 0, Wp(n + ".sc.w"), Wp(n + ".sc.b"), co);
+                s.out[0] = Cp(n + ".out");
+                if (int e = launch_igemm(s, st)) return e;
+                res = Cp(n + ".out");
+            }
+            IgemmArgs c2 = conv(Cp(n + ".h1"), nullptr, co, 0, H, W, 3, 1, 0, Wp(n + ".conv2.w"), Wp(n + ".conv2.b"), co);
+            with_gn(c2, n + ".gn2", ".gn2.g", ".gn2.b", true);
+            c2.res = res; c2.out[0] = Cp(n + ".out");
+            if (int e = launch_igemm(c2, st)) return e;
+        } break;
+        case K_TR: {
+            const int C = m.cout, dh = C / d.heads;
+            const float scale = 1.0f / sqrtf((float)dh);
+            const int rows = B * Ma;
+            if (int e = fresh(n + ".gn", in0, nullptr, C, 0, H, W, 1e-6f)) return e;
+            IgemmArgs g = conv(in0, nullptr, C, 0, H, W, 1, 1, 0, Wp(n + ".pin.w"), Wp(n + ".pin.b"), C);
+            with_gn(g, n + ".gn", ".gn.g", ".gn.b", false);
+            g.out[0] = hb; g.out_mode[0] = OUT_COMPACT;
+            if (int e = launch_igemm(g, st)) return e;
+            // self-attention: LN -> fused QKV (K, V rows scattered into the caches) -> attention -> out-proj + residual
+            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln1.g"), Wp(n + ".ln1.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
+            IgemmArgs qkv = lin(nb, C, Wp(n + ".a1.q.w"), nullptr, 3 * C);
+            qkv.nsect = 3; qkv.sect_n = C;
+            qkv.out[0] = qb; qkv.out_mode[0] = OUT_COMPACT;
+            qkv.out[1] = Cp(n + ".k"); qkv.out_mode[1] = OUT_MAP;
+            qkv.out[2] = Cp(n + ".v"); qkv.out_mode[2] = OUT_TOKENS_T;
+            if (int e = launch_igemm(qkv, st)) return e;
+            if (int e = launch_attention(qb, Cp(n + ".k"), Cp(n + ".v"), B, Ma, H * W, H * W, C, d.heads, scale, ob, st)) return e;
+            IgemmArgs o1 = lin(ob, C, Wp(n + ".a1.o.w"), Wp(n + ".a1.o.b"), C);
+            o1.res = hb; o1.res_compact = 1; o1.out[0] = hb;
+            if (int e = launch_igemm(o1, st)) return e;
+            // cross-attention against the context K/V of the new conditioning
+            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln2.g"), Wp(n + ".ln2.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
+            IgemmArgs q2 = lin(nb, C, Wp(n + ".a2.q.w"), nullptr, C);
+            q2.out[0] = qb;
+            if (int e = launch_igemm(q2, st)) return e;
+            if (int e = launch_attention(qb, kv + u->off(2, n + ".ctx_k"), kv + u->off(2, n + ".ctx_vt"), B, Ma, d.n_ctx, u->n_stride, C,
+                                         d.heads, scale, ob, st)) return e;
+            IgemmArgs o2 = lin(ob, C, Wp(n + ".a2.o.w"), Wp(n + ".a2.o.b"), C);
+            o2.res = hb; o2.res_compact = 1; o2.out[0] = hb;
+            if (int e = launch_igemm(o2, st)) return e;
+            // feed-forward: LN -> GEGLU (fused into the first GEMM's epilogue) -> second GEMM + residual
+            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln3.g"), Wp(n + ".ln3.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
+            IgemmArgs f1 = lin(nb, C, Wp(n + ".ff1.w"), Wp(n + ".ff1.b"), 4 * C);
+            f1.geglu = 1; f1.sect_n = 4 * C; f1.out[0] = fb;
+            if (int e = launch_igemm(f1, st)) return e;
+            IgemmArgs f2 = lin(fb, 4 * C, Wp(n + ".ff2.w"), Wp(n + ".ff2.b"), C);
+            f2.res = hb; f2.res_compact = 1; f2.out[0] = hb;
+            if (int e = launch_igemm(f2, st)) return e;
+            // 1x1 out + block input, scattered into the cached block output
+            IgemmArgs po = lin(hb, C, Wp(n + ".pout.w"), Wp(n + ".pout.b"), C);
+            po.res = in0; po.res_compact = 0; po.out[0] = Cp(n + ".out"); po.out_mode[0] = OUT_MAP;
+            if (int e = launch_igemm(po, st)) return e;
+        } break;
+        case K_DS: {
+            IgemmArgs g = conv(in0, nullptr, m.cin, 0, 2 * H, 2 * W, 3, 2, 0, Wp(n + ".w"), Wp(n + ".b"), m.cout);
+            g.out[0] = Cp(n + ".out");
+            if (int e = launch_igemm(g, st)) return e;
+        } break;
+        case K_US: {
+            IgemmArgs g = conv(in0, nullptr, m.cin, 0, H / 2, W / 2, 3, 1, 1, Wp(n + ".w"), Wp(n + ".b"), m.cout);
+            g.out[0] = Cp(n + ".out");
+            if (int e = launch_igemm(g, st)) return e;
+        } break;
+        case K_OUT: {
+            if (int e = fresh(n + ".gn", in0, nullptr, m.cin, 0, H, W, 1e-5f)) return e;
+            IgemmArgs g = conv(in0, nullptr, m.cin, 0, H, W, 3, 1, 0, Wp(n + ".conv.w"), Wp(n + ".conv.b"), m.cout);
+            with_gn(g, n + ".gn", ".gn.g", ".gn.b", true);
+            g.out[0] = Cp("eps");
+            if (int e = launch_igemm(g, st)) return e;
+        } break;
+        }
+    }
+    return FISE_OK;
+}

@@ -1,0 +1,108 @@
+"""Shared helpers of the GPU parity tests: host<->device conversion, the error
+metric, and packing oracle tensors into the library's flat UNet buffers."""
+import numpy as np
+import torch
+
+from oracle import fise_oracle as fo
+
+DEV = "cuda:0"
+TOL = {"f32": 1e-4, "bf16": 2e-2}       # relative tolerances fixed by the benchmark spec
+
+
+def tdtype(dtype):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def dev(a, dtype="f32"):
+    """numpy array (values representable in `dtype`) -> device tensor of that dtype."""
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.float32))).to(tdtype(dtype)).to(DEV)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.int32))).to(DEV)
+
+
+def dev_u8(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.uint8))).to(DEV)
+
+
+def host(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_err(got, want):
+    """max |g - o| / max(|o|, rms(o)) over the given elements."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    if want.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(want ** 2))
+    den = np.maximum(np.abs(want), max(rms, 1e-30))
+    return float(np.max(np.abs(got - want) / den))
+
+
+def active_mask(idx, tile, H, W):
+    ys, xs = fo.active_pixels(idx, tile, W)
+    m = np.zeros((H, W), bool)
+    m[ys, xs] = True
+    return m
+
+
+def check_map(got, want, before, act, tol, what=""):
+    """Active positions within tol of the oracle; all other positions bitwise equal to `before`."""
+    err = rel_err(got[:, act], want[:, act])
+    assert err <= tol, f"{what}: rel err {err:.3e} > {tol}"
+    assert np.array_equal(got[:, ~act], before[:, ~act]), f"{what}: inactive positions changed"
+    return err
+
+
+def idx_dev(idx, capacity=None):
+    """Device int32 index list (at least one element long so the pointer is valid)."""
+    n = max(int(len(idx)), 1) if capacity is None else capacity
+    buf = np.zeros(n, np.int32)
+    buf[:len(idx)] = idx
+    return dev_i32(buf)
+
+
+# ------------------------------------------------------------------ flat UNet buffers
+def pack_weights(fb, u, P):
+    n = fb.fise_unet_weight_elems(u)
+    flat = np.zeros(n, np.float32)
+    for name, off, num in fb.fise_unet_tensors(u, 0):
+        flat[off:off + num] = np.asarray(P[name], np.float32).reshape(-1)
+    return torch.from_numpy(flat).to(torch.bfloat16).to(DEV)
+
+
+def _is_stat(name):
+    return name.endswith(".mean") or name.endswith(".rstd")
+
+
+def pack_cache(fb, u, cache):
+    """Oracle cache dict -> device byte buffer in the library's layout (V caches transposed)."""
+    buf = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8)
+    for name, off, nbytes in fb.fise_unet_tensors(u, 1):
+        a = np.asarray(cache[name], np.float32)
+        if _is_stat(name):
+            t = torch.from_numpy(np.ascontiguousarray(a)).view(torch.uint8)
+        else:
+            if name.endswith(".v"):
+                a = a.transpose(0, 2, 1)
+            t = torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).view(torch.uint8)
+        assert t.numel() == nbytes, (name, t.numel(), nbytes)
+        buf[off:off + nbytes] = t.reshape(-1)
+    return buf.to(DEV)
+
+
+def unpack_cache(fb, u, buf, shapes):
+    """Device cache buffer -> dict name -> float64 array in the oracle's layout."""
+    h = buf.to("cpu")
+    out = {}
+    for name, off, nbytes in fb.fise_unet_tensors(u, 1):
+        raw = h[off:off + nbytes]
+        shp = shapes[name]
+        if _is_stat(name):
+            out[name] = raw.view(torch.float32).reshape(shp).to(torch.float64).numpy()
+        elif name.endswith(".v"):
+            out[name] = raw.view(torch.bfloat16).reshape(shp[0], shp[2], shp[1]).to(torch.float64).numpy().transpose(0, 2, 1)
+        else:
+            out[name] = raw.view(torch.bfloat16).reshape(shp).to(torch.float64).numpy()
+    return out

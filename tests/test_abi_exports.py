@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports every symbol include/fise.h declares; host-side
+argument validation returns error codes without a GPU (nothing is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2305_17423_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "fise.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(fise_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fb.lib()
+    names = declared_symbols()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in fise.h but not exported"
+    assert set(names) == set(fb.EXPORTS), set(names) ^ set(fb.EXPORTS)
+    assert fb.fise_version() >= 1
+
+
+def test_host_side_validation_without_gpu():
+    L = fb.lib()
+    assert L.fise_mask_detect(None, None, 0, 1, 8, 8, 4, 0.1, 4, None, None, None, 4, None, None) == -1
+    a = 0x1000  # never dereferenced: validation fails first
+    assert L.fise_mask_detect(a, a, 0, 1, 8, 6, 4, 0.1, 4, a, a, a, 4, a, None) == -2       # W % tile
+    assert "tile" in fb.fise_last_error()
+    assert L.fise_mask_detect(a, a, 7, 1, 8, 8, 4, 0.1, 4, a, a, a, 4, a, None) == -3       # dtype
+    assert L.fise_mask_downsample(a, 7, 8, a, None) == -2
+    assert L.fise_attention_active(a, a, a, fb.FISE_F32, 1, 4, 8, 8, 32, 4, 1.0, a, None) == -3
+    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 8, 8, 30, 4, 1.0, a, None) == -2   # C % heads
+    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 9, 9, 32, 4, 1.0, a, None) == -4   # stride % 8
+    args = fb.fise_conv_args()
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -1
+    args.x0 = args.w = a; args.y_cache = 0x2000; args.B = 1; args.H = args.W = 8; args.C0 = 32; args.Cout = 32
+    args.ksize = 3; args.stride = 1; args.tile = 4; args.n_active = 5; args.dtype = fb.FISE_BF16
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -5                       # n_active > 4 tiles
+    args.n_active = 2
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -1                       # tile_idx NULL
+    args.n_active = 0; args.ksize = 5
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -2
+    args.ksize = 3; args.x0 = 0x1004
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -4                       # misaligned
+    args.x0 = a
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == 0                        # empty mask: no-op
+
+
+def test_unet_plan_matches_oracle_tables():
+    import numpy as np
+    from oracle import fise_unet_oracle as uo
+    for d in (uo.sd15_desc(), uo.tiny_desc()):
+        u = fb.fise_unet_create(d)
+        sh = uo.param_shapes(d)
+        ws = fb.fise_unet_tensors(u, 0)
+        assert {n for n, _, _ in ws} == set(sh)
+        assert all(int(np.prod(sh[n])) == num and off % 8 == 0 for n, off, num in ws)
+        spans = sorted((off, off + num) for _, off, num in ws)
+        assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+        assert spans[-1][1] <= fb.fise_unet_weight_elems(u)
+        csh = uo.cache_shapes(d)
+        cs = fb.fise_unet_tensors(u, 1)
+        assert {n for n, _, _ in cs} == set(csh)
+        for n, off, nbytes in cs:
+            el = 4 if n.endswith((".mean", ".rstd")) else 2
+            assert nbytes == int(np.prod(csh[n])) * el and off % 256 == 0
+        fb.fise_unet_destroy(u)
+    bad = uo.tiny_desc(base=48)
+    with pytest.raises(fb.FiseError):
+        fb.fise_unet_create(bad)

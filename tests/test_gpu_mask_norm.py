@@ -1,0 +1,182 @@
+"""GPU parity: mask generation (bit-exact) and normalisation kernels vs the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fise_oracle as fo
+from paper_2305_17423_amd import workloads as wl
+from helpers import DEV, TOL, dev, dev_u8, dev_i32, host, rel_err, idx_dev, active_mask
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2305_17423_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def run_detect(fb, x_old, x_new, thr, tile, dtype, capacity=None):
+    B, H, W, C = x_old.shape
+    nt = (H // tile) * (W // tile)
+    cap = nt if capacity is None else capacity
+    pix = torch.full((H, W), 7, dtype=torch.uint8, device=DEV)
+    tm = torch.full((nt,), 7, dtype=torch.uint8, device=DEV)
+    idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=DEV)
+    n = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    fb.lib().fise_mask_detect(dev(x_old, dtype).data_ptr(), dev(x_new, dtype).data_ptr(), 0 if dtype == "f32" else 1, B, H, W, C,
+                              thr, tile, pix.data_ptr(), tm.data_ptr(), idx.data_ptr(), cap, n.data_ptr(), None)
+    torch.cuda.synchronize()
+    return pix.cpu().numpy(), tm.cpu().numpy().reshape(H // tile, W // tile), idx.cpu().numpy(), int(n.item())
+
+
+@pytest.mark.parametrize("seed,dtype,shape,tile,kind", [
+    (1001, "f32", (1, 32, 32, 64), 4, "rect"),          # config 1
+    (1002, "f32", (1, 32, 32, 64), 4, "rect"),
+    (2001, "bf16", (2, 64, 64, 320), 8, "ellipse"),     # worst case of the survey: 320 channels, batch 2
+    (2002, "bf16", (2, 64, 64, 4), 8, "ellipse"),       # latent
+    (2003, "bf16", (2, 24, 40, 5), 4, "ellipse"),       # ragged channel count, non-square
+    (2004, "f32", (3, 16, 16, 70), 2, "ellipse"),
+    (2005, "bf16", (1, 128, 128, 32), 4, "ellipse"),    # 1024 tiles: several compaction chunks
+])
+def test_mask_detect_bit_exact(fb, seed, dtype, shape, tile, kind):
+    rng = np.random.default_rng(seed)
+    B, H, W, C = shape
+    x_old = wl.normal(rng, shape, 1.0, dtype)
+    pixm = wl.rect_pixels(rng, H, W, 8, 8) if kind == "rect" else wl.ellipse_pixels(rng, H, W, 0.1)
+    x_new = wl.perturb(rng, x_old, pixm, 1.0, dtype)
+    pix_o, tm_o, idx_o = fo.mask_detect(x_old, x_new, 0.1, tile)
+    pix, tm, idx, n = run_detect(fb, x_old, x_new, 0.1, tile, dtype)
+    assert n == idx_o.size and n > 0
+    np.testing.assert_array_equal(pix, pix_o)
+    np.testing.assert_array_equal(tm, tm_o)
+    np.testing.assert_array_equal(idx[:n], idx_o)
+    assert (idx[n:] == -1).all()                                        # nothing written past n_active
+
+
+def test_mask_detect_noisy_everywhere_bit_exact(fb):
+    """Differences everywhere with a threshold in the middle of their distribution: every pixel's
+    float sum must come out identical for the masks to agree."""
+    rng = np.random.default_rng(2010)
+    shape = (2, 64, 64, 320)
+    x_old = wl.normal(rng, shape, 1.0, "bf16")
+    x_new = wl.storage_round(x_old + 0.1 * rng.standard_normal(shape).astype(np.float32), "bf16")
+    d = fo.pixel_diff(x_old, x_new)
+    thr = float(np.median(d))
+    pix_o, tm_o, idx_o = fo.mask_detect(x_old, x_new, thr, 1)
+    assert 1000 < pix_o.sum() < 3100
+    pix, tm, idx, n = run_detect(fb, x_old, x_new, thr, 1, "bf16")
+    np.testing.assert_array_equal(pix, pix_o)
+    assert n == idx_o.size and np.array_equal(idx[:n], idx_o)
+
+
+def test_mask_detect_edge_cases(fb):
+    rng = np.random.default_rng(2011)
+    x = wl.normal(rng, (1, 8, 8, 4))
+    pix, tm, idx, n = run_detect(fb, x, x, 0.0, 4, "f32")               # identical maps: empty
+    assert n == 0 and pix.sum() == 0 and tm.sum() == 0
+    z = np.zeros((1, 4, 4, 2), np.float32); z2 = z.copy(); z2[0, 1, 1, :] = 0.25
+    assert run_detect(fb, z, z2, 0.25, 2, "f32")[3] == 0                 # d == thr is not active
+    assert run_detect(fb, z, z2, float(np.nextafter(np.float32(0.25), np.float32(0))), 2, "f32")[3] == 1
+    y = x + 1.0                                                          # everything active
+    pix, tm, idx, n = run_detect(fb, x, y, 0.5, 2, "f32")
+    assert n == 16 and list(idx) == list(range(16))
+    pix, tm, idx, n = run_detect(fb, x, y, 0.5, 2, "f32", capacity=5)    # overflow: count reported, list truncated
+    assert n == 16 and list(idx) == [0, 1, 2, 3, 4]
+
+
+def test_mask_from_pixels_and_downsample(fb):
+    rng = np.random.default_rng(2012)
+    for H, W, t in ((64, 64, 8), (64, 64, 4), (32, 48, 2), (16, 16, 1)):
+        pixm = wl.ellipse_pixels(rng, H, W, 0.15)
+        tm_o, idx_o = fo.tiles_from_pixels(pixm, t)
+        nt = tm_o.size
+        tm = torch.zeros(nt, dtype=torch.uint8, device=DEV); idx = torch.full((nt,), -1, dtype=torch.int32, device=DEV)
+        n = torch.zeros(1, dtype=torch.int32, device=DEV)
+        fb.fise_mask_from_pixels(dev_u8(pixm), t, tm, idx, n)
+        np.testing.assert_array_equal(tm.cpu().numpy().reshape(tm_o.shape), tm_o)
+        assert int(n.item()) == idx_o.size
+        np.testing.assert_array_equal(idx.cpu().numpy()[:idx_o.size], idx_o)
+        out = torch.zeros((H // 2, W // 2), dtype=torch.uint8, device=DEV)
+        fb.fise_mask_downsample(dev_u8(pixm), out)
+        np.testing.assert_array_equal(out.cpu().numpy(), fo.mask_downsample(pixm))
+
+
+def test_otsu_and_accumulate_and_apsc(fb):
+    rng = np.random.default_rng(2013)
+    B, H, W, C = 2, 64, 64, 4
+    steps_old = [wl.normal(rng, (B, H, W, C), 1.0, "bf16") for _ in range(4)]
+    pixm = wl.ellipse_pixels(rng, H, W, 0.12)
+    steps_new = [wl.storage_round(wl.perturb(rng, s, pixm, 0.6, "bf16") + 0.03 * rng.standard_normal(s.shape).astype(np.float32), "bf16")
+                 for s in steps_old]
+    acc = torch.zeros((H, W), dtype=torch.float32, device=DEV)
+    for so, sn in zip(steps_old, steps_new):
+        fb.fise_diff_accumulate(dev(so, "bf16"), dev(sn, "bf16"), acc)
+    acc_o = fo.accumulate_diff(steps_old, steps_new)
+    assert rel_err(host(acc), acc_o) < 1e-5
+    # Otsu on the device-accumulated map: the oracle gets the same float32 values
+    diff = acc.cpu().numpy()
+    eps_o, mask_o = fo.otsu_threshold(fo.normalize_minmax(diff))
+    eps = torch.zeros(1, dtype=torch.float32, device=DEV); pm = torch.zeros((H, W), dtype=torch.uint8, device=DEV)
+    wsb = torch.zeros(fb.fise_otsu_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    fb.fise_otsu_mask(acc, eps, pm, wsb)
+    np.testing.assert_array_equal(pm.cpu().numpy(), mask_o)
+    assert abs(float(eps.item()) - eps_o) < 1e-7
+    assert abs(mask_o.mean() - pixm.mean()) < 0.02                        # it found the blob
+    # constant map: everything lands in class B
+    fb.fise_otsu_mask(torch.ones(64, device=DEV), eps, pm.reshape(-1)[:64], wsb)
+    e2, m2 = fo.otsu_threshold(fo.normalize_minmax(np.ones(64)))
+    assert float(eps.item()) == e2 and int(pm.reshape(-1)[:64].sum().item()) == int(m2.sum())
+    # block counts for the 25 candidate sizes
+    counts = torch.zeros(25, dtype=torch.int32, device=DEV)
+    fb.fise_apsc_block_counts(dev_u8(mask_o), counts)
+    c = counts.cpu().numpy()
+    best = None
+    for i, h in enumerate((2, 4, 8, 16, 32)):
+        for j, w in enumerate((2, 4, 8, 16, 32)):
+            assert c[i * 5 + j] * (h + 2) * (w + 2) == fo.apsc_cost(mask_o, h, w)
+            cost = c[i * 5 + j] * (h + 2) * (w + 2)
+            if best is None or cost < best[0]:
+                best = (cost, h, w)
+    assert (best[1], best[2], best[0]) == fo.apsc_block_size(mask_o)
+    pm48 = dev_u8(np.ones((48, 48), np.uint8)); fb.fise_apsc_block_counts(pm48, counts)
+    assert counts.cpu().numpy()[4 * 5 + 4] == -1                           # 32 does not divide 48
+
+
+@pytest.mark.parametrize("dtype,shape,G,two", [("f32", (1, 32, 32, 64), 32, False), ("bf16", (2, 64, 64, 320), 32, False),
+                                               ("bf16", (2, 16, 16, 1280), 32, True), ("bf16", (2, 10, 6, 96), 4, True)])
+def test_groupnorm_stats(fb, dtype, shape, G, two):
+    rng = np.random.default_rng(3001)
+    B, H, W, C = shape
+    x = wl.normal(rng, shape, 1.7, dtype, mean=0.4)
+    x1 = wl.normal(rng, (B, H, W, C // 2), 0.6, dtype, mean=-1.0) if two else None
+    Ct = C + (C // 2 if two else 0)
+    mean = torch.zeros((B, G), device=DEV); rstd = torch.zeros((B, G), device=DEV)
+    wsb = torch.zeros(fb.fise_groupnorm_stats_workspace_bytes(B, H, W, Ct), dtype=torch.uint8, device=DEV)
+    fb.fise_groupnorm_stats(dev(x, dtype), None if x1 is None else dev(x1, dtype), G, 1e-5, mean, rstd, wsb)
+    m_o, r_o = fo.gn_stats([x, x1] if two else x, G, 1e-5)
+    assert np.abs(host(mean) - m_o).max() < 2e-5 and rel_err(host(rstd), r_o) < 2e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_masked_groupnorm_silu(fb, dtype):
+    rng = np.random.default_rng(3002)
+    B, H, W, C, G, t = 2, 32, 32, 64, 32, 4
+    x = wl.normal(rng, (B, H, W, C), 1.5, dtype)
+    g = wl.normal(rng, (C,), 0.1, dtype, mean=1.0); bt = wl.normal(rng, (C,), 0.1, dtype)
+    mean, rstd = fo.gn_stats(wl.normal(rng, (B, H, W, C), 1.5, dtype), G, 1e-5)      # statistics of ANOTHER map: they are inputs
+    cache = wl.normal(rng, (B, H, W, C), 1.0, dtype)
+    _, idx = fo.tiles_from_pixels(wl.ellipse_pixels(rng, H, W, 0.1), t)
+    want = cache.astype(np.float64).copy()
+    fo.masked_gn_silu(x, mean, rstd, g, bt, G, idx, t, want, dtype)
+    y = dev(cache, dtype)
+    fb.fise_masked_groupnorm_silu(dev(x, dtype), dev(mean), dev(rstd), dev(g, dtype), dev(bt, dtype), G, idx_dev(idx), idx.size, t, y)
+    act = active_mask(idx, t, H, W)
+    got = host(y)
+    assert rel_err(got[:, act], want[:, act]) <= TOL[dtype]
+    assert np.array_equal(got[:, ~act], cache.astype(np.float64)[:, ~act])
+    y2 = dev(cache, dtype)
+    fb.fise_masked_groupnorm_silu(dev(x, dtype), dev(mean), dev(rstd), dev(g, dtype), dev(bt, dtype), G, idx_dev(idx), 0, t, y2)
+    assert np.array_equal(host(y2), cache.astype(np.float64))                        # empty mask

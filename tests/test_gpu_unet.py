@@ -1,0 +1,137 @@
+"""GPU parity: the masked UNet step vs the CPU oracle on a small instance of the architecture
+(element by element), and structural properties at the full SD-1.5 shape."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fise_oracle as fo
+from oracle import fise_unet_oracle as uo
+from paper_2305_17423_amd import workloads as wl
+from helpers import (DEV, TOL, dev, host, rel_err, idx_dev, active_mask, pack_weights, pack_cache, unpack_cache)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2305_17423_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def problem(d, seed, std):
+    rng = np.random.default_rng(seed)
+    P = wl.params_from_shapes(rng, uo.param_shapes(d), std, "bf16")
+    lat = wl.normal(rng, (d["B"], d["H"], d["W"], d["in_ch"]), 1.0, "bf16")
+    ctx_old = wl.normal(rng, (d["B"], d["n_ctx"], d["ctx_dim"]), 1.0, "bf16")
+    ctx_new = wl.normal(rng, (d["B"], d["n_ctx"], d["ctx_dim"]), 1.0, "bf16")
+    t_sin = uo.timestep_embedding(np.full(d["B"], 481.0), d["base"]).astype(np.float32)
+    return rng, P, lat, ctx_old, ctx_new, t_sin
+
+
+def stored_maps(d):
+    for m in uo.unet_modules(d):
+        names = {"res": ["h1", "out"], "tr": ["out", "k", "v"], "ds": ["out"], "us": ["out"], "conv_in": ["out"]}.get(m["kind"], [])
+        for s in names:
+            yield m, f"{m['name']}.{s}"
+    yield uo.unet_modules(d)[-1], "eps"
+
+
+def compare_caches(d, got, want, before, idx, bt, tol):
+    worst = ("", 0.0)
+    for m, name in stored_maps(d):
+        H, W = d["H"] >> m["lvl"], d["W"] >> m["lvl"]
+        act = active_mask(idx, bt >> m["lvl"], H, W)
+        g, w_, b_ = got[name], want[name], before[name]
+        if g.ndim == 3:                                   # K / V caches [B, N, C]
+            act = act.reshape(-1)
+        err = rel_err(g[:, act], w_[:, act])
+        if err > worst[1]:
+            worst = (name, err)
+        assert err <= tol, f"{name}: rel err {err:.3e}"
+        assert np.array_equal(g[:, ~act], b_[:, ~act]), f"{name}: inactive positions changed"
+    return worst
+
+
+@pytest.mark.parametrize("seed", [5001, 5002])
+def test_tiny_unet_step_vs_oracle(fb, seed):
+    d = uo.tiny_desc()
+    rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, seed, 0.08)
+    H, W, bt = d["H"], d["W"], 8
+    shapes = uo.cache_shapes(d)
+    kv_old = uo.context_kv_all(P, d, ctx_old, "bf16"); kv_new = uo.context_kv_all(P, d, ctx_new, "bf16")
+    _, cache_old = uo.unet_dense(P, d, lat, t_sin, kv_old, "bf16")
+
+    u = fb.fise_unet_create(d)
+    Wd = pack_weights(fb, u, P)
+    kvd_old = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=DEV); kvd_new = torch.zeros_like(kvd_old)
+    fb.fise_unet_context_kv(u, Wd, dev(ctx_old, "bf16"), kvd_old); fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd_new)
+    ntiles = (H // bt) * (W // bt)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, ntiles, bt), dtype=torch.uint8, device=DEV)
+    tsd = dev(t_sin)
+    full = fo.full_index(H, W, bt)
+
+    # (1) dense forward on the device (full list, fresh statistics, zero cache) vs the oracle's dense walk
+    cd = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_masked_unet_step(u, Wd, cd, dev(lat, "bf16"), tsd, kvd_old, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
+    got = unpack_cache(fb, u, cd, shapes)
+    zero = {k: np.zeros_like(v) for k, v in cache_old.items()}
+    worst = compare_caches(d, got, cache_old, zero, full, bt, TOL["bf16"])
+    for k in shapes:
+        if k.endswith(".mean"):
+            assert np.abs(got[k] - cache_old[k]).max() < 2e-2, k
+        if k.endswith(".rstd"):
+            assert rel_err(got[k], cache_old[k]) < 2e-2, k
+
+    # (2) masked step from the ORACLE's cache (both sides start from identical state)
+    pixm = wl.rect_pixels(rng, H, W, 5, 6)
+    lat_new = wl.perturb(rng, lat, pixm, 1.0, "bf16")
+    _, _, idx = fo.mask_detect(lat, lat_new, 0.1, bt)
+    assert 0 < idx.size < ntiles
+    want = {k: v.copy() for k, v in cache_old.items()}
+    uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16")
+    cm = pack_cache(fb, u, cache_old)
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
+    got = unpack_cache(fb, u, cm, shapes)
+    compare_caches(d, got, want, cache_old, idx, bt, TOL["bf16"])
+    for k in shapes:
+        if k.endswith((".mean", ".rstd")):
+            assert np.array_equal(got[k], cache_old[k].astype(np.float32).astype(np.float64)), k   # cached statistics untouched
+    # (3) idempotent; (4) empty mask leaves every byte alone
+    snap = cm.clone()
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
+    assert torch.equal(cm, snap)
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat, "bf16"), tsd, kvd_old, idx_dev(idx), 0, bt, fb.FISE_STATS_CACHED, None, ws)
+    assert torch.equal(cm, snap)
+    # (5) per-level dense override
+    want2 = {k: v.copy() for k, v in cache_old.items()}
+    ld = [False, False, True, True]
+    uo.unet_step(P, d, want2, lat_new, t_sin, kv_new, idx, bt, "bf16", level_dense=ld)
+    c5 = pack_cache(fb, u, cache_old)
+    fb.fise_masked_unet_step(u, Wd, c5, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, ld, ws)
+    got5 = unpack_cache(fb, u, c5, shapes)
+    assert rel_err(got5["eps"], want2["eps"]) <= TOL["bf16"] and rel_err(got5["mid.tr.0.out"], want2["mid.tr.0.out"]) <= TOL["bf16"]
+    fb.fise_unet_destroy(u)
+
+
+def test_tiny_unet_full_mask_fresh_equals_dense_of_new_inputs(fb):
+    d = uo.tiny_desc()
+    rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, 5003, 0.08)
+    H, W, bt = d["H"], d["W"], 8
+    shapes = uo.cache_shapes(d)
+    kv_old = uo.context_kv_all(P, d, ctx_old, "bf16"); kv_new = uo.context_kv_all(P, d, ctx_new, "bf16")
+    _, cache_old = uo.unet_dense(P, d, lat, t_sin, kv_old, "bf16")
+    lat_new = wl.perturb(rng, lat, wl.rect_pixels(rng, H, W, 7, 7), 1.0, "bf16")
+    eps_new, cache_new = uo.unet_dense(P, d, lat_new, t_sin, kv_new, "bf16")
+    u = fb.fise_unet_create(d)
+    Wd = pack_weights(fb, u, P)
+    kvd = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd)
+    full = fo.full_index(H, W, bt)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, full.size, bt), dtype=torch.uint8, device=DEV)
+    cm = pack_cache(fb, u, cache_old)
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), dev(t_sin), kvd, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
+    got = unpack_cache(fb, u, cm, shapes)
+    assert rel_err(got["eps"], cache_new["eps"]) <= TOL["bf16"]
+    fb.fise_unet_destroy(u)
