@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Bench of the masked UNet step (config 5: full SD-1.5-shaped UNet, bf16, batch 2, latent
+64x64x4, context 77x768, one seeded blob covering ~10 % of the latent, 8x8 base tiles).
+
+A "step" is one pass of the whole hot path: fise_mask_detect on (cached latent, new latent)
+followed by fise_masked_unet_step on the per-timestep cache.  Everything is resident in HBM
+before the timed region; nothing inside it synchronises with the host.
+
+Prints ONE JSON line (see the keys below).  `value` is the dense-equivalent rate: FLOPs of
+a dense evaluation divided by the masked step time; `useful_tflops` counts only the FLOPs
+the masked step executes and is the number the roofline fraction is built on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0
+
+SD15 = dict(in_ch=4, out_ch=4, base=320, mults=(1, 2, 4, 4), layers=2, attn=(True, True, True, False),
+            heads=8, ctx_dim=768, n_ctx=77, groups=32, H=64, W=64, B=2)
+SMALL = dict(SD15, base=64, heads=4, ctx_dim=128, n_ctx=16, H=32, W=32)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def sinusoid(t, dim):
+    import numpy as np
+    half = dim // 2
+    f = np.exp(-math.log(10000.0) * np.arange(half) / half)
+    a = np.asarray(t, np.float64)[:, None] * f[None, :]
+    return np.concatenate([np.cos(a), np.sin(a)], 1).astype(np.float32)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--frac", type=float, default=0.10, help="fraction of latent pixels inside the blob")
+    ap.add_argument("--tile", type=int, default=8)
+    ap.add_argument("--caches", type=int, default=10, help="distinct per-timestep caches cycled through (260 MB each)")
+    ap.add_argument("--small", action="store_true", help="a narrow UNet for quick checks (not the headline workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--seed", type=int, default=5000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2305_17423_amd import binding as fb, workloads as wl
+    fb.lib()                                     # raises if the HIP library has not been built
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    d = SMALL if args.small else SD15
+    B, H, W, bt = d["B"], d["H"], d["W"], args.tile
+    rng = np.random.default_rng(args.seed)
+    gen = torch.Generator(device=dev); gen.manual_seed(args.seed)
+
+    # ---- plan, weights N(0, 0.02^2) (norm scales 1, biases and shifts 0), generated on the device
+    u = fb.fise_unet_create(d)
+    nW = fb.fise_unet_weight_elems(u)
+    Wd = torch.zeros(nW, dtype=torch.bfloat16, device=dev)
+    for name, off, num in fb.fise_unet_tensors(u, 0):
+        if name.endswith(".w"):
+            Wd[off:off + num] = (0.02 * torch.randn(num, device=dev, generator=gen)).to(torch.bfloat16)
+        elif name.endswith(".g"):
+            Wd[off:off + num] = 1.0
+    lat_old = torch.from_numpy(wl.normal(rng, (B, H, W, d["in_ch"]), 1.0, "bf16")).to(torch.bfloat16).to(dev)
+    pix = wl.ellipse_pixels(rng, H, W, args.frac)
+    lat_new_h = wl.perturb(rng, lat_old.float().cpu().numpy(), pix, 1.0, "bf16")
+    lat_new = torch.from_numpy(lat_new_h).to(torch.bfloat16).to(dev)
+    ctx_old = torch.from_numpy(wl.normal(rng, (B, d["n_ctx"], d["ctx_dim"]), 1.0, "bf16")).to(torch.bfloat16).to(dev)
+    ctx_new_h = wl.normal(rng, (B, d["n_ctx"], d["ctx_dim"]), 1.0, "bf16")
+    ctx_new = torch.from_numpy(ctx_new_h).to(torch.bfloat16).to(dev)
+    T = 50
+    ts = np.arange(T)[::-1] * (1000 // T)
+    t_sin_all = [torch.from_numpy(sinusoid(np.full(B, float(t)), d["base"])).to(dev) for t in ts]
+
+    kv_old = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=dev); kv_new = torch.zeros_like(kv_old)
+    fb.fise_unet_context_kv(u, Wd, ctx_old, kv_old); fb.fise_unet_context_kv(u, Wd, ctx_new, kv_new)
+    ntiles = (H // bt) * (W // bt)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, ntiles, bt), dtype=torch.uint8, device=dev)
+    full = torch.arange(ntiles, dtype=torch.int32, device=dev)
+
+    # ---- per-timestep caches of the old generation: dense passes (full list, fresh statistics)
+    ncache = max(1, min(args.caches, T))
+    cbytes = fb.fise_unet_cache_bytes(u)
+    caches = [torch.zeros(cbytes, dtype=torch.uint8, device=dev) for _ in range(ncache)]
+    t0 = time.time()
+    for i, c in enumerate(caches):
+        fb.fise_masked_unet_step(u, Wd, c, lat_old, t_sin_all[i], kv_old, full, ntiles, bt, fb.FISE_STATS_FRESH, None, ws)
+    torch.cuda.synchronize()
+    log(f"[bench] built {ncache} caches of {cbytes / 1e6:.0f} MB in {time.time() - t0:.2f} s")
+
+    # ---- mask: detect once, read n_active back once
+    pm = torch.zeros((H, W), dtype=torch.uint8, device=dev); tm = torch.zeros(ntiles, dtype=torch.uint8, device=dev)
+    idx = torch.zeros(ntiles, dtype=torch.int32, device=dev); nact = torch.zeros(1, dtype=torch.int32, device=dev)
+    fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)
+    na = int(nact.item())
+    log(f"[bench] blob {pix.mean() * 100:.1f} % of pixels -> {na}/{ntiles} tiles active ({na / ntiles * 100:.1f} %)")
+
+    def step(i, n_active, index, mode=fb.FISE_STATS_CACHED):
+        fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)          # a1 + a2 (device only)
+        fb.fise_masked_unet_step(u, Wd, caches[i % ncache], lat_new, t_sin_all[i % T], kv_new, index, n_active, bt, mode, None, ws)
+
+    def timed(n, n_active, index):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            step(i, n_active, index)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    for i in range(args.warmup):
+        step(i, na, idx)
+    ms_masked = timed(args.steps, na, idx)
+    ms_dense = None
+    if not args.no_dense:
+        for i in range(2):
+            step(i, ntiles, full)
+        ms_dense = timed(max(3, min(args.steps, 10)), ntiles, full)
+
+    # ---- per-kernel accounting with HIP events on the launch stream (separate passes: the events
+    # widen the gaps between kernels, so these passes are not the timed ones)
+    def profile(n, n_active, index):
+        fb.fise_profile_read(-1)
+        fb.fise_profile_enable(True)
+        for i in range(n):
+            step(i, n_active, index)
+        torch.cuda.synchronize()
+        fb.fise_profile_enable(False)
+        out = {k: fb.fise_profile_read(k) for k in range(4)}
+        fb.fise_profile_read(-1)
+        return out
+    npass = 3
+    pm_masked = profile(npass, na, idx)
+    flops_masked = sum(v[1] for v in pm_masked.values()) / npass
+    flops_dense = None
+    if not args.no_dense:
+        pd = profile(1, ntiles, full)
+        flops_dense = sum(v[1] for v in pd.values())
+    else:
+        flops_dense = flops_masked * ntiles / max(na, 1)
+    names = {0: "igemm_kernel<64,64,2,2>", 1: "igemm_kernel<64,128,2,2> (GEGLU)", 2: "attention_kernel", 3: "igemm wide"}
+    kinds = {}
+    for k, (ms, fl, by, n) in pm_masked.items():
+        if n:
+            kinds[names[k]] = dict(launches_per_step=n // npass, ms_per_step=ms / npass, avg_us=1e3 * ms / n,
+                                   tflops=fl / ms / 1e9 if ms > 0 else None, gbs=by / ms / 1e6 if ms > 0 else None)
+    dom = max(pm_masked, key=lambda k: pm_masked[k][0])
+    dms, dfl, dby, dn = pm_masked[dom]
+    roofline = dict(bound="mfma", kernel=names[dom], achieved=dfl / dms / 1e9, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=dfl / dms / 1e9 / MFMA_BF16_PEAK_TFLOPS, traffic=None, avg_launch_us=1e3 * dms / dn,
+                    launches_per_step=dn // npass, algorithmic_gbs=dby / dms / 1e6, hbm_frac=dby / dms / 1e6 / HBM_PEAK_GBS)
+
+    res = {
+        "metric": "masked_unet_step_dense_equivalent_tflops_at_10pct_mask", "value": flops_dense / ms_masked / 1e9,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_masked,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": ("small UNet (not the headline workload)" if args.small else
+                                "config 5: SD-1.5-shaped UNet step, batch 2, latent 64x64x4, context 77x768, seeded blob, "
+                                "8x8 base tiles; mask detect + masked step per timed step"),
+                   "pixel_fraction": float(pix.mean()), "active_tile_fraction": na / ntiles, "tile": bt, "caches_cycled": ncache},
+        "masked_ms": ms_masked, "dense_ms": ms_dense, "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None,
+        "unet_calls_per_s": 1e3 / ms_masked, "useful_tflops": flops_masked / ms_masked / 1e9,
+        "masked_gflop": flops_masked / 1e9, "dense_gflop": flops_dense / 1e9,
+        "dense_tflops": (flops_dense / ms_dense / 1e9) if ms_dense else None,
+        "weight_stream_floor_ms": nW * 2 / (HBM_PEAK_GBS * 1e6),
+        "kernels": kinds, "roofline": roofline,
+    }
+
+    # ---- the oracle, as it stands, on the host cores: one masked step of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import fise_oracle as fo, fise_unet_oracle as uo        # cpu_baseline leg only
+        t0 = time.time()
+        Wh = Wd.float().cpu().numpy()
+        P = {}
+        shapes = uo.param_shapes(d)
+        for name, off, num in fb.fise_unet_tensors(u, 0):
+            P[name] = Wh[off:off + num].reshape(shapes[name])
+        cache = {k: (np.ones(s) if k.endswith(".rstd") else np.zeros(s)) for k, s in uo.cache_shapes(d).items()}
+        for k in cache:                       # synthetic cached activations: the cost does not depend on their values
+            if not k.endswith((".mean", ".rstd")):
+                cache[k] = rng.standard_normal(cache[k].shape)
+        kvo = uo.context_kv_all(P, d, ctx_new_h, "bf16")
+        _, _, idx_o = fo.mask_detect(lat_old.float().cpu().numpy(), lat_new_h, 0.1, bt)
+        assert idx_o.size == na
+        log(f"[bench] oracle set-up {time.time() - t0:.1f} s; timing one masked oracle step ...")
+        t0 = time.time()
+        uo.unet_step(P, d, cache, lat_new_h, t_sin_all[0].cpu().numpy(), kvo, idx_o, bt, "bf16")
+        dt = time.time() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        res["cpu_baseline"] = {"value": flops_dense / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                               "sample": "one masked UNet step of the same workload (same mask, weights, shapes; synthetic "
+                                         "cached activations), numpy float64, threads = all cores via the BLAS pool",
+                               "seconds": dt}
+    print(json.dumps(res))
+    fb.fise_unet_destroy(u)
+
+
+if __name__ == "__main__":
+    main()

@@ -204,6 +204,65 @@ int fise_masked_attention(const void* x, const void* ln_gamma, const void* ln_be
                           void* y_cache, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Masked ResNet and transformer modules (section "Sparse Computation": "the
+ * U-Net architecture is composed of several attention and ResNet modules";
+ * each is recomputed on the masked region only).  bf16 only.  The UNet step
+ * below is a sequence of these two calls plus resampling convolutions.
+ * ------------------------------------------------------------------------ */
+
+/* out = shortcut(x) + conv2(SiLU(GN2(h1))),  h1 = conv1(SiLU(GN1(x))) + temb,
+ * at active pixels; x = channel concatenation of x0 [B,H,W,C0] and x1
+ * [B,H,W,C1] (skip link; NULL / 0 for none).  h1_cache and out_cache
+ * [B,H,W,Cout] are updated in place (conv2's halo reads cached h1).
+ * shortcut = identity (C0+C1 == Cout, sc_w NULL) or the 1x1 conv sc_w/sc_b.
+ * gn*_mean/rstd [B,G] float: with stats_fresh == 0 they are inputs (statistics
+ * cached from the previous generation); with stats_fresh != 0 they are
+ * recomputed from the current x / updated h1 and written back (eps 1e-5).
+ * temb [B, temb_stride] float, column c of this block at temb[b*temb_stride+c]
+ * (NULL = none).  Channel counts multiples of 32. */
+typedef struct {
+    const void* x0; const void* x1; int C0, C1;
+    int B, H, W, Cout, G;
+    float* gn1_mean; float* gn1_rstd; const void* gn1_gamma; const void* gn1_beta;
+    const void* conv1_w; const void* conv1_b;
+    const float* temb; int temb_stride;
+    float* gn2_mean; float* gn2_rstd; const void* gn2_gamma; const void* gn2_beta;
+    const void* conv2_w; const void* conv2_b;
+    const void* sc_w; const void* sc_b;
+    const int32_t* tile_idx; int n_active; int tile;
+    void* h1_cache; void* out_cache;
+    int stats_fresh;
+} fise_resnet_args;
+size_t fise_masked_resnet_block_workspace_bytes(const fise_resnet_args* a /* host */);
+int fise_masked_resnet_block(const fise_resnet_args* a /* host */, void* workspace, size_t workspace_bytes, void* stream);
+
+/* out = x + P_out( FF( CA( SA( P_in(GN(x)) ) ) ) ) on active tokens:
+ *   h  = pin(GN(x))                        GroupNorm eps 1e-6, no activation; 1x1 conv
+ *   h += Wo1 Attn(LN1(h); K,V of all tokens) + bo1     K,V rows of active tokens refreshed first
+ *   h += Wo2 Attn(LN2(h); K_ctx, Vt_ctx)   + bo2       text context of the NEW conditioning
+ *   h += W2 GEGLU(W1 LN3(h) + b1) + b2
+ *   out = pout(h) + x                      scattered into out_cache [B,H,W,C]
+ * qkv_w is [3C, C]: Wq, Wk, Wv stacked.  K_cache [B,H*W,C], Vt_cache [B,C,H*W]
+ * (transposed) are updated in place at active tokens.  gn_mean/rstd as in the
+ * ResNet block.  C multiple of 32, C/heads multiple of 8 and <= 160, H*W
+ * multiple of 8.  x must not alias out_cache. */
+typedef struct {
+    const void* x; int B, H, W, C, G, heads;
+    float* gn_mean; float* gn_rstd; const void* gn_gamma; const void* gn_beta;
+    const void* pin_w; const void* pin_b;
+    const void* ln1_g; const void* ln1_b; const void* qkv_w; const void* o1_w; const void* o1_b;
+    const void* ln2_g; const void* ln2_b; const void* q2_w; const void* o2_w; const void* o2_b;
+    const void* K_ctx; const void* Vt_ctx; int n_ctx, n_ctx_stride;
+    const void* ln3_g; const void* ln3_b; const void* ff1_w; const void* ff1_b; const void* ff2_w; const void* ff2_b;
+    const void* pout_w; const void* pout_b;
+    void* K_cache; void* Vt_cache; void* out_cache;
+    const int32_t* tile_idx; int n_active; int tile;
+    int stats_fresh;
+} fise_transformer_args;
+size_t fise_masked_transformer_block_workspace_bytes(const fise_transformer_args* a /* host */);
+int fise_masked_transformer_block(const fise_transformer_args* a /* host */, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Masked UNet step (section "Sparse Computation": the U-Net's ResNet and
  * attention modules run on the masked region only, the rest is reused from
  * the cache of the previous generation; overview figure: pre-computed
@@ -258,6 +317,30 @@ int fise_masked_unet_step(const fise_unet* u, const void* weights, void* cache, 
                           const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
                           int base_tile, int stats_mode, const int* level_dense /* host */,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same step restricted to modules [first_module, first_module + n_modules) of the
+ * walk (conv_in, ResNet / transformer blocks, resamplers, output conv, in execution
+ * order); the time-embedding projections are always recomputed.  Module i reads its
+ * input maps from `cache` as they stand.  Used to check or time one module at a time. */
+int fise_unet_num_modules(const fise_unet* u);
+int fise_unet_module_name(const fise_unet* u, int i, char* name /* host, >= 64 bytes */);
+int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cache, const void* latent,
+                             const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
+                             int base_tile, int stats_mode, const int* level_dense /* host */,
+                             int first_module, int n_modules,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Tracing.  With profiling enabled every launch of the gathered-GEMM and
+ * attention kernels is bracketed by two HIP events on the caller's stream
+ * (host objects; no device memory).  fise_profile_read(kind, ...) waits for the
+ * events and returns the summed event time (ms), algorithmic FLOPs and bytes
+ * and the number of launches recorded for `kind` (0 = gathered GEMM, 1 = the
+ * same with the GEGLU epilogue, 2 = attention, 3 = wide-tile gathered GEMM);
+ * kind = -1 clears the log.  All pointers host.  Not thread safe.
+ * ------------------------------------------------------------------------ */
+int fise_profile_enable(int on);
+int fise_profile_read(int kind, double* total_ms, double* total_flops, double* total_bytes, int* launches);
 
 #ifdef __cplusplus
 }

@@ -253,7 +253,11 @@ def empty_cache(desc):
     return {k: np.zeros(s, F64) for k, s in cache_shapes(desc).items()}
 
 
-def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stats="cached", level_dense=None):
+def module_output_name(m):
+    return "eps" if m["kind"] == "out" else f"{m['name']}.out"
+
+
+def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stats="cached", level_dense=None, only=None):
     """One masked UNet evaluation.  `latent` [B,H,W,in_ch] is the (updated)
     input; `t_sin` [B, base] the sinusoidal time embedding; `ctx_kv` the dict
     from context_kv_all for the *new* conditioning; `idx` the active-tile list
@@ -262,7 +266,8 @@ def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stat
     that is a union of base tiles gives exactly that), so base_tile must be
     divisible by 2**(levels-1).  The cache is updated in place; returns the
     predicted noise map cache['eps'].  level_dense[l] = True runs level l with
-    the full index list."""
+    the full index list.  only = a set of module positions in the walk: the
+    others are skipped and their cached output stands in for them."""
     G, heads = desc["groups"], desc["heads"]
     H, W = desc["H"], desc["W"]
     nl = len(desc["mults"])
@@ -275,9 +280,12 @@ def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stat
 
     emb = fo.linear(_silu(fo.linear(t_sin, P["time.l1.w"], P["time.l1.b"])), P["time.l2.w"], P["time.l2.b"])
     cur = None
-    for m in unet_modules(desc):
+    for mi, m in enumerate(unet_modules(desc)):
         n, k = m["name"], m["kind"]
         li, lt = lv(m["lvl"])
+        if only is not None and mi not in only:
+            cur = cache[module_output_name(m)]
+            continue
         if k == "conv_in":
             cur = fo.masked_conv(np.asarray(latent, F64), P[f"{n}.w"], P[f"{n}.b"], li, lt, cache[f"{n}.out"], dtype)
         elif k == "res":

@@ -36,6 +36,26 @@ class fise_conv_args(C.Structure):
                 ("y_cache", vp), ("dtype", i32)]
 
 
+class fise_resnet_args(C.Structure):
+    _fields_ = [("x0", vp), ("x1", vp), ("C0", i32), ("C1", i32), ("B", i32), ("H", i32), ("W", i32), ("Cout", i32), ("G", i32),
+                ("gn1_mean", vp), ("gn1_rstd", vp), ("gn1_gamma", vp), ("gn1_beta", vp), ("conv1_w", vp), ("conv1_b", vp),
+                ("temb", vp), ("temb_stride", i32),
+                ("gn2_mean", vp), ("gn2_rstd", vp), ("gn2_gamma", vp), ("gn2_beta", vp), ("conv2_w", vp), ("conv2_b", vp),
+                ("sc_w", vp), ("sc_b", vp), ("tile_idx", vp), ("n_active", i32), ("tile", i32),
+                ("h1_cache", vp), ("out_cache", vp), ("stats_fresh", i32)]
+
+
+class fise_transformer_args(C.Structure):
+    _fields_ = [("x", vp), ("B", i32), ("H", i32), ("W", i32), ("C", i32), ("G", i32), ("heads", i32),
+                ("gn_mean", vp), ("gn_rstd", vp), ("gn_gamma", vp), ("gn_beta", vp), ("pin_w", vp), ("pin_b", vp),
+                ("ln1_g", vp), ("ln1_b", vp), ("qkv_w", vp), ("o1_w", vp), ("o1_b", vp),
+                ("ln2_g", vp), ("ln2_b", vp), ("q2_w", vp), ("o2_w", vp), ("o2_b", vp),
+                ("K_ctx", vp), ("Vt_ctx", vp), ("n_ctx", i32), ("n_ctx_stride", i32),
+                ("ln3_g", vp), ("ln3_b", vp), ("ff1_w", vp), ("ff1_b", vp), ("ff2_w", vp), ("ff2_b", vp),
+                ("pout_w", vp), ("pout_b", vp), ("K_cache", vp), ("Vt_cache", vp), ("out_cache", vp),
+                ("tile_idx", vp), ("n_active", i32), ("tile", i32), ("stats_fresh", i32)]
+
+
 class fise_unet_desc(C.Structure):
     _fields_ = [("in_ch", i32), ("out_ch", i32), ("base", i32), ("n_levels", i32),
                 ("mults", i32 * FISE_MAX_LEVELS), ("attn", i32 * FISE_MAX_LEVELS), ("layers", i32),
@@ -65,6 +85,10 @@ _SIGS = {
     "fise_masked_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
     "fise_masked_attention": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp,
                                     i32, i32, vp, i32, i32, vp, vp, sz, vp]),
+    "fise_masked_resnet_block_workspace_bytes": (sz, [C.POINTER(fise_resnet_args)]),
+    "fise_masked_resnet_block": (i32, [C.POINTER(fise_resnet_args), vp, sz, vp]),
+    "fise_masked_transformer_block_workspace_bytes": (sz, [C.POINTER(fise_transformer_args)]),
+    "fise_masked_transformer_block": (i32, [C.POINTER(fise_transformer_args), vp, sz, vp]),
     "fise_unet_create": (i32, [C.POINTER(fise_unet_desc), C.POINTER(vp)]),
     "fise_unet_destroy": (None, [vp]),
     "fise_unet_num_tensors": (i32, [vp, i32]),
@@ -75,6 +99,11 @@ _SIGS = {
     "fise_unet_workspace_bytes": (sz, [vp, i32, i32]),
     "fise_unet_context_kv": (i32, [vp, vp, vp, vp, vp, sz, vp]),
     "fise_masked_unet_step": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), vp, sz, vp]),
+    "fise_profile_enable": (i32, [i32]),
+    "fise_profile_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]),
+    "fise_unet_num_modules": (i32, [vp]),
+    "fise_unet_module_name": (i32, [vp, i32, C.c_char_p]),
+    "fise_masked_unet_modules": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), i32, i32, vp, sz, vp]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -248,6 +277,40 @@ def fise_masked_attention(x, ln_gamma, ln_beta, Wq, Wk, Wv, Wo, bo, heads, K_cac
                                     _p(tile_idx), n_active, tile, _p(y_cache), _p(workspace), nbytes, _stream(stream)))
 
 
+# --------------------------------------------------------------------------- modules
+def fill_args(struct_type, keep, **kw):
+    """A ctypes argument struct from keyword values; tensors become addresses and are appended
+    to `keep` so they outlive the (asynchronous) call."""
+    a = struct_type()
+    types = dict(struct_type._fields_)
+    for k, v in kw.items():
+        if types[k] is vp:
+            if hasattr(v, "data_ptr"):
+                keep.append(v)
+            setattr(a, k, _p(v))
+        else:
+            setattr(a, k, int(v))
+    return a
+
+
+def fise_masked_resnet_block_workspace_bytes(args):
+    return lib().fise_masked_resnet_block_workspace_bytes(C.byref(args))
+
+
+def fise_masked_resnet_block(args, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _ck(lib().fise_masked_resnet_block(C.byref(args), _p(workspace), nbytes, _stream(stream)))
+
+
+def fise_masked_transformer_block_workspace_bytes(args):
+    return lib().fise_masked_transformer_block_workspace_bytes(C.byref(args))
+
+
+def fise_masked_transformer_block(args, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _ck(lib().fise_masked_transformer_block(C.byref(args), _p(workspace), nbytes, _stream(stream)))
+
+
 # --------------------------------------------------------------------------- UNet
 def make_desc(d):
     s = fise_unet_desc()
@@ -310,3 +373,33 @@ def fise_masked_unet_step(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_a
     _ck(lib().fise_masked_unet_step(u, _p(weights), _p(cache), _p(latent), _p(t_sin), _p(ctxkv), _p(tile_idx), n_active,
                                     base_tile, stats_mode, ld, _p(workspace), workspace.numel() * workspace.element_size(),
                                     _stream(stream)))
+
+
+def fise_unet_module_names(u):
+    name = C.create_string_buffer(64)
+    out = []
+    for i in range(lib().fise_unet_num_modules(u)):
+        _ck(lib().fise_unet_module_name(u, i, name))
+        out.append(name.value.decode())
+    return out
+
+
+def fise_masked_unet_modules(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_active, base_tile, stats_mode,
+                             level_dense, first_module, n_modules, workspace, stream=None):
+    ld = None
+    if level_dense is not None:
+        ld = (i32 * len(level_dense))(*[int(v) for v in level_dense])
+    _ck(lib().fise_masked_unet_modules(u, _p(weights), _p(cache), _p(latent), _p(t_sin), _p(ctxkv), _p(tile_idx), n_active,
+                                       base_tile, stats_mode, ld, first_module, n_modules, _p(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fise_profile_enable(on):
+    _ck(lib().fise_profile_enable(1 if on else 0))
+
+
+def fise_profile_read(kind):
+    """(total_ms, total_flops, total_bytes, launches) of the launches recorded for `kind`; -1 clears."""
+    ms, fl, by, n = C.c_double(), C.c_double(), C.c_double(), i32()
+    _ck(lib().fise_profile_read(kind, C.byref(ms), C.byref(fl), C.byref(by), C.byref(n)))
+    return ms.value, fl.value, by.value, n.value

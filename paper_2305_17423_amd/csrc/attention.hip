@@ -4,6 +4,7 @@
 // query's running max / sum to itself, and the output is accumulated transposed
 // (O^T = V^T P^T), which is why V operands are stored keys-innermost.
 #include "igemm.h"
+#include "profile.h"
 
 namespace fise {
 
@@ -162,6 +163,8 @@ int launch_attention(const void* q, const void* K, const void* Vt, int B, int M,
     if (M <= 0) return FISE_OK;
     const int d = C / heads;
     const int kd = ceil_div(d, 16), db = ceil_div(d, 32);
+    ProfileScope prof(PROF_ATTENTION, 4.0 * B * (double)M * n_keys * C,
+                      2.0 * ((double)B * n_keys * C * 2 + 2.0 * B * M * C), st);
     if (kd <= 1) launch_at<1, 1>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
     else if (kd == 2) launch_at<2, 1>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
     else if (kd == 3) launch_at<3, 2>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);

@@ -102,7 +102,6 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     int Ho, Wo;
     if (int e = validate(a, Ho, Wo)) return e;
     if (a->n_active == 0) return FISE_OK;
-    (void)workspace; (void)workspace_bytes;
     if (!mfma_path(a)) {
         if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st);
         else launch_scalar<bf16_t>(a, Ho, Wo, st);
@@ -119,8 +118,10 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     g.w = (const bf16_t*)a->w; g.N = a->Cout; g.K = a->ksize * a->ksize * (a->C0 + a->C1); g.geglu = 0;
     g.bias = (const bf16_t*)a->bias; g.temb = a->temb; g.temb_stride = a->Cout; g.res = (const bf16_t*)a->residual; g.res_compact = 0;
     g.nsect = 1; g.sect_n = a->Cout; g.out[0] = (bf16_t*)a->y_cache; g.out_mode[0] = OUT_MAP;
-    g.splits = 1; g.partial = nullptr; g.counters = nullptr;
-    return launch_igemm(g, st);
+    g.splits = 1; g.partial = nullptr;
+    IgemmWorkspace iw;
+    if (int e = igemm_workspace_init(workspace, workspace_bytes, &iw, st)) return e;
+    return launch_igemm(g, &iw, st);
 }
 
 }  // namespace fise
@@ -129,7 +130,7 @@ using namespace fise;
 
 extern "C" size_t fise_masked_conv_workspace_bytes(const fise_conv_args* a) {
     (void)a;
-    return 256;
+    return igemm_workspace_bytes();          // split-K scratch; a smaller (or null) workspace runs unsplit
 }
 
 extern "C" int fise_masked_conv(const fise_conv_args* a, void* workspace, size_t workspace_bytes, void* stream) {

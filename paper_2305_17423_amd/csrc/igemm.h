@@ -7,34 +7,48 @@
 namespace fise {
 
 enum { PRO_NONE = 0, PRO_GN = 1, PRO_GN_SILU = 2 };
-enum { OUT_COMPACT = 0, OUT_MAP = 1, OUT_TOKENS_T = 2 };
+enum { OUT_COMPACT = 0, OUT_MAP = 1, OUT_TOKENS_T = 2, OUT_COMPACT_F32 = 3 };
 
 struct IgemmArgs {
     // ---- A operand: rows = B * Ma active pixels (or compact rows) x K
     const bf16_t* a0; const bf16_t* a1; int C0, C1;    // map sources [B,Hin,Win,C*] (a1 unused when C1 == 0)
-    int a_compact;                                      // 1: a0 is a compact [rows, C0] buffer (ksize must be 1)
+    int a_compact;                                      // 1: a0 is a compact bf16 [rows, C0] buffer (ksize must be 1)
     int Hin, Win, ksize, stride, ups;
     // ---- row geometry (output map)
     const int* tile_idx; int tile, tiles_w, Ho, Wo, B, Ma;
     // ---- prologue on A: GroupNorm (+SiLU) with given statistics
     int pro; const float* gn_mean; const float* gn_rstd; const bf16_t* gn_gamma; const bf16_t* gn_beta; int G;
+    const float2* gn_table;                             // [B, Cin] (scale, shift), filled by the launcher when it has scratch
     // ---- B operand: weights [rows_w, K], K innermost
     const bf16_t* w; int N; int K;                      // N = output columns (GEGLU: N = D, weights have 2D rows)
     int geglu;
     // ---- epilogue
-    const bf16_t* bias; const float* temb; int temb_stride; const bf16_t* res; int res_compact;
+    const bf16_t* bias; const float* temb; int temb_stride;
+    const bf16_t* res; int res_compact;                 // 0: map at the output pixel, 1: compact bf16 rows, 2: compact float rows
     int nsect, sect_n;                                  // N = nsect * sect_n; section s goes to out[s]
     bf16_t* out[3]; int out_mode[3];
+    bf16_t* mirror;                                     // OUT_COMPACT_F32 only: also store a bf16 copy here (may be null)
+    // ---- optional side product accumulated into the same tile: 1x1 conv of the raw maps s0 | s1
+    // [B,Ho,Wo,S*] at the output pixel with weights w2 [N, K2] and bias2 (K2 = S0 + S1, 0 = none)
+    const bf16_t* s0; const bf16_t* s1; int S0, S1; const bf16_t* w2; const bf16_t* bias2; int K2;
     // ---- split-K (splits == 1: none)
-    int splits; float* partial; int* counters;
+    int splits; float* partial;
 };
 
-// Enqueue; rows == 0 is a no-op.  Returns a fise_status.
-int launch_igemm(const IgemmArgs& a, hipStream_t st);
-size_t igemm_workspace_bytes(int rows, int N, int K);
+// Scratch of the launcher: GroupNorm (scale, shift) table and the parked partial sums of split-K launches.
+constexpr size_t IGEMM_PARTIAL_BYTES = 32u << 20;
+constexpr size_t IGEMM_GN_TABLE_BYTES = 256u << 10;
+struct IgemmWorkspace { float* partial; size_t partial_bytes; float2* gn_table; size_t gn_table_bytes; };
+size_t igemm_workspace_bytes();
+// Carves the scratch out of `workspace`; with a null or too
+// small workspace `out` is left empty and every launch runs unsplit.
+int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hipStream_t st);
+// Enqueue; rows == 0 is a no-op.  `ws` may be null (no split-K).  Returns a fise_status.
+int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st);
 // LayerNorm of rows -> compact out[rows, C].  tile_idx == nullptr: `in` is compact [rows, C];
 // otherwise `in` is a token map [B, H*W, C] and row r = (b, active pixel r % Ma).
-int launch_ln_rows(const void* in, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
+// in_f32 != 0: compact float rows (tile_idx must be nullptr).
+int launch_ln_rows(const void* in, int in_f32, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
                    const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st);
 int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st);
 // out[b, n] = act(bias[n] + sum_k in[b, k] * W[n, k]) for a handful of rows b (float in/out, bf16 weights).

@@ -1,34 +1,75 @@
 // Gathered implicit GEMM, bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
 //
-//   out[row, n] = epilogue( sum_k A[row, k] * W[n, k] )
+//   out[row, n] = epilogue( sum_k A[row, k] * W[n, k]  (+ sum_k A2[row, k] * W2[n, k]) )
 //
 // A rows are gathered on the fly: row -> (b, y, x) of an active pixel, k ->
 // (tap, channel) of the (optionally normalised + activated) input maps; nothing
-// is packed in HBM.  The workgroup tile is BM x BN with a K step of 32; global
-// loads for step i+1 are issued before the MFMAs of step i and land in the other
-// half of a double-buffered LDS tile.
+// is packed in HBM.  The optional second product is a 1x1 convolution of other
+// maps at the same pixel (the ResNet shortcut), accumulated into the same tile.
+//
+// The masked problems are small (a few GFLOP, often a few dozen rows against tens
+// of MB of weights), so the kernel is built to keep memory requests in flight
+// rather than to maximise MFMA issue: the K loop moves 64 elements per step, global
+// loads run PF steps ahead of the MFMAs in a register FIFO, LDS tiles are double
+// buffered with one barrier per step, several workgroups share a CU, and long K
+// loops are split over workgroups (partials parked in a workspace, summed in split
+// order by the last workgroup of a tile so the result is deterministic).
+#include <algorithm>
+#include <cstdlib>
 #include "igemm.h"
+#include "profile.h"
 
 namespace fise {
 
-constexpr int BK = 32;            // K elements per step
-constexpr int LDT = BK + 8;       // LDS row pitch in bf16 (80 bytes: keeps 16-byte reads conflict-light)
+constexpr int PF = 4;             // prefetch distance in K steps
 
 struct RowInfo { int b, y, x, ok; };
 
-template <int BM, int BN, int WGM, int WGN>
+// Barrier for LDS hand-over only: waits for this wave's LDS traffic, not for its global loads in
+// flight (a full __syncthreads() would drain the prefetch FIFO at every step).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Last stage of the epilogue for output element (row gm = (b, y, x), column col) whose value v already
+// holds the accumulated sum, biases and the GEGLU gate: time projection, residual, store by section.
+__device__ __forceinline__ void epilogue_store(const IgemmArgs& a, int gm, int b, int y, int x, int col, float v) {
+    if (a.temb) v += a.temb[b * a.temb_stride + col];
+    const size_t pix = ((size_t)b * a.Ho + y) * a.Wo + x;
+    if (a.res) {
+        if (a.res_compact == 2) v += reinterpret_cast<const float*>(a.res)[(size_t)gm * a.N + col];
+        else v += bf2f(a.res_compact ? a.res[(size_t)gm * a.N + col] : a.res[pix * a.N + col]);
+    }
+    const int sect = col / a.sect_n, scol = col % a.sect_n;
+    bf16_t* outp = a.out[sect];
+    const int omode = a.out_mode[sect];
+    if (omode == OUT_COMPACT_F32) {
+        reinterpret_cast<float*>(outp)[(size_t)gm * a.sect_n + scol] = v;
+        if (a.mirror) a.mirror[(size_t)gm * a.sect_n + scol] = f2bf(v);
+    } else if (omode == OUT_COMPACT) {
+        outp[(size_t)gm * a.sect_n + scol] = f2bf(v);
+    } else if (omode == OUT_MAP) {
+        outp[pix * a.sect_n + scol] = f2bf(v);
+    } else {
+        outp[((size_t)b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v);
+    }
+}
+
+// BK: K elements per step (64, or 32 for channel counts that are not multiples of 64)
+template <int BM, int BN, int WGM, int WGN, int BK>
 __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     static_assert(WGM * WGN == 4, "four waves");
+    constexpr int LDT = BK + 8;                        // LDS row pitch in bf16: 16-byte aligned, not a power of two
+    constexpr int TPR = BK / 8;                        // threads per tile row (16 bytes each)
+    constexpr int RP = 256 / TPR;                      // tile rows covered per pass
     constexpr int WM = BM / WGM, WN = BN / WGN;        // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;          // 32x32 MFMA blocks per wave
     static_assert(TM >= 1 && TN >= 1, "wave tile too small");
-    constexpr int AL = (BM * 4 + 255) / 256;           // 16-byte A loads per thread per step
-    constexpr int BL = (BN * 4 + 255) / 256;
+    constexpr int AL = (BM + RP - 1) / RP;             // 16-byte A loads per thread per step
+    constexpr int BL = (BN + RP - 1) / RP;
 
     __shared__ __attribute__((aligned(16))) bf16_t As[2][BM][LDT];
     __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN][LDT];
     __shared__ RowInfo rinfo[BM];
-    extern __shared__ float2 gn_ss[];                  // [span][Cin] (scale, shift) when a.pro != PRO_NONE
+    extern __shared__ __attribute__((aligned(16))) float2 gn_ss[];                  // [span][Cin] (scale, shift) when a.pro != PRO_NONE
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
@@ -48,35 +89,55 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         }
         rinfo[r] = ri;
     }
-    // ---- GroupNorm scale/shift table for the batch elements this tile touches
+    // ---- K range of this workgroup
+    const int nsteps1 = a.K / BK;                      // main product
+    const int nsteps_total = nsteps1 + a.K2 / BK;      // + the 1x1 side product
+    int kc_begin = 0, kc_end = nsteps_total;
+    if (a.splits > 1) {
+        const int per = (nsteps_total + a.splits - 1) / a.splits;
+        kc_begin = blockIdx.z * per; kc_end = min(nsteps_total, kc_begin + per);
+    }
+    // ---- GroupNorm (scale, shift) of the channels this K range touches, for the batch elements of
+    // this tile, staged in LDS.  A range shorter than Cin is stored rotated: slot = (c - c_lo) mod Cin.
     const int b_first = m0 / a.Ma;
+    int c_lo = 0, clen = Cin;
     if (a.pro != PRO_NONE) {
+        const int k_lo = kc_begin * BK, k_hi = min(kc_end, nsteps1) * BK;
+        if (k_hi - k_lo < Cin) { c_lo = k_lo % Cin; clen = max(k_hi - k_lo, 0); }
         const int b_last = min(a.B - 1, (m0 + BM - 1) / a.Ma);
         const int cpg = Cin / a.G;
-        for (int e = tid; e < (b_last - b_first + 1) * Cin; e += 256) {
-            const int bb = b_first + e / Cin, c = e % Cin;
-            const float rs = a.gn_rstd[bb * a.G + c / cpg], mu = a.gn_mean[bb * a.G + c / cpg];
-            const float sc = rs * bf2f(a.gn_gamma[c]);
-            gn_ss[e] = make_float2(sc, bf2f(a.gn_beta[c]) - mu * sc);
+        for (int e = tid * 2; e < (b_last - b_first + 1) * clen; e += 512) {      // two entries (16 bytes) per thread
+            const int bb = b_first + e / clen;
+            int c = c_lo + e % clen; if (c >= Cin) c -= Cin;
+            if (a.gn_table) {
+                *reinterpret_cast<float4*>(&gn_ss[e]) = *reinterpret_cast<const float4*>(&a.gn_table[(size_t)bb * Cin + c]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const float rs = a.gn_rstd[bb * a.G + (c + q) / cpg], mu = a.gn_mean[bb * a.G + (c + q) / cpg];
+                    const float sc = rs * bf2f(a.gn_gamma[c + q]);
+                    gn_ss[e + q] = make_float2(sc, bf2f(a.gn_beta[c + q]) - mu * sc);
+                }
+            }
         }
     }
     __syncthreads();
 
-    // ---- per-thread load slots
-    const int seg = tid & 3;                           // which 8-element segment of the 32-wide K step
-    int arow[AL]; bool aok[AL]; int ab[AL], ay[AL], ax[AL];
+    // ---- per-thread load slots: TPR threads per tile row, RP rows per pass
+    const int seg = tid % TPR;                         // which 8-element segment of the K step
+    const int lrow = tid / TPR;
+    bool aok[AL]; int ab[AL], ay[AL], ax[AL];
 #pragma unroll
     for (int j = 0; j < AL; ++j) {
-        arow[j] = (tid >> 2) + 64 * j;
-        const bool in = arow[j] < BM;
-        const RowInfo ri = rinfo[in ? arow[j] : 0];
+        const bool in = lrow + RP * j < BM;
+        const RowInfo ri = rinfo[in ? lrow + RP * j : 0];
         aok[j] = in && ri.ok; ab[j] = ri.b; ay[j] = ri.y; ax[j] = ri.x;
     }
     // weight row of tile column j (GEGLU: first half of a wave's columns = value rows, second half = gate rows)
     int brow[BL]; bool bok[BL];
 #pragma unroll
     for (int j = 0; j < BL; ++j) {
-        const int col = (tid >> 2) + 64 * j;
+        const int col = lrow + RP * j;
         int wr; bool ok = col < BN;
         if (a.geglu) {
             const int wv = col / WN, jj = col % WN, half = jj / (WN / 2), cc = jj % (WN / 2);
@@ -88,79 +149,85 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         brow[j] = wr; bok[j] = ok;
     }
 
-    const int nsteps_total = a.K / BK;
-    int kc_begin = 0, kc_end = nsteps_total;
-    if (a.splits > 1) {
-        const int per = (nsteps_total + a.splits - 1) / a.splits;
-        kc_begin = blockIdx.z * per; kc_end = min(nsteps_total, kc_begin + per);
-    }
-    // running (tap, channel) position of the K cursor
-    int k0 = kc_begin * BK;
-    int tap = k0 / Cin, cc = k0 % Cin;
+    // running (tap, channel) position of the load cursor in the main product
+    int tap = 0, cc = 0;
+    if (kc_begin < nsteps1) { const int k0 = kc_begin * BK; tap = k0 / Cin; cc = k0 % Cin; }
 
-    uint4 ra[AL], rb[BL];
-    auto load_step = [&](int kc) {
-        // ---- A
+    // register FIFO: stage s holds the raw data of K step (kc_begin + i) with i % PF == s
+    uint4 ra[PF][AL], rb[PF][BL];
+    int st_cc[PF]; unsigned st_in[PF];                 // per stage: channel offset (for the prologue), in-image bits
+
+    // Loads of K step kc into FIFO stage s.  Every slot issues exactly one 16-byte load (rows or taps
+    // that do not exist read a harmless in-bounds address and are zeroed when the stage is stashed),
+    // so the number of loads in flight is the same on every path and the waits stay partial.
+    auto issue = [&](int kc, int s) {
+        const bool side = kc >= nsteps1;
+        const int c2 = (kc - nsteps1) * BK;
         const int ky = tap / a.ksize, kx = tap % a.ksize;
-        const bool second = cc >= a.C0;
-        const bf16_t* src = second ? a.a1 : a.a0;
-        const int Cs = second ? a.C1 : a.C0;
-        const int cs = (second ? cc - a.C0 : cc) + seg * 8;
+        const int ccur = side ? c2 : cc;
+        const int split = side ? a.S0 : a.C0;
+        const bool second = ccur >= split;
+        const bf16_t* src = side ? (second ? a.s1 : a.s0) : (second ? a.a1 : a.a0);
+        const int Cs = side ? (second ? a.S1 : a.S0) : (second ? a.C1 : a.C0);
+        const int cs = (second ? ccur - split : ccur) + seg * 8;
+        const int Hs = side ? a.Ho : a.Hin, Ws = side ? a.Wo : a.Win;
+        unsigned inbits = 0;
 #pragma unroll
         for (int j = 0; j < AL; ++j) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (aok[j]) {
-                if (a.a_compact) {
-                    v = *reinterpret_cast<const uint4*>(src + (size_t)(m0 + arow[j]) * Cs + cs);
+            size_t off = 0; bool in = aok[j];
+            if (a.a_compact) {
+                off = (size_t)(m0 + lrow + RP * j) * Cs;
+            } else {
+                int iy, ix;
+                if (side) { iy = ay[j]; ix = ax[j]; }
+                else if (a.ups) {
+                    const int uy = ay[j] + ky - pad, ux = ax[j] + kx - pad;
+                    in = in && uy >= 0 && uy < 2 * a.Hin && ux >= 0 && ux < 2 * a.Win;
+                    iy = uy >> 1; ix = ux >> 1;
                 } else {
-                    int iy, ix; bool in;
-                    if (a.ups) {
-                        const int uy = ay[j] + ky - pad, ux = ax[j] + kx - pad;
-                        in = uy >= 0 && uy < 2 * a.Hin && ux >= 0 && ux < 2 * a.Win;
-                        iy = uy >> 1; ix = ux >> 1;
-                    } else {
-                        iy = ay[j] * a.stride + ky - pad; ix = ax[j] * a.stride + kx - pad;
-                        in = iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win;
-                    }
-                    if (in) {
-                        v = *reinterpret_cast<const uint4*>(src + (((size_t)ab[j] * a.Hin + iy) * a.Win + ix) * Cs + cs);
-                        if (a.pro != PRO_NONE) {
-                            const float2* ss = gn_ss + (ab[j] - b_first) * Cin + cc + seg * 8;
-                            unsigned w4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float2 s0 = ss[2 * e], s1 = ss[2 * e + 1];
-                                float u0 = __uint_as_float(w4[e] << 16) * s0.x + s0.y;
-                                float u1 = __uint_as_float(w4[e] & 0xffff0000u) * s1.x + s1.y;
-                                if (a.pro == PRO_GN_SILU) { u0 = silu_f(u0); u1 = silu_f(u1); }
-                                w4[e] = (unsigned)f2bf(u0) | ((unsigned)f2bf(u1) << 16);
-                            }
-                            v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-                        }
-                    }
+                    iy = ay[j] * a.stride + ky - pad; ix = ax[j] * a.stride + kx - pad;
+                    in = in && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win;
                 }
+                off = (((size_t)ab[j] * Hs + iy) * Ws + ix) * Cs;
             }
-            ra[j] = v;
+            off = in ? off + cs : 0;
+            ra[s][j] = *reinterpret_cast<const uint4*>(src + off);
+            inbits |= (in ? 1u : 0u) << j;
         }
-        // ---- B
+        const bf16_t* wsrc = side ? a.w2 : a.w;
+        const size_t wk = side ? (size_t)a.K2 : (size_t)a.K;
+        const size_t wc = (side ? (size_t)c2 : (size_t)kc * BK) + seg * 8;
 #pragma unroll
-        for (int j = 0; j < BL; ++j) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (bok[j]) v = *reinterpret_cast<const uint4*>(a.w + (size_t)brow[j] * a.K + (size_t)kc * BK + seg * 8);
-            rb[j] = v;
-        }
-        cc += BK;
-        if (cc >= Cin) { cc = 0; ++tap; }
+        for (int j = 0; j < BL; ++j) rb[s][j] = *reinterpret_cast<const uint4*>(wsrc + (bok[j] ? (size_t)brow[j] * wk + wc : 0));
+        st_cc[s] = side ? -1 : (cc >= c_lo ? cc - c_lo : cc - c_lo + Cin);     // slot in the staged table
+        st_in[s] = inbits;
+        if (!side) { cc += BK; if (cc >= Cin) { cc = 0; ++tap; } }
     };
-    auto store_step = [&](int buf) {
+    // registers of stage s -> LDS buffer `buf`, applying the GroupNorm(+SiLU) prologue to in-image elements
+    auto stash = [&](int s, int buf) {
 #pragma unroll
-        for (int j = 0; j < AL; ++j)
-            if (arow[j] < BM) *reinterpret_cast<uint4*>(&As[buf][arow[j]][seg * 8]) = ra[j];
+        for (int j = 0; j < AL; ++j) {
+            uint4 v = ra[s][j];
+            const bool in = (st_in[s] >> j) & 1u;
+            if (!in) v = make_uint4(0, 0, 0, 0);
+            if (a.pro != PRO_NONE && st_cc[s] >= 0 && in) {
+                const float2* ss = gn_ss + (ab[j] - b_first) * clen + st_cc[s] + seg * 8;
+                unsigned w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int j = 0; j < BL; ++j) {
-            const int col = (tid >> 2) + 64 * j;
-            if (col < BN) *reinterpret_cast<uint4*>(&Bs[buf][col][seg * 8]) = rb[j];
+                for (int e = 0; e < 4; ++e) {
+                    const float2 s0 = ss[2 * e], s1 = ss[2 * e + 1];
+                    float u0 = __uint_as_float(w4[e] << 16) * s0.x + s0.y;
+                    float u1 = __uint_as_float(w4[e] & 0xffff0000u) * s1.x + s1.y;
+                    if (a.pro == PRO_GN_SILU) { u0 = silu_f(u0); u1 = silu_f(u1); }
+                    w4[e] = (unsigned)f2bf(u0) | ((unsigned)f2bf(u1) << 16);
+                }
+                v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            }
+            if (lrow + RP * j < BM) *reinterpret_cast<uint4*>(&As[buf][lrow + RP * j][seg * 8]) = v;
         }
+#pragma unroll
+        for (int j = 0; j < BL; ++j)
+            if (lrow + RP * j < BN) *reinterpret_cast<uint4*>(&Bs[buf][lrow + RP * j][seg * 8]) = bok[j] ? rb[s][j] : make_uint4(0, 0, 0, 0);
     };
 
     f32x16_t acc[TM][TN];
@@ -171,14 +238,20 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (kc_begin < kc_end) {
-        load_step(kc_begin);
-        store_step(0);
-        __syncthreads();
-        for (int kc = kc_begin; kc < kc_end; ++kc) {
-            const int buf = (kc - kc_begin) & 1;
-            const bool more = kc + 1 < kc_end;
-            if (more) load_step(kc + 1);
+    // fill the FIFO (steps past the end re-read the last step: never used, keeps the load count uniform)
+    const int kc_last = kc_end - 1;
+#pragma unroll
+    for (int s = 0; s < PF; ++s) issue(min(kc_begin + s, kc_last), s);
+
+    for (int kc0 = kc_begin; kc0 < kc_end; kc0 += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            const int kc = kc0 + s;
+            if (kc >= kc_end) break;                   // uniform across the workgroup
+            const int buf = s & 1;                     // PF is even: the parity of kc - kc_begin
+            stash(s, buf);
+            issue(min(kc + PF, kc_last), s);
+            lds_barrier();
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 bf16x8_t fa[TM], fb[TN];
@@ -194,59 +267,51 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
-            if (more) store_step(buf ^ 1);
-            __syncthreads();
         }
     }
+    if (kc_begin >= kc_end) { /* an empty split contributes zeros */ }
 
-    // ---- split-K: park partial sums; the last workgroup of a tile sums them in split order
+    // ---- split-K: park this workgroup's partial sums as partial[z][row][weight row]; a second small
+    // kernel adds them up in split order and applies the epilogue (no cross-workgroup hand-over inside
+    // this kernel: that would need device-scope fences, which write back and invalidate the L2s).
     if (a.splits > 1) {
-        const int tile_id = blockIdx.y * gridDim.x + blockIdx.x;
-        float* mine = a.partial + ((size_t)tile_id * a.splits + blockIdx.z) * (BM * BN);
+        const int ncols = a.geglu ? 2 * a.N : a.N;
+        float* P = a.partial + (size_t)blockIdx.z * rows * ncols;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) {
+            int wr;
+            if (a.geglu) {
+                const int half = j / (TN / 2 > 0 ? TN / 2 : 1), jj = j % (TN / 2 > 0 ? TN / 2 : 1);
+                const int oc = blockIdx.y * (BN / 2) + (wave % WGN) * (WN / 2) + jj * 32 + (lane & 31);
+                wr = oc < a.N ? oc + half * a.N : -1;
+            } else {
+                wr = blockIdx.y * BN + wn0 + j * 32 + (lane & 31);
+                if (wr >= a.N) wr = -1;
+            }
+            if (wr < 0) continue;
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    mine[((wave * TM + i) * TN + j) * 1024 + e * 64 + lane] = acc[i][j][e];
-        __threadfence();
-        __syncthreads();
-        __shared__ int s_last;
-        if (tid == 0) s_last = atomicAdd(a.counters + tile_id, 1) == a.splits - 1;
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
-        const float* base = a.partial + (size_t)tile_id * a.splits * (BM * BN);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    float s = 0.f;
-                    for (int z = 0; z < a.splits; ++z)
-                        s += __builtin_nontemporal_load(base + (size_t)z * (BM * BN) + ((wave * TM + i) * TN + j) * 1024 + e * 64 + lane);
-                    acc[i][j][e] = s;
+                    const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    if (m0 + r < rows) P[(size_t)(m0 + r) * ncols + wr] = acc[i][j][e];
                 }
-        if (tid == 0) a.counters[tile_id] = 0;             // ready for the next launch
+        }
+        return;
     }
 
     // ---- epilogue
-    constexpr int TNE = TN;   // geglu pairs block j with j + TN/2
-    const int n_out_blocks = a.geglu ? TNE / 2 : TNE;
+    const int n_out_blocks = a.geglu ? TN / 2 : TN;       // GEGLU pairs block j (value) with block j + TN/2 (gate)
 #pragma unroll
-    for (int j = 0; j < TNE; ++j) {
+    for (int j = 0; j < TN; ++j) {
         if (j >= n_out_blocks) break;
         int col;
         if (a.geglu) col = blockIdx.y * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
         else col = blockIdx.y * BN + wn0 + j * 32 + (lane & 31);
         if (col >= a.N) continue;
-        const float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
+        float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
+        if (a.bias2) bias_v += bf2f(a.bias2[col]);
         const float bias_g = (a.geglu && a.bias) ? bf2f(a.bias[col + a.N]) : 0.f;
-        const int sect = col / a.sect_n, scol = col % a.sect_n;
-        bf16_t* outp = a.out[sect];
-        const int omode = a.out_mode[sect];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -256,61 +321,155 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
                 if (!ri.ok) continue;
                 float v = acc[i][j][e] + bias_v;
                 if (a.geglu) {
-                    const float g = acc[i][(j + TNE / 2) % TNE][e] + bias_g;
+                    const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
                     v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
                 }
-                if (a.temb) v += a.temb[ri.b * a.temb_stride + col];
-                const size_t pix = ((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x;
-                if (a.res) v += bf2f(a.res_compact ? a.res[(size_t)(m0 + r) * a.N + col] : a.res[pix * a.N + col]);
-                if (omode == OUT_COMPACT) outp[(size_t)(m0 + r) * a.sect_n + scol] = f2bf(v);
-                else if (omode == OUT_MAP) outp[pix * a.sect_n + scol] = f2bf(v);
-                else outp[((size_t)ri.b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + (size_t)ri.y * a.Wo + ri.x] = f2bf(v);
+                epilogue_store(a, m0 + r, ri.b, ri.y, ri.x, col, v);
             }
         }
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
-static int launch_cfg(const IgemmArgs& a, hipStream_t st) {
+// Second half of a split-K launch: one thread per output element sums the parked partials in split
+// order (deterministic) and applies the epilogue.
+__global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
+    const int rows = a.B * a.Ma;
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)rows * a.N) return;
+    const int gm = (int)(i / a.N), col = (int)(i % a.N);
+    const int ncols = a.geglu ? 2 * a.N : a.N;
+    const size_t stride = (size_t)rows * ncols;
+    const float* P = a.partial + (size_t)gm * ncols + col;
+    float v = a.bias ? bf2f(a.bias[col]) : 0.f;
+    if (a.bias2) v += bf2f(a.bias2[col]);
+    for (int z = 0; z < a.splits; ++z) v += P[z * stride];
+    if (a.geglu) {
+        float g = a.bias ? bf2f(a.bias[col + a.N]) : 0.f;
+        for (int z = 0; z < a.splits; ++z) g += P[z * stride + a.N];
+        v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
+    }
+    int y = 0, x = gm % a.Ma;
+    const int b = gm / a.Ma;
+    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
+    epilogue_store(a, gm, b, y, x, col, v);
+}
+
+// (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given statistics
+__global__ void gn_table_kernel(const float* __restrict__ mean, const float* __restrict__ rstd, const bf16_t* __restrict__ gamma,
+                                const bf16_t* __restrict__ beta, int B, int Cin, int G, float2* __restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * Cin) return;
+    const int b = i / Cin, c = i % Cin, g = c / (Cin / G);
+    const float sc = rstd[b * G + g] * bf2f(gamma[c]);
+    out[i] = make_float2(sc, bf2f(beta[c]) - mean[b * G + g] * sc);
+}
+
+
+// ---------------------------------------------------------------------------
+// host side: tile shape and K split per problem
+// ---------------------------------------------------------------------------
+size_t igemm_workspace_bytes() { return IGEMM_GN_TABLE_BYTES + IGEMM_PARTIAL_BYTES; }
+
+int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hipStream_t st) {
+    (void)st;
+    out->partial = nullptr; out->partial_bytes = 0; out->gn_table = nullptr; out->gn_table_bytes = 0;
+    if (!workspace || bytes < igemm_workspace_bytes()) return FISE_OK;          // no split-K without it
+    out->gn_table = (float2*)workspace; out->gn_table_bytes = IGEMM_GN_TABLE_BYTES;
+    out->partial = (float*)((char*)workspace + IGEMM_GN_TABLE_BYTES);
+    out->partial_bytes = IGEMM_PARTIAL_BYTES;
+    return FISE_OK;
+}
+
+// How many workgroups share the K loop of one output tile.  A CU can only pull a few tens of GB/s
+// on its own, so what matters is that every CU streams part of the operands: aim at two to three
+// workgroups per CU, keep at least two K steps per workgroup, and bound the parked partials.
+template <int BM, int BN, int BK>
+static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) {
+    if (!ws || !ws->partial) return 1;
+    const int rows = a.B * a.Ma;
+    const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
+    const int nsteps = (a.K + a.K2) / BK;
+    static const int target = [] { const char* e = getenv("FISE_SPLIT_TARGET"); return e ? atoi(e) : 640; }();
+    if (tiles * 2 > target || nsteps < 4) return 1;
+    const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
+    int s = (target + tiles - 1) / tiles;
+    s = std::min(s, nsteps / 2);
+    s = std::min<int>(s, (int)(ws->partial_bytes / out_bytes));
+    // partial traffic (written once, read once) should stay below the operand traffic of the launch
+    const double op_bytes = 2.0 * (double)(a.K + a.K2) * ((double)ncols * ceil_div(rows, BM) + (double)rows * ceil_div(ncols, BN));
+    while (s > 1 && 2.0 * s * out_bytes > op_bytes) --s;
+    return std::max(s, 1);
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK>
+static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipStream_t st) {
     const int rows = a.B * a.Ma;
     const int ncols = a.geglu ? 2 * a.N : a.N;
+    a.splits = pick_splits<BM, BN, BK>(a, ws, ncols);
+    if (a.splits > 1) a.partial = ws->partial;
     dim3 grid(ceil_div(rows, BM), ceil_div(ncols, BN), a.splits);
     size_t shmem = 0;
     if (a.pro != PRO_NONE) {
         const int span = std::min(a.B, (BM - 1) / a.Ma + 2);
-        shmem = (size_t)span * (a.C0 + a.C1) * sizeof(float2);
-        constexpr size_t kMaxDyn = 112 * 1024;      // 160 KB of LDS per workgroup minus the static tiles
+        const int Cin = a.C0 + a.C1;
+        const int per = ceil_div((a.K + a.K2) / BK, a.splits);
+        shmem = (size_t)span * std::min(Cin, per * BK) * sizeof(float2);
+        if (ws && ws->gn_table && (size_t)a.B * Cin * sizeof(float2) <= ws->gn_table_bytes) {
+            hipLaunchKernelGGL(gn_table_kernel, dim3(ceil_div(a.B * Cin, 256)), dim3(256), 0, st, a.gn_mean, a.gn_rstd, a.gn_gamma,
+                               a.gn_beta, a.B, Cin, a.G, ws->gn_table);
+            FISE_CHECK_LAUNCH("igemm gn table");
+            a.gn_table = ws->gn_table;
+        }
+        constexpr size_t kMaxDyn = 64 * 1024;
         if (shmem > kMaxDyn) return fail(FISE_ERR_SHAPE, "igemm: GroupNorm table of %zu bytes does not fit in LDS", shmem);
-        static bool raised = false;                 // once: allow more than the default 64 KB of dynamic LDS
+        static bool raised = false;                 // once per instantiation: static tiles + table may exceed 64 KB
         if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN, BK>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDyn) != hipSuccess)
                 return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
             raised = true;
         }
     }
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN>), grid, dim3(256), shmem, st, a);
+    const double flops = 2.0 * rows * (double)ncols * ((double)a.K + a.K2);
+    const double bytes = 2.0 * ((double)ncols * ((double)a.K + a.K2) + (double)rows * (a.C0 + a.C1 + a.S0 + a.S1) + (double)rows * a.N);
+    ProfileScope prof(prof_kind, flops, bytes, st);
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK>), grid, dim3(256), shmem, st, a);
     FISE_CHECK_LAUNCH("igemm");
+    if (a.splits > 1) {
+        const long long n = (long long)rows * a.N;
+        hipLaunchKernelGGL(igemm_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+        FISE_CHECK_LAUNCH("igemm reduce");
+    }
     return FISE_OK;
 }
 
-size_t igemm_workspace_bytes(int rows, int N, int K) {
-    (void)rows; (void)N; (void)K;
-    return 0;
+template <int BM, int BN, int WGM, int WGN>
+static int launch_cfg(const IgemmArgs& a, const IgemmWorkspace* ws, int prof_kind, hipStream_t st) {
+    const bool k64 = a.C0 % 64 == 0 && a.C1 % 64 == 0 && a.S0 % 64 == 0 && a.S1 % 64 == 0;
+    if (k64) return launch_bk<BM, BN, WGM, WGN, 64>(a, ws, prof_kind, st);
+    return launch_bk<BM, BN, WGM, WGN, 32>(a, ws, prof_kind, st);
 }
 
-int launch_igemm(const IgemmArgs& a, hipStream_t st) {
+int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     const int rows = a.B * a.Ma;
     if (rows <= 0) return FISE_OK;
     const int Cin = a.C0 + a.C1;
     if (a.K != a.ksize * a.ksize * Cin) return fail(FISE_ERR_SHAPE, "igemm: K=%d != %d*%d*%d", a.K, a.ksize, a.ksize, Cin);
-    if (a.C0 % BK || a.C1 % BK) return fail(FISE_ERR_ALIGN, "igemm: channel counts %d,%d must be multiples of %d", a.C0, a.C1, BK);
+    if (a.C0 % 32 || a.C1 % 32) return fail(FISE_ERR_ALIGN, "igemm: channel counts %d,%d must be multiples of 32", a.C0, a.C1);
     if (a.a_compact && (a.ksize != 1 || a.C1 != 0)) return fail(FISE_ERR_SHAPE, "igemm: compact A needs ksize 1, one source");
     if (a.pro != PRO_NONE && (a.G < 1 || Cin % a.G)) return fail(FISE_ERR_SHAPE, "igemm: Cin=%d %% G=%d", Cin, a.G);
     if (a.nsect < 1 || a.nsect > 3 || a.nsect * a.sect_n != a.N) return fail(FISE_ERR_SHAPE, "igemm: sections");
-    if (a.splits != 1) return fail(FISE_ERR_SHAPE, "igemm: split-K not enabled");
-    if (a.geglu) return launch_cfg<64, 128, 2, 2>(a, st);
-    return launch_cfg<64, 64, 2, 2>(a, st);
+    if (a.K2 != a.S0 + a.S1 || a.S0 % 32 || a.S1 % 32 || (a.K2 > 0 && (!a.w2 || !a.s0 || a.a_compact || a.stride != 1 || a.ups)))
+        return fail(FISE_ERR_SHAPE, "igemm: side product");
+    const bool wide = rows >= 4096 && a.N >= 128;          // dense-sized problems: 128x128 tiles
+    if (a.geglu) {
+        if (wide) return launch_cfg<128, 128, 2, 2>(a, ws, PROF_IGEMM_WIDE, st);
+        if (rows <= 32) return launch_cfg<32, 256, 1, 4>(a, ws, PROF_IGEMM_GEGLU, st);
+        return launch_cfg<64, 128, 2, 2>(a, ws, PROF_IGEMM_GEGLU, st);
+    }
+    if (wide) return launch_cfg<128, 128, 2, 2>(a, ws, PROF_IGEMM_WIDE, st);
+    if (rows <= 32) return launch_cfg<32, 128, 1, 4>(a, ws, PROF_IGEMM, st);
+    return launch_cfg<64, 64, 2, 2>(a, ws, PROF_IGEMM, st);
 }
 
 }  // namespace fise

@@ -80,14 +80,15 @@ __global__ void masked_gn_silu_kernel(const T* __restrict__ x, const float* __re
 
 // LayerNorm of rows -> compact out[rows, C] (bf16), one wave per row, two passes (mean,
 // then centred variance) in float.  With tile_idx the rows are gathered from a token map.
-__global__ __launch_bounds__(256) void ln_rows_kernel(const bf16_t* __restrict__ in, int rows, int C,
+template <typename T>
+__global__ __launch_bounds__(256) void ln_rows_kernel(const T* __restrict__ in, int rows, int C,
                                                       const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta,
                                                       float eps, bf16_t* __restrict__ out, const int* __restrict__ tile_idx,
                                                       int tile, int tiles_w, int H, int W, int Ma) {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (row >= rows) return;
-    const bf16_t* r;
+    const T* r;
     if (tile_idx) {
         int py, px;
         active_pixel(tile_idx, row % Ma, tile, tiles_w, py, px);
@@ -96,22 +97,27 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const bf16_t* __restrict__
         r = in + (size_t)row * C;
     }
     float s = 0.f;
-    for (int c = lane; c < C; c += 64) s += bf2f(r[c]);
+    for (int c = lane; c < C; c += 64) s += Elem<T>::ld(r + c);
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
     const float mu = s / C;
     float q = 0.f;
-    for (int c = lane; c < C; c += 64) { const float d = bf2f(r[c]) - mu; q += d * d; }
+    for (int c = lane; c < C; c += 64) { const float d = Elem<T>::ld(r + c) - mu; q += d * d; }
     for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
     const float rs = rsqrtf(q / C + eps);
     for (int c = lane; c < C; c += 64)
-        out[(size_t)row * C + c] = f2bf((bf2f(r[c]) - mu) * rs * bf2f(gamma[c]) + bf2f(beta[c]));
+        out[(size_t)row * C + c] = f2bf((Elem<T>::ld(r + c) - mu) * rs * bf2f(gamma[c]) + bf2f(beta[c]));
 }
 
-int launch_ln_rows(const void* in, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
+int launch_ln_rows(const void* in, int in_f32, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
                    const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st) {
     if (rows <= 0) return FISE_OK;
-    hipLaunchKernelGGL(ln_rows_kernel, dim3(ceil_div(rows, 4)), dim3(256), 0, st, (const bf16_t*)in, rows, C,
-                       (const bf16_t*)gamma, (const bf16_t*)beta, eps, (bf16_t*)out, tile_idx, tile, tiles_w, H, W, Ma);
+    const dim3 grid(ceil_div(rows, 4)), block(256);
+    if (in_f32)
+        hipLaunchKernelGGL(ln_rows_kernel<float>, grid, block, 0, st, (const float*)in, rows, C, (const bf16_t*)gamma,
+                           (const bf16_t*)beta, eps, (bf16_t*)out, tile_idx, tile, tiles_w, H, W, Ma);
+    else
+        hipLaunchKernelGGL(ln_rows_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)in, rows, C, (const bf16_t*)gamma,
+                           (const bf16_t*)beta, eps, (bf16_t*)out, tile_idx, tile, tiles_w, H, W, Ma);
     FISE_CHECK_LAUNCH("layernorm rows");
     return FISE_OK;
 }

@@ -10,6 +10,12 @@
 
 namespace fise {
 IgemmArgs linear_args(const void* A, int rows_per_b, int B, int Cin, const void* W, const void* bias, int N);
+int run_conv(const void* a0, int C0, int B, int Hin, int Win, int stride, int ups, const void* w, const void* bias, int N,
+             const int* idx, int n_active, int tile, void* out, const IgemmWorkspace* iw, hipStream_t st);
+int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st);
+int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st);
+size_t resnet_ws_bytes(const fise_resnet_args* a);
+size_t transformer_ws_bytes(const fise_transformer_args* a);
 }
 
 using namespace fise;
@@ -211,13 +217,11 @@ extern "C" size_t fise_unet_cache_bytes(const fise_unet* u) { return u ? u->cach
 extern "C" size_t fise_unet_ctxkv_bytes(const fise_unet* u) { return u ? u->ctxkv_bytes : 0; }
 
 namespace {
-struct WsLayout { size_t idx_full, emb_a, emb_b, temb, h, n, q, o, ff, gn, total; };
+struct WsLayout { size_t idx_full, emb_a, emb_b, temb, block, igemm, total; };
 
-// rows of level l for `n_tiles` active tiles (per batch element)
-inline int64_t level_rows(const fise_unet_desc& d, int l, int n_tiles, int base_tile, bool dense) {
-    if (dense) return (int64_t)(d.H >> l) * (d.W >> l);
-    const int t = base_tile >> l;
-    return (int64_t)n_tiles * t * t;
+// active tiles of level l: the caller's list, or every tile when the level runs dense
+inline int level_tiles(const fise_unet_desc& d, int base_tile, int n_active, bool dense) {
+    return dense ? (d.H / base_tile) * (d.W / base_tile) : n_active;
 }
 
 WsLayout ws_layout(const fise_unet* u, int n_tiles, int base_tile, const int* level_dense) {
@@ -230,22 +234,29 @@ WsLayout ws_layout(const fise_unet* u, int n_tiles, int base_tile, const int* le
     const int te = 4 * d.base;
     w.emb_a = take((size_t)d.B * te * 4); w.emb_b = take((size_t)d.B * te * 4);
     w.temb = take((size_t)d.B * u->temb_total * 4);
-    int64_t max_rc = 0, max_c = 0;
+    size_t blk = 256;
     for (const Module& m : u->mods) {
         const bool dense = level_dense && level_dense[m.lvl];
-        const int64_t rows = d.B * level_rows(d, m.lvl, n_tiles, base_tile, dense);
-        if (m.kind == K_TR) max_rc = std::max(max_rc, rows * m.cout);
-        max_c = std::max<int64_t>(max_c, m.cin + m.cskip);
+        if (m.kind == K_TR) {
+            fise_transformer_args t{};
+            t.B = d.B; t.H = d.H >> m.lvl; t.W = d.W >> m.lvl; t.C = m.cout; t.G = d.groups;
+            t.n_active = level_tiles(d, base_tile, n_tiles, dense); t.tile = base_tile >> m.lvl;
+            blk = std::max(blk, transformer_ws_bytes(&t));
+        } else if (m.kind == K_RES) {
+            fise_resnet_args r{};
+            r.B = d.B; r.H = d.H >> m.lvl; r.W = d.W >> m.lvl; r.G = d.groups;
+            blk = std::max(blk, resnet_ws_bytes(&r));
+        }
     }
-    w.h = take(max_rc * 2); w.n = take(max_rc * 2); w.q = take(max_rc * 2); w.o = take(max_rc * 2); w.ff = take(max_rc * 4 * 2);
-    w.gn = take(fise_groupnorm_stats_workspace_bytes(d.B, d.H, d.W, d.groups));
+    w.block = take(blk);
+    w.igemm = take(igemm_workspace_bytes());
     w.total = c;
     return w;
 }
 }  // namespace
 
 extern "C" size_t fise_unet_workspace_bytes(const fise_unet* u, int max_active_tiles, int base_tile) {
-    if (!u || base_tile < 1 || max_active_tiles < 0) return 0;
+    if (!u || base_tile < 1 || max_active_tiles < 0 || (base_tile >> (u->d.n_levels - 1)) < 1) return 0;
     return ws_layout(u, max_active_tiles, base_tile, nullptr).total;
 }
 
@@ -264,8 +275,17 @@ extern "C" int fise_unet_context_kv(const fise_unet* u, const void* weights, con
         g.nsect = 2; g.sect_n = C; g.Ho = 1; g.Wo = u->n_stride;
         g.out[0] = (bf16_t*)((char*)ctxkv + u->off(2, m.name + ".ctx_k")); g.out_mode[0] = OUT_COMPACT;
         g.out[1] = (bf16_t*)((char*)ctxkv + u->off(2, m.name + ".ctx_vt")); g.out_mode[1] = OUT_TOKENS_T;
-        if (int e = launch_igemm(g, st)) return e;
+        if (int e = launch_igemm(g, nullptr, st)) return e;
     }
+    return FISE_OK;
+}
+
+extern "C" int fise_unet_num_modules(const fise_unet* u) { return u ? (int)u->mods.size() : 0; }
+
+extern "C" int fise_unet_module_name(const fise_unet* u, int i, char* name) {
+    if (!u || !name) return fail(FISE_ERR_NULL, "fise_unet_module_name: null pointer");
+    if (i < 0 || i >= (int)u->mods.size()) return fail(FISE_ERR_CAPACITY, "fise_unet_module_name: index %d", i);
+    snprintf(name, 64, "%s", u->mods[i].name.c_str());
     return FISE_OK;
 }
 
@@ -273,17 +293,27 @@ extern "C" int fise_masked_unet_step(const fise_unet* u, const void* weights, vo
                                      const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
                                      int base_tile, int stats_mode, const int* level_dense, void* workspace,
                                      size_t workspace_bytes, void* stream) {
+    return fise_masked_unet_modules(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_active, base_tile, stats_mode,
+                                    level_dense, 0, u ? (int)u->mods.size() : 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cache, const void* latent,
+                                        const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
+                                        int base_tile, int stats_mode, const int* level_dense, int first_module,
+                                        int n_modules, void* workspace, size_t workspace_bytes, void* stream) {
     if (!u || !weights || !cache || !latent || !t_sin || !ctxkv) return fail(FISE_ERR_NULL, "fise_masked_unet_step: null pointer");
     const fise_unet_desc& d = u->d;
     const int nl = d.n_levels;
     if (base_tile < 1 || base_tile % (1 << (nl - 1)) || d.H % base_tile || d.W % base_tile)
         return fail(FISE_ERR_SHAPE, "fise_masked_unet_step: base_tile %d must divide H, W and be a multiple of %d", base_tile, 1 << (nl - 1));
-    const int tiles_w = d.W / base_tile, tiles_total = tiles_w * (d.H / base_tile);
+    const int tiles_total = (d.W / base_tile) * (d.H / base_tile);
     if (n_active < 0 || n_active > tiles_total) return fail(FISE_ERR_CAPACITY, "fise_masked_unet_step: n_active %d of %d tiles", n_active, tiles_total);
     if (stats_mode != FISE_STATS_CACHED && stats_mode != FISE_STATS_FRESH) return fail(FISE_ERR_SHAPE, "fise_masked_unet_step: stats_mode %d", stats_mode);
     bool any_dense = false;
     if (level_dense) for (int l = 0; l < nl; ++l) any_dense |= level_dense[l] != 0;
-    if (n_active == 0 && !any_dense) return FISE_OK;
+    if (first_module < 0 || n_modules < 0 || first_module + n_modules > (int)u->mods.size())
+        return fail(FISE_ERR_CAPACITY, "fise_masked_unet_modules: modules [%d, %d) of %zu", first_module, first_module + n_modules, u->mods.size());
+    if ((n_active == 0 && !any_dense) || n_modules == 0) return FISE_OK;
     if (n_active > 0 && !tile_idx) return fail(FISE_ERR_NULL, "fise_masked_unet_step: null tile_idx");
     const WsLayout wl = ws_layout(u, n_active, base_tile, level_dense);
     if (!workspace || workspace_bytes < wl.total) return fail(FISE_ERR_CAPACITY, "fise_masked_unet_step: workspace %zu < %zu bytes", workspace_bytes, wl.total);
@@ -293,65 +323,38 @@ extern "C" int fise_masked_unet_step(const fise_unet* u, const void* weights, vo
     hipStream_t st = as_stream(stream);
     const bf16_t* Wt = (const bf16_t*)weights;
     char* cb = (char*)cache; char* ws = (char*)workspace; const char* kv = (const char*)ctxkv;
-    auto Wp = [&](const std::string& n) { return Wt + u->off(0, n); };
-    auto Cp = [&](const std::string& n) { return (bf16_t*)(cb + u->off(1, n)); };
+    auto Wp = [&](const std::string& n) { return (const void*)(Wt + u->off(0, n)); };
+    auto Cp = [&](const std::string& n) { return (void*)(cb + u->off(1, n)); };
     auto Cf = [&](const std::string& n) { return (float*)(cb + u->off(1, n)); };
     int* idx_full = (int*)(ws + wl.idx_full);
     float* emb_a = (float*)(ws + wl.emb_a); float* emb_b = (float*)(ws + wl.emb_b); float* temb = (float*)(ws + wl.temb);
-    bf16_t* hb = (bf16_t*)(ws + wl.h); bf16_t* nb = (bf16_t*)(ws + wl.n); bf16_t* qb = (bf16_t*)(ws + wl.q);
-    bf16_t* ob = (bf16_t*)(ws + wl.o); bf16_t* fb = (bf16_t*)(ws + wl.ff);
-    void* gnws = ws + wl.gn;
+    void* blockws = ws + wl.block;
     const int B = d.B, G = d.groups, te = 4 * d.base;
+    const int fresh = stats_mode == FISE_STATS_FRESH;
 
+    IgemmWorkspace iws; const IgemmWorkspace* iw = &iws;
+    if (int e = igemm_workspace_init(ws + wl.igemm, igemm_workspace_bytes(), &iws, st)) return e;
     if (any_dense) if (int e = launch_iota(idx_full, tiles_total, st)) return e;
     // time embedding MLP and the stacked per-block projections (dense, a few rows)
     if (int e = launch_small_linear(t_sin, B, d.base, Wp("time.l1.w"), Wp("time.l1.b"), te, 1, emb_a, st)) return e;
     if (int e = launch_small_linear(emb_a, B, te, Wp("time.l2.w"), Wp("time.l2.b"), te, 1, emb_b, st)) return e;
-    {
-        const Module* first = nullptr;
-        for (const Module& m : u->mods) if (m.kind == K_RES) { first = &m; break; }
-        if (first)
-            if (int e = launch_small_linear(emb_b, B, te, Wp(first->name + ".temb.w"), Wp(first->name + ".temb.b"), u->temb_total, 0, temb, st)) return e;
-    }
+    for (const Module& m : u->mods)
+        if (m.kind == K_RES) {
+            if (int e = launch_small_linear(emb_b, B, te, Wp(m.name + ".temb.w"), Wp(m.name + ".temb.b"), u->temb_total, 0, temb, st)) return e;
+            break;
+        }
 
-    for (const Module& m : u->mods) {
+    for (int mi = first_module; mi < first_module + n_modules; ++mi) {
+        const Module& m = u->mods[mi];
         const bool dense = level_dense && level_dense[m.lvl];
         const int* idx = dense ? idx_full : tile_idx;
         const int nt = dense ? tiles_total : n_active;
         if (nt == 0) continue;
         const int tile = base_tile >> m.lvl;
         const int H = d.H >> m.lvl, W = d.W >> m.lvl;
-        const int Ma = nt * tile * tile;
         const std::string& n = m.name;
-        const bf16_t* in0 = m.in_map.empty() ? (const bf16_t*)latent : Cp(m.in_map);
-        const bf16_t* in1 = m.skip_map.empty() ? nullptr : Cp(m.skip_map);
-
-        // a conv-shaped launch on maps of this module's level
-        auto conv = [&](const bf16_t* a0, const bf16_t* a1, int C0, int C1, int Hin, int Win, int ks, int stride, int ups,
-                        const bf16_t* w, const bf16_t* bias, int N) {
-            IgemmArgs g{};
-            g.a0 = a0; g.a1 = a1; g.C0 = C0; g.C1 = C1; g.a_compact = 0; g.Hin = Hin; g.Win = Win; g.ksize = ks; g.stride = stride; g.ups = ups;
-            g.tile_idx = idx; g.tile = tile; g.tiles_w = tiles_w; g.Ho = H; g.Wo = W; g.B = B; g.Ma = Ma;
-            g.pro = PRO_NONE; g.G = G;
-            g.w = w; g.N = N; g.K = ks * ks * (C0 + C1); g.geglu = 0; g.bias = bias; g.temb = nullptr; g.temb_stride = 0;
-            g.res = nullptr; g.res_compact = 0; g.nsect = 1; g.sect_n = N; g.out_mode[0] = OUT_MAP;
-            g.splits = 1;
-            return g;
-        };
-        auto with_gn = [&](IgemmArgs& g, const std::string& key, const char* gname, const char* bname, bool silu) {
-            g.pro = silu ? PRO_GN_SILU : PRO_GN;
-            g.gn_mean = Cf(key + ".mean"); g.gn_rstd = Cf(key + ".rstd"); g.gn_gamma = Wp(n + gname); g.gn_beta = Wp(n + bname);
-        };
-        auto fresh = [&](const std::string& key, const bf16_t* a0, const bf16_t* a1, int C0, int C1, int Hs, int Ws, float eps) -> int {
-            if (stats_mode != FISE_STATS_FRESH) return FISE_OK;
-            return fise_groupnorm_stats(a0, a1, FISE_BF16, B, Hs, Ws, C0, C1, G, eps, Cf(key + ".mean"), Cf(key + ".rstd"), gnws, st);
-        };
-        auto lin = [&](const bf16_t* A, int Cin, const bf16_t* w, const bf16_t* bias, int N) {
-            IgemmArgs g = linear_args(A, Ma, B, Cin, w, bias, N);
-            g.tile_idx = idx; g.tile = tile; g.tiles_w = tiles_w; g.Ho = H; g.Wo = W;
-            return g;
-        };
-
+        const void* in0 = m.in_map.empty() ? latent : Cp(m.in_map);
+        const void* in1 = m.skip_map.empty() ? nullptr : Cp(m.skip_map);
         switch (m.kind) {
         case K_CONV_IN: {
             fise_conv_args a{};
@@ -360,86 +363,45 @@ extern "C" int fise_masked_unet_step(const fise_unet* u, const void* weights, vo
             if (int e = conv_dispatch(&a, nullptr, 0, st)) return e;
         } break;
         case K_RES: {
-            const int ci = m.cin + m.cskip, co = m.cout;
-            if (int e = fresh(n + ".gn1", in0, in1, m.cin, m.cskip, H, W, 1e-5f)) return e;
-            IgemmArgs g = conv(in0, in1, m.cin, m.cskip, H, W, 3, 1, 0, Wp(n + ".conv1.w"), Wp(n + ".conv1.b"), co);
-            with_gn(g, n + ".gn1", ".gn1.g", ".gn1.b", true);
-            g.temb = temb + m.temb_off; g.temb_stride = u->temb_total;
-            g.out[0] = Cp(n + ".h1");
-            if (int e = launch_igemm(g, st)) return e;
-            if (int e = fresh(n + ".gn2", Cp(n + ".h1"), nullptr, co, 0, H, W, 1e-5f)) return e;
-            const bf16_t* res = in0;
-            if (ci != co) {       // 1x1 shortcut, parked in the output map, then consumed as the residual
-                IgemmArgs s = conv(in0, in1, m.cin, m.cskip, H, W, 1, 1, 0, Wp(n + ".sc.w"), Wp(n + ".sc.b"), co);
-                s.out[0] = Cp(n + ".out");
-                if (int e = launch_igemm(s, st)) return e;
-                res = Cp(n + ".out");
-            }
-            IgemmArgs c2 = conv(Cp(n + ".h1"), nullptr, co, 0, H, W, 3, 1, 0, Wp(n + ".conv2.w"), Wp(n + ".conv2.b"), co);
-            with_gn(c2, n + ".gn2", ".gn2.g", ".gn2.b", true);
-            c2.res = res; c2.out[0] = Cp(n + ".out");
-            if (int e = launch_igemm(c2, st)) return e;
+            fise_resnet_args r{};
+            r.x0 = in0; r.x1 = in1; r.C0 = m.cin; r.C1 = m.cskip; r.B = B; r.H = H; r.W = W; r.Cout = m.cout; r.G = G;
+            r.gn1_mean = Cf(n + ".gn1.mean"); r.gn1_rstd = Cf(n + ".gn1.rstd"); r.gn1_gamma = Wp(n + ".gn1.g"); r.gn1_beta = Wp(n + ".gn1.b");
+            r.conv1_w = Wp(n + ".conv1.w"); r.conv1_b = Wp(n + ".conv1.b"); r.temb = temb + m.temb_off; r.temb_stride = u->temb_total;
+            r.gn2_mean = Cf(n + ".gn2.mean"); r.gn2_rstd = Cf(n + ".gn2.rstd"); r.gn2_gamma = Wp(n + ".gn2.g"); r.gn2_beta = Wp(n + ".gn2.b");
+            r.conv2_w = Wp(n + ".conv2.w"); r.conv2_b = Wp(n + ".conv2.b");
+            if (m.cin + m.cskip != m.cout) { r.sc_w = Wp(n + ".sc.w"); r.sc_b = Wp(n + ".sc.b"); }
+            r.tile_idx = idx; r.n_active = nt; r.tile = tile; r.h1_cache = Cp(n + ".h1"); r.out_cache = Cp(n + ".out"); r.stats_fresh = fresh;
+            if (int e = run_resnet(&r, blockws, iw, st)) return e;
         } break;
         case K_TR: {
-            const int C = m.cout, dh = C / d.heads;
-            const float scale = 1.0f / sqrtf((float)dh);
-            const int rows = B * Ma;
-            if (int e = fresh(n + ".gn", in0, nullptr, C, 0, H, W, 1e-6f)) return e;
-            IgemmArgs g = conv(in0, nullptr, C, 0, H, W, 1, 1, 0, Wp(n + ".pin.w"), Wp(n + ".pin.b"), C);
-            with_gn(g, n + ".gn", ".gn.g", ".gn.b", false);
-            g.out[0] = hb; g.out_mode[0] = OUT_COMPACT;
-            if (int e = launch_igemm(g, st)) return e;
-            // self-attention: LN -> fused QKV (K, V rows scattered into the caches) -> attention -> out-proj + residual
-            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln1.g"), Wp(n + ".ln1.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
-            IgemmArgs qkv = lin(nb, C, Wp(n + ".a1.q.w"), nullptr, 3 * C);
-            qkv.nsect = 3; qkv.sect_n = C;
-            qkv.out[0] = qb; qkv.out_mode[0] = OUT_COMPACT;
-            qkv.out[1] = Cp(n + ".k"); qkv.out_mode[1] = OUT_MAP;
-            qkv.out[2] = Cp(n + ".v"); qkv.out_mode[2] = OUT_TOKENS_T;
-            if (int e = launch_igemm(qkv, st)) return e;
-            if (int e = launch_attention(qb, Cp(n + ".k"), Cp(n + ".v"), B, Ma, H * W, H * W, C, d.heads, scale, ob, st)) return e;
-            IgemmArgs o1 = lin(ob, C, Wp(n + ".a1.o.w"), Wp(n + ".a1.o.b"), C);
-            o1.res = hb; o1.res_compact = 1; o1.out[0] = hb;
-            if (int e = launch_igemm(o1, st)) return e;
-            // cross-attention against the context K/V of the new conditioning
-            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln2.g"), Wp(n + ".ln2.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
-            IgemmArgs q2 = lin(nb, C, Wp(n + ".a2.q.w"), nullptr, C);
-            q2.out[0] = qb;
-            if (int e = launch_igemm(q2, st)) return e;
-            if (int e = launch_attention(qb, kv + u->off(2, n + ".ctx_k"), kv + u->off(2, n + ".ctx_vt"), B, Ma, d.n_ctx, u->n_stride, C,
-                                         d.heads, scale, ob, st)) return e;
-            IgemmArgs o2 = lin(ob, C, Wp(n + ".a2.o.w"), Wp(n + ".a2.o.b"), C);
-            o2.res = hb; o2.res_compact = 1; o2.out[0] = hb;
-            if (int e = launch_igemm(o2, st)) return e;
-            // feed-forward: LN -> GEGLU (fused into the first GEMM's epilogue) -> second GEMM + residual
-            if (int e = launch_ln_rows(hb, rows, C, Wp(n + ".ln3.g"), Wp(n + ".ln3.b"), 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
-            IgemmArgs f1 = lin(nb, C, Wp(n + ".ff1.w"), Wp(n + ".ff1.b"), 4 * C);
-            f1.geglu = 1; f1.sect_n = 4 * C; f1.out[0] = fb;
-            if (int e = launch_igemm(f1, st)) return e;
-            IgemmArgs f2 = lin(fb, 4 * C, Wp(n + ".ff2.w"), Wp(n + ".ff2.b"), C);
-            f2.res = hb; f2.res_compact = 1; f2.out[0] = hb;
-            if (int e = launch_igemm(f2, st)) return e;
-            // 1x1 out + block input, scattered into the cached block output
-            IgemmArgs po = lin(hb, C, Wp(n + ".pout.w"), Wp(n + ".pout.b"), C);
-            po.res = in0; po.res_compact = 0; po.out[0] = Cp(n + ".out"); po.out_mode[0] = OUT_MAP;
-            if (int e = launch_igemm(po, st)) return e;
+            fise_transformer_args t{};
+            t.x = in0; t.B = B; t.H = H; t.W = W; t.C = m.cout; t.G = G; t.heads = d.heads;
+            t.gn_mean = Cf(n + ".gn.mean"); t.gn_rstd = Cf(n + ".gn.rstd"); t.gn_gamma = Wp(n + ".gn.g"); t.gn_beta = Wp(n + ".gn.b");
+            t.pin_w = Wp(n + ".pin.w"); t.pin_b = Wp(n + ".pin.b");
+            t.ln1_g = Wp(n + ".ln1.g"); t.ln1_b = Wp(n + ".ln1.b"); t.qkv_w = Wp(n + ".a1.q.w"); t.o1_w = Wp(n + ".a1.o.w"); t.o1_b = Wp(n + ".a1.o.b");
+            t.ln2_g = Wp(n + ".ln2.g"); t.ln2_b = Wp(n + ".ln2.b"); t.q2_w = Wp(n + ".a2.q.w"); t.o2_w = Wp(n + ".a2.o.w"); t.o2_b = Wp(n + ".a2.o.b");
+            t.K_ctx = kv + u->off(2, n + ".ctx_k"); t.Vt_ctx = kv + u->off(2, n + ".ctx_vt"); t.n_ctx = d.n_ctx; t.n_ctx_stride = u->n_stride;
+            t.ln3_g = Wp(n + ".ln3.g"); t.ln3_b = Wp(n + ".ln3.b"); t.ff1_w = Wp(n + ".ff1.w"); t.ff1_b = Wp(n + ".ff1.b");
+            t.ff2_w = Wp(n + ".ff2.w"); t.ff2_b = Wp(n + ".ff2.b"); t.pout_w = Wp(n + ".pout.w"); t.pout_b = Wp(n + ".pout.b");
+            t.K_cache = Cp(n + ".k"); t.Vt_cache = Cp(n + ".v"); t.out_cache = Cp(n + ".out");
+            t.tile_idx = idx; t.n_active = nt; t.tile = tile; t.stats_fresh = fresh;
+            if (int e = run_transformer(&t, blockws, iw, st)) return e;
         } break;
-        case K_DS: {
-            IgemmArgs g = conv(in0, nullptr, m.cin, 0, 2 * H, 2 * W, 3, 2, 0, Wp(n + ".w"), Wp(n + ".b"), m.cout);
-            g.out[0] = Cp(n + ".out");
-            if (int e = launch_igemm(g, st)) return e;
-        } break;
-        case K_US: {
-            IgemmArgs g = conv(in0, nullptr, m.cin, 0, H / 2, W / 2, 3, 1, 1, Wp(n + ".w"), Wp(n + ".b"), m.cout);
-            g.out[0] = Cp(n + ".out");
-            if (int e = launch_igemm(g, st)) return e;
-        } break;
+        case K_DS:
+            if (int e = run_conv(in0, m.cin, B, 2 * H, 2 * W, 2, 0, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st)) return e;
+            break;
+        case K_US:
+            if (int e = run_conv(in0, m.cin, B, H / 2, W / 2, 1, 1, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st)) return e;
+            break;
         case K_OUT: {
-            if (int e = fresh(n + ".gn", in0, nullptr, m.cin, 0, H, W, 1e-5f)) return e;
-            IgemmArgs g = conv(in0, nullptr, m.cin, 0, H, W, 3, 1, 0, Wp(n + ".conv.w"), Wp(n + ".conv.b"), m.cout);
-            with_gn(g, n + ".gn", ".gn.g", ".gn.b", true);
-            g.out[0] = Cp("eps");
-            if (int e = launch_igemm(g, st)) return e;
+            fise_conv_args a{};
+            a.x0 = in0; a.C0 = m.cin; a.B = B; a.H = H; a.W = W; a.w = Wp(n + ".conv.w"); a.bias = Wp(n + ".conv.b"); a.Cout = m.cout;
+            a.ksize = 3; a.stride = 1; a.gn_mean = Cf(n + ".gn.mean"); a.gn_rstd = Cf(n + ".gn.rstd"); a.gn_gamma = Wp(n + ".gn.g");
+            a.gn_beta = Wp(n + ".gn.b"); a.G = G; a.gn_silu = 1; a.tile_idx = idx; a.n_active = nt; a.tile = tile; a.y_cache = Cp("eps");
+            a.dtype = FISE_BF16;
+            if (fresh)
+                if (int e = fise_groupnorm_stats(in0, nullptr, FISE_BF16, B, H, W, m.cin, 0, G, 1e-5f, Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), blockws, st)) return e;
+            if (int e = conv_dispatch(&a, ws + wl.igemm, igemm_workspace_bytes(), st)) return e;
         } break;
         }
     }

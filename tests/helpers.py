@@ -40,6 +40,14 @@ def rel_err(got, want):
     return float(np.max(np.abs(got - want) / den))
 
 
+def rel_l2(got, want):
+    """||g - o||_2 / ||o||_2 over the given elements."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    if want.size == 0:
+        return 0.0
+    return float(np.sqrt(np.sum((got - want) ** 2)) / max(np.sqrt(np.sum(want ** 2)), 1e-30))
+
+
 def active_mask(idx, tile, H, W):
     ys, xs = fo.active_pixels(idx, tile, W)
     m = np.zeros((H, W), bool)

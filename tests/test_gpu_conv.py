@@ -68,6 +68,8 @@ CASES = [
     ("narrow-out", 2, 16, 16, 64, 0, 4, 3, 1, 0, 4, True, 1, False, False, 0.2),
     ("ragged-n", 1, 16, 16, 32, 0, 72, 3, 1, 0, 4, False, 0, False, True, 0.1),
     ("scalar-cin4", 2, 16, 16, 4, 0, 32, 3, 1, 0, 4, False, 0, False, False, 0.2),
+    ("deep-1280-few-rows", 2, 8, 8, 1280, 1280, 1280, 3, 1, 0, 1, True, 1, True, False, 0.2),     # long K, split over workgroups
+    ("deep-16x16", 2, 16, 16, 1280, 640, 1280, 3, 1, 0, 2, True, 1, True, False, 0.2),
 ]
 
 
@@ -115,11 +117,19 @@ def test_bf16_conv_variants(fb, case):
         y = dev(cache, dt)
         a = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, t, y, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
                          gn_silu=silu, temb=tembd, residual=resd)
-        fb.fise_masked_conv(a)
+        # with the split-K scratch (filled with garbage: the library zeroes what it needs) ...
+        ws = torch.full((fb.fise_masked_conv_workspace_bytes(a),), 0xA5, dtype=torch.uint8, device=DEV)
+        fb.fise_masked_conv(a, ws)
         got = host(y)
         check_map(got, oracle(ix), cache.astype(np.float64), active_mask(ix, t, Ho, Wo), TOL[dt], f"{name} n={ix.size}")
-        fb.fise_masked_conv(a)
+        fb.fise_masked_conv(a, ws)
         assert np.array_equal(host(y), got), "not idempotent"
+        # ... and without it (no K split): same result up to the summation order
+        y2 = dev(cache, dt)
+        a2 = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, t, y2, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
+                          gn_silu=silu, temb=tembd, residual=resd)
+        fb.fise_masked_conv(a2)
+        check_map(host(y2), oracle(ix), cache.astype(np.float64), active_mask(ix, t, Ho, Wo), TOL[dt], f"{name} unsplit n={ix.size}")
 
 
 def test_conv_residual_in_place(fb):

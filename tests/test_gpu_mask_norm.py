@@ -26,8 +26,11 @@ def run_detect(fb, x_old, x_new, thr, tile, dtype, capacity=None):
     tm = torch.full((nt,), 7, dtype=torch.uint8, device=DEV)
     idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=DEV)
     n = torch.full((1,), -1, dtype=torch.int32, device=DEV)
-    fb.lib().fise_mask_detect(dev(x_old, dtype).data_ptr(), dev(x_new, dtype).data_ptr(), 0 if dtype == "f32" else 1, B, H, W, C,
-                              thr, tile, pix.data_ptr(), tm.data_ptr(), idx.data_ptr(), cap, n.data_ptr(), None)
+    xo, xn = dev(x_old, dtype), dev(x_new, dtype)
+    rc = fb.lib().fise_mask_detect(xo.data_ptr(), xn.data_ptr(), 0 if dtype == "f32" else 1, B, H, W, C,
+                                   thr, tile, pix.data_ptr(), tm.data_ptr(), idx.data_ptr(), cap, n.data_ptr(),
+                                   torch.cuda.current_stream().cuda_stream)
+    assert rc == 0, fb.fise_last_error()
     torch.cuda.synchronize()
     return pix.cpu().numpy(), tm.cpu().numpy().reshape(H // tile, W // tile), idx.cpu().numpy(), int(n.item())
 
