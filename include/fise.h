@@ -179,9 +179,13 @@ int fise_masked_conv3x3(const void* x, const void* w, const void* bias, int dtyp
 
 /* out[b,m,:] = softmax_k(q[b,m,h].K[b,k,h] * scale) V[b,k,h] per head h
  * (channels [h*d,(h+1)*d), d = C/heads) over ALL n_keys keys.  q, out
- * [B, M, C].  bf16 only; d a multiple of 8, d <= 160. */
+ * [B, M, C].  bf16 only; d a multiple of 8, d <= 160.  With a workspace the key
+ * range is split over workgroups when there are few queries (partials merged in
+ * a fixed order); workspace NULL runs unsplit. */
+size_t fise_attention_active_workspace_bytes(int B, int M, int n_keys, int C, int heads);
 int fise_attention_active(const void* q, const void* K, const void* Vt, int dtype, int B, int M, int n_keys,
-                          int n_stride, int C, int heads, float scale, void* out, void* stream);
+                          int n_stride, int C, int heads, float scale, void* out,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* K/V of the text context, once per conditioning: K_ctx[B,n_ctx,C] =
  * ctx[B,n_ctx,Dc] Wk^T, Vt_ctx[B,C,n_stride] = (ctx Wv^T)^T. */

@@ -79,7 +79,8 @@ _SIGS = {
     "fise_masked_conv": (i32, [C.POINTER(fise_conv_args), vp, sz, vp]),
     "fise_masked_conv3x3": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, i32,
                                   vp, vp, vp, vp, sz, vp]),
-    "fise_attention_active": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp]),
+    "fise_attention_active_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
+    "fise_attention_active": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]),
     "fise_context_kv_workspace_bytes": (sz, [i32, i32, i32, i32]),
     "fise_context_kv": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]),
     "fise_masked_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
@@ -250,11 +251,16 @@ def fise_masked_conv3x3(x, w, bias, stride, tile_idx, n_active, tile, y_cache, g
 
 
 # --------------------------------------------------------------------------- attention
-def fise_attention_active(q, K, Vt, heads, scale, out, n_keys=None, stream=None):
+def fise_attention_active_workspace_bytes(B, M, n_keys, Cc, heads):
+    return lib().fise_attention_active_workspace_bytes(B, M, n_keys, Cc, heads)
+
+
+def fise_attention_active(q, K, Vt, heads, scale, out, n_keys=None, workspace=None, stream=None):
     B, M, Cc = q.shape
     n_keys = K.shape[1] if n_keys is None else n_keys
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _ck(lib().fise_attention_active(_p(q), _p(K), _p(Vt), _dt(q), B, M, n_keys, Vt.shape[2], Cc, heads, scale, _p(out),
-                                    _stream(stream)))
+                                    _p(workspace), nbytes, _stream(stream)))
 
 
 def fise_context_kv(ctx, Wk, Wv, K_ctx, Vt_ctx, stream=None):

@@ -1,8 +1,16 @@
 // Active-query attention on bf16 MFMA: each wave owns 32 gathered queries of one
-// (batch, head) and streams all keys in blocks of 64 through LDS with an online
+// (batch, head) and streams keys in blocks of 64 through LDS with an online
 // softmax.  Scores are computed transposed (S^T = K Q^T) so that a lane keeps one
 // query's running max / sum to itself, and the output is accumulated transposed
 // (O^T = V^T P^T), which is why V operands are stored keys-innermost.
+//
+// With few active queries there are few (query tile, head, batch) workgroups, so
+// the key range is also split over workgroups: each writes an unnormalised partial
+// (running max, sum, output) and a second small kernel merges the partials in
+// split order.  The next key block is fetched into registers while the current
+// one is being multiplied; the LDS hand-over uses a barrier that does not wait for
+// those loads.
+#include <algorithm>
 #include "igemm.h"
 #include "profile.h"
 
@@ -11,21 +19,34 @@ namespace fise {
 constexpr int AT_BKV = 64;        // keys per block
 constexpr int AT_QW = 32;         // queries per wave
 constexpr int AT_WAVES = 4;
+constexpr int AT_BQ = AT_QW * AT_WAVES;
+
+__device__ __forceinline__ void at_lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int KD, int DB>          // KD: 16-wide steps over the head dim; DB: 32-row blocks of the output head dim
 __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ K,
-                                                        const bf16_t* __restrict__ Vt, int M, int n_keys, int n_stride,
-                                                        int C, int d, float scale_log2e, bf16_t* __restrict__ out) {
+                                                        const bf16_t* __restrict__ Vt, int B, int M, int n_keys, int n_stride,
+                                                        int C, int d, float scale_log2e, int splits, bf16_t* __restrict__ out,
+                                                        float* __restrict__ part_o, float* __restrict__ part_ml) {
     constexpr int DP = KD * 16;
     constexpr int KP = DP + 8;            // K tile pitch (bf16)
     constexpr int VP = AT_BKV + 8;        // V^T tile pitch
+    constexpr int KCH = AT_BKV * (DP / 8);        // 16-byte chunks of the K tile
+    constexpr int VCH = DB * 32 * (AT_BKV / 8);   // and of the V^T tile
+    constexpr int KL = (KCH + 255) / 256, VL = (VCH + 255) / 256;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[AT_BKV][KP];
     __shared__ __attribute__((aligned(16))) bf16_t Vs[DB * 32][VP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5, l32 = lane & 31;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int qrow = blockIdx.x * (AT_QW * AT_WAVES) + wave * AT_QW + l32;
+    const int h = blockIdx.y, b = blockIdx.z / splits, sp = blockIdx.z % splits;
+    const int qrow = blockIdx.x * AT_BQ + wave * AT_QW + l32;
     const bool qok = qrow < M;
+    const int dchunks = d / 8;
+
+    // key blocks of this split
+    const int nblocks = (n_keys + AT_BKV - 1) / AT_BKV;
+    const int per = (nblocks + splits - 1) / splits;
+    const int blk0 = sp * per, blk1 = min(nblocks, blk0 + per);
 
     // query fragments: B operand of S^T = K Q^T (column = query, 8 consecutive head-dim elements)
     bf16x8_t qf[KD];
@@ -44,36 +65,60 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int dchunks = d / 8;
-    for (int k0 = 0; k0 < n_keys; k0 += AT_BKV) {
-        __syncthreads();                                   // previous block fully consumed
-        // ---- K tile: [64 keys][DP], zero padded
-        for (int e = tid; e < AT_BKV * (DP / 8); e += 256) {
+    // register staging of one key block (unconditional loads of harmless addresses where nothing exists)
+    uint4 rk[KL], rv[VL];
+    auto fetch = [&](int blk) {
+        const int k0 = blk * AT_BKV;
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            const int e = tid + 256 * j;
             const int kk = e / (DP / 8), c8 = e % (DP / 8);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (k0 + kk < n_keys && c8 < dchunks)
-                v = *reinterpret_cast<const uint4*>(K + ((size_t)b * n_keys + k0 + kk) * C + h * d + c8 * 8);
-            *reinterpret_cast<uint4*>(&Ks[kk][c8 * 8]) = v;
+            const bool ok = e < KCH && k0 + kk < n_keys && c8 < dchunks;
+            rk[j] = *reinterpret_cast<const uint4*>(K + (ok ? ((size_t)b * n_keys + k0 + kk) * C + h * d + c8 * 8 : 0));
         }
-        // ---- V^T tile: [DB*32 head-dim rows][64 keys], zero where the row or the key does not exist
-        for (int e = tid; e < DB * 32 * (AT_BKV / 8); e += 256) {
+#pragma unroll
+        for (int j = 0; j < VL; ++j) {
+            const int e = tid + 256 * j;
+            const int r = e / (AT_BKV / 8), c8 = e % (AT_BKV / 8);
+            const bool ok = e < VCH && r < d && k0 + c8 * 8 < n_keys;
+            rv[j] = *reinterpret_cast<const uint4*>(Vt + (ok ? ((size_t)b * C + h * d + r) * n_stride + k0 + c8 * 8 : 0));
+        }
+    };
+    auto stash = [&](int blk) {
+        const int k0 = blk * AT_BKV;
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            const int e = tid + 256 * j;
+            const int kk = e / (DP / 8), c8 = e % (DP / 8);
+            const bool ok = k0 + kk < n_keys && c8 < dchunks;
+            if (e < KCH) *reinterpret_cast<uint4*>(&Ks[kk][c8 * 8]) = ok ? rk[j] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < VL; ++j) {
+            const int e = tid + 256 * j;
             const int r = e / (AT_BKV / 8), c8 = e % (AT_BKV / 8);
             const int key = k0 + c8 * 8;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (r < d && key < n_keys) {
-                v = *reinterpret_cast<const uint4*>(Vt + ((size_t)b * C + h * d + r) * n_stride + key);
-                const int nvalid = n_keys - key;           // >= 1
-                if (nvalid < 8) {
-                    unsigned w4[4] = {v.x, v.y, v.z, v.w};
+            uint4 v = rv[j];
+            if (!(r < d && key < n_keys)) v = make_uint4(0, 0, 0, 0);
+            else if (n_keys - key < 8) {                     // zero the keys that do not exist
+                const int nvalid = n_keys - key;
+                unsigned w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j >= nvalid) w4[j >> 1] &= (j & 1) ? 0x0000ffffu : 0xffff0000u;
-                    v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-                }
+                for (int t = 0; t < 8; ++t)
+                    if (t >= nvalid) w4[t >> 1] &= (t & 1) ? 0x0000ffffu : 0xffff0000u;
+                v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
-            *reinterpret_cast<uint4*>(&Vs[r][c8 * 8]) = v;
+            if (e < VCH) *reinterpret_cast<uint4*>(&Vs[r][c8 * 8]) = v;
         }
-        __syncthreads();
+    };
+
+    if (blk0 < blk1) fetch(blk0);
+    for (int blk = blk0; blk < blk1; ++blk) {
+        const int k0 = blk * AT_BKV;
+        at_lds_barrier();                                  // previous block fully consumed
+        stash(blk);
+        fetch(min(blk + 1, blk1 - 1));                     // next block in flight during the MFMAs below
+        at_lds_barrier();
 
         // ---- S^T = K Q^T for two 32-key blocks
         f32x16_t s[2];
@@ -136,8 +181,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
             }
     }
 
-    // ---- normalise and store: lane holds query l32, head-dim rows i*32 + (e/4)*8 + hl*4 + e%4
-    if (qok) {
+    // ---- store: lane holds query l32, head-dim rows i*32 + (e/4)*8 + hl*4 + e%4
+    if (!qok) return;
+    if (splits == 1) {
         const float inv = 1.0f / l_run;
         bf16_t* o = out + ((size_t)b * M + qrow) * C + h * d;
 #pragma unroll
@@ -147,33 +193,94 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                 const int r = i * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
                 if (r < d) o[r] = f2bf(oacc[i][e] * inv);
             }
+    } else {
+        // unnormalised partial of this key range: O[sp][b][qrow][h*d + r], (m, l)[sp][b][h][qrow]
+        float* po = part_o + (((size_t)sp * B + b) * M + qrow) * C + h * d;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int r = i * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
+                if (r < d) po[r] = oacc[i][e];
+            }
+        if (hl == 0) {
+            float* pm = part_ml + ((((size_t)sp * B + b) * gridDim.y + h) * M + qrow) * 2;
+            pm[0] = m_run; pm[1] = l_run;
+        }
     }
+}
+
+// out[b,m,c] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s), splits visited in index order.
+__global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                              int B, int M, int C, int heads, int d, int splits,
+                                                              bf16_t* __restrict__ out) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)B * M * C) return;
+    const int c = (int)(i % C), m = (int)((i / C) % M), b = (int)(i / ((long long)C * M));
+    const int h = c / d;
+    float mx = -INFINITY;
+    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, part_ml[((((size_t)s * B + b) * heads + h) * M + m) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < splits; ++s) {
+        const float* ml = part_ml + ((((size_t)s * B + b) * heads + h) * M + m) * 2;
+        const float w = exp2f(ml[0] - mx);                 // an empty split has m = -inf: weight 0
+        num += w * part_o[(((size_t)s * B + b) * M + m) * C + c];
+        den += w * ml[1];
+    }
+    out[i] = f2bf(num / den);
 }
 
 template <int KD, int DB>
 static void launch_at(const void* q, const void* K, const void* Vt, int B, int M, int n_keys, int n_stride, int C, int heads,
-                      int d, float scale, void* out, hipStream_t st) {
-    dim3 grid(ceil_div(M, AT_QW * AT_WAVES), heads, B);
+                      int d, float scale, int splits, void* out, float* part_o, float* part_ml, hipStream_t st) {
+    dim3 grid(ceil_div(M, AT_BQ), heads, B * splits);
     hipLaunchKernelGGL((attention_kernel<KD, DB>), grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)K,
-                       (const bf16_t*)Vt, M, n_keys, n_stride, C, d, scale * 1.4426950408889634f, (bf16_t*)out);
+                       (const bf16_t*)Vt, B, M, n_keys, n_stride, C, d, scale * 1.4426950408889634f, splits, (bf16_t*)out,
+                       part_o, part_ml);
+}
+
+static int attention_splits(int B, int M, int n_keys, int heads) {
+    const int wgs = ceil_div(M, AT_BQ) * heads * B;
+    const int nblocks = ceil_div(n_keys, AT_BKV);
+    int s = ceil_div(640, wgs);
+    s = std::min(s, nblocks / 2);
+    return std::max(1, std::min(s, 32));
+}
+
+size_t attention_workspace_bytes(int B, int M, int n_keys, int C, int heads) {
+    const int s = attention_splits(B, M, n_keys, heads);
+    if (s <= 1) return 0;
+    return align256((size_t)s * B * M * C * sizeof(float)) + align256((size_t)s * B * heads * M * 2 * sizeof(float));
 }
 
 int launch_attention(const void* q, const void* K, const void* Vt, int B, int M, int n_keys, int n_stride, int C, int heads,
-                     float scale, void* out, hipStream_t st) {
+                     float scale, void* out, void* ws, size_t ws_bytes, hipStream_t st) {
     if (M <= 0) return FISE_OK;
     const int d = C / heads;
     const int kd = ceil_div(d, 16), db = ceil_div(d, 32);
+    int splits = attention_splits(B, M, n_keys, heads);
+    if (splits > 1 && (!ws || ws_bytes < attention_workspace_bytes(B, M, n_keys, C, heads))) splits = 1;
+    float* part_o = (float*)ws;
+    float* part_ml = splits > 1 ? (float*)((char*)ws + align256((size_t)splits * B * M * C * sizeof(float))) : nullptr;
     ProfileScope prof(PROF_ATTENTION, 4.0 * B * (double)M * n_keys * C,
                       2.0 * ((double)B * n_keys * C * 2 + 2.0 * B * M * C), st);
-    if (kd <= 1) launch_at<1, 1>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd == 2) launch_at<2, 1>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd == 3) launch_at<3, 2>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd == 4) launch_at<4, 2>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd <= 6 && db <= 3) launch_at<6, 3>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd <= 8) launch_at<8, 4>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
-    else if (kd <= 10) launch_at<10, 5>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, out, st);
+#define FISE_AT(KDV, DBV) launch_at<KDV, DBV>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, splits, out, part_o, part_ml, st)
+    if (kd <= 1) FISE_AT(1, 1);
+    else if (kd == 2) FISE_AT(2, 1);
+    else if (kd == 3) FISE_AT(3, 2);
+    else if (kd == 4) FISE_AT(4, 2);
+    else if (kd <= 6 && db <= 3) FISE_AT(6, 3);
+    else if (kd <= 8) FISE_AT(8, 4);
+    else if (kd <= 10) FISE_AT(10, 5);
     else return fail(FISE_ERR_SHAPE, "attention: head dim %d > 160", d);
+#undef FISE_AT
     FISE_CHECK_LAUNCH("attention");
+    if (splits > 1) {
+        const long long n = (long long)B * M * C;
+        hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part_o, part_ml, B, M, C,
+                           heads, d, splits, (bf16_t*)out);
+        FISE_CHECK_LAUNCH("attention merge");
+    }
     return FISE_OK;
 }
 
@@ -181,14 +288,21 @@ int launch_attention(const void* q, const void* K, const void* Vt, int B, int M,
 
 using namespace fise;
 
+extern "C" size_t fise_attention_active_workspace_bytes(int B, int M, int n_keys, int C, int heads) {
+    if (B < 1 || M < 1 || n_keys < 1 || C < 1 || heads < 1) return 0;
+    return attention_workspace_bytes(B, M, n_keys, C, heads);
+}
+
 extern "C" int fise_attention_active(const void* q, const void* K, const void* Vt, int dtype, int B, int M, int n_keys,
-                                     int n_stride, int C, int heads, float scale, void* out, void* stream) {
+                                     int n_stride, int C, int heads, float scale, void* out, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
     if (!q || !K || !Vt || !out) return fail(FISE_ERR_NULL, "fise_attention_active: null pointer");
     if (dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_attention_active: bf16 only (dtype %d)", dtype);
     if (B < 1 || M < 0 || n_keys < 1 || C < 1 || heads < 1 || C % heads) return fail(FISE_ERR_SHAPE, "fise_attention_active: B%d M%d keys%d C%d heads%d", B, M, n_keys, C, heads);
     const int d = C / heads;
     if (d % 8 || d > 160) return fail(FISE_ERR_SHAPE, "fise_attention_active: head dim %d (multiple of 8, <= 160)", d);
     if (n_stride < n_keys || n_stride % 8) return fail(FISE_ERR_ALIGN, "fise_attention_active: n_stride %d (>= n_keys, multiple of 8)", n_stride);
-    if (!aligned16(q) || !aligned16(K) || !aligned16(Vt) || !aligned16(out)) return fail(FISE_ERR_ALIGN, "fise_attention_active: pointers must be 16-byte aligned");
-    return launch_attention(q, K, Vt, B, M, n_keys, n_stride, C, heads, scale, out, as_stream(stream));
+    if (!aligned16(q) || !aligned16(K) || !aligned16(Vt) || !aligned16(out) || (workspace && !aligned16(workspace)))
+        return fail(FISE_ERR_ALIGN, "fise_attention_active: pointers must be 16-byte aligned");
+    return launch_attention(q, K, Vt, B, M, n_keys, n_stride, C, heads, scale, out, workspace, workspace_bytes, as_stream(stream));
 }

@@ -48,24 +48,32 @@ static void set_gn(IgemmArgs& g, const float* mean, const float* rstd, const voi
     g.gn_mean = mean; g.gn_rstd = rstd; g.gn_gamma = (const bf16_t*)gamma; g.gn_beta = (const bf16_t*)beta; g.G = G;
 }
 
+// ResNet scratch: [GroupNorm statistics partials | activation map of conv1's input | of conv2's input]
+static size_t resnet_gn_bytes(const fise_resnet_args* a) { return align256(fise_groupnorm_stats_workspace_bytes(a->B, a->H, a->W, a->G)); }
+static size_t resnet_act_bytes(const fise_resnet_args* a, int C) { return align256((size_t)a->B * a->H * a->W * C * sizeof(bf16_t)); }
 size_t resnet_ws_bytes(const fise_resnet_args* a) {
-    return fise_groupnorm_stats_workspace_bytes(a->B, a->H, a->W, a->G);
+    return resnet_gn_bytes(a) + resnet_act_bytes(a, a->C0 + a->C1) + resnet_act_bytes(a, a->Cout);
 }
 
 int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st) {
     const int Ci = a->C0 + a->C1, Co = a->Cout, B = a->B, H = a->H, W = a->W;
+    char* act1 = (char*)ws + resnet_gn_bytes(a);
+    char* act2 = act1 + resnet_act_bytes(a, Ci);
     if (a->stats_fresh)
         if (int e = fise_groupnorm_stats(a->x0, a->x1, FISE_BF16, B, H, W, a->C0, a->C1, a->G, 1e-5f, a->gn1_mean, a->gn1_rstd, ws, st)) return e;
-    IgemmArgs c1 = conv_args(a->x0, a->x1, a->C0, a->C1, B, H, W, H, W, 3, 1, 0, a->conv1_w, a->conv1_b, Co, a->tile_idx,
+    // the normalised + activated input (active tiles and their ring) is written once, then convolved
+    if (int e = launch_gn_act_halo(a->x0, a->x1, a->C0, a->C1, B, H, W, a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, a->G, 1,
+                                   a->tile_idx, a->n_active, a->tile, act1, st)) return e;
+    IgemmArgs c1 = conv_args(act1, nullptr, Ci, 0, B, H, W, H, W, 3, 1, 0, a->conv1_w, a->conv1_b, Co, a->tile_idx,
                              a->n_active, a->tile, a->h1_cache);
-    set_gn(c1, a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, a->G, true);
     c1.temb = a->temb; c1.temb_stride = a->temb_stride;
     if (int e = launch_igemm(c1, iw, st)) return e;
     if (a->stats_fresh)
         if (int e = fise_groupnorm_stats(a->h1_cache, nullptr, FISE_BF16, B, H, W, Co, 0, a->G, 1e-5f, a->gn2_mean, a->gn2_rstd, ws, st)) return e;
-    IgemmArgs c2 = conv_args(a->h1_cache, nullptr, Co, 0, B, H, W, H, W, 3, 1, 0, a->conv2_w, a->conv2_b, Co, a->tile_idx,
+    if (int e = launch_gn_act_halo(a->h1_cache, nullptr, Co, 0, B, H, W, a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, a->G, 1,
+                                   a->tile_idx, a->n_active, a->tile, act2, st)) return e;
+    IgemmArgs c2 = conv_args(act2, nullptr, Co, 0, B, H, W, H, W, 3, 1, 0, a->conv2_w, a->conv2_b, Co, a->tile_idx,
                              a->n_active, a->tile, a->out_cache);
-    set_gn(c2, a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, a->G, true);
     if (a->sc_w) {            // 1x1 shortcut: extra K steps of the same GEMM, never stored
         c2.s0 = (const bf16_t*)a->x0; c2.s1 = (const bf16_t*)a->x1; c2.S0 = a->C0; c2.S1 = a->C1; c2.K2 = Ci;
         c2.w2 = (const bf16_t*)a->sc_w; c2.bias2 = (const bf16_t*)a->sc_b;
@@ -75,8 +83,8 @@ int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hi
     return launch_igemm(c2, iw, st);
 }
 
-struct TrWs { size_t h, h16, n, q, o, ff, gn, total; };
-static TrWs tr_ws(int B, int H, int W, int C, int G, int n_active, int tile) {
+struct TrWs { size_t h, h16, n, q, o, ff, gn, at, at_bytes, total; };
+static TrWs tr_ws(int B, int H, int W, int C, int G, int heads, int n_active, int tile) {
     TrWs w{};
     const size_t rows = (size_t)B * n_active * tile * tile;
     size_t c = 0;
@@ -84,16 +92,18 @@ static TrWs tr_ws(int B, int H, int W, int C, int G, int n_active, int tile) {
     w.h = take(rows * C * 4); w.h16 = take(rows * C * 2); w.n = take(rows * C * 2); w.q = take(rows * C * 2); w.o = take(rows * C * 2);
     w.ff = take(rows * 4 * C * 2);
     w.gn = take(fise_groupnorm_stats_workspace_bytes(B, H, W, G));
+    w.at_bytes = attention_workspace_bytes(B, n_active * tile * tile, H * W, C, heads > 0 ? heads : 1);
+    w.at = take(w.at_bytes);
     w.total = c;
     return w;
 }
 size_t transformer_ws_bytes(const fise_transformer_args* a) {
-    return tr_ws(a->B, a->H, a->W, a->C, a->G, a->n_active, a->tile).total;
+    return tr_ws(a->B, a->H, a->W, a->C, a->G, a->heads, a->n_active, a->tile).total;
 }
 
 int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st) {
     const int B = a->B, H = a->H, W = a->W, C = a->C, Ma = a->n_active * a->tile * a->tile, rows = B * Ma;
-    const TrWs wl = tr_ws(B, H, W, C, a->G, a->n_active, a->tile);
+    const TrWs wl = tr_ws(B, H, W, C, a->G, a->heads, a->n_active, a->tile);
     char* ws = (char*)workspace;
     float* hb = (float*)(ws + wl.h);                 // residual stream of the active tokens, float
     bf16_t* nb = (bf16_t*)(ws + wl.n); bf16_t* qb = (bf16_t*)(ws + wl.q); bf16_t* ob = (bf16_t*)(ws + wl.o);
@@ -120,14 +130,14 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     qkv.out[1] = (bf16_t*)a->K_cache; qkv.out_mode[1] = OUT_MAP;
     qkv.out[2] = (bf16_t*)a->Vt_cache; qkv.out_mode[2] = OUT_TOKENS_T;
     if (int e = launch_igemm(qkv, iw, st)) return e;
-    if (int e = launch_attention(qb, a->K_cache, a->Vt_cache, B, Ma, H * W, H * W, C, a->heads, scale, ob, st)) return e;
+    if (int e = launch_attention(qb, a->K_cache, a->Vt_cache, B, Ma, H * W, H * W, C, a->heads, scale, ob, ws + wl.at, wl.at_bytes, st)) return e;
     IgemmArgs o1 = lin(ob, C, a->o1_w, a->o1_b, C); into_h(o1);
     if (int e = launch_igemm(o1, iw, st)) return e;
     // cross-attention against the context K/V
     if (int e = launch_ln_rows(hb, 1, rows, C, a->ln2_g, a->ln2_b, 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
     IgemmArgs q2 = lin(nb, C, a->q2_w, nullptr, C); q2.out[0] = qb;
     if (int e = launch_igemm(q2, iw, st)) return e;
-    if (int e = launch_attention(qb, a->K_ctx, a->Vt_ctx, B, Ma, a->n_ctx, a->n_ctx_stride, C, a->heads, scale, ob, st)) return e;
+    if (int e = launch_attention(qb, a->K_ctx, a->Vt_ctx, B, Ma, a->n_ctx, a->n_ctx_stride, C, a->heads, scale, ob, nullptr, 0, st)) return e;
     IgemmArgs o2 = lin(ob, C, a->o2_w, a->o2_b, C); into_h(o2);
     if (int e = launch_igemm(o2, iw, st)) return e;
     // feed-forward: LN -> first GEMM with the GEGLU gate in its epilogue -> second GEMM + residual
@@ -230,7 +240,8 @@ extern "C" int fise_context_kv(const void* ctx, const void* Wk, const void* Wv, 
 extern "C" size_t fise_masked_attention_workspace_bytes(int B, int C, int n_active, int tile) {
     if (B < 1 || C < 1 || n_active < 0 || tile < 1) return 0;
     const size_t rows = (size_t)B * n_active * tile * tile;
-    return 3 * align256(rows * C * sizeof(bf16_t)) + 256;
+    // the key-split scratch is sized for the longest key set a caller can pass (a 128 x 128 token map)
+    return 3 * align256(rows * C * sizeof(bf16_t)) + attention_workspace_bytes(B, n_active * tile * tile, 128 * 128, C, 8) + 256;
 }
 
 extern "C" int fise_masked_attention(const void* x, const void* ln_gamma, const void* ln_beta, const void* Wq, const void* Wk,
@@ -274,9 +285,9 @@ extern "C" int fise_masked_attention(const void* x, const void* ln_gamma, const 
         if (int e = launch_igemm(g, iw, st)) return e;
         g.w = (const bf16_t*)Wv; g.out[0] = (bf16_t*)Vt_cache; g.out_mode[0] = OUT_TOKENS_T;
         if (int e = launch_igemm(g, iw, st)) return e;
-        if (int e = launch_attention(qbuf, K_cache, Vt_cache, B, Ma, H * W, H * W, C, heads, scale, obuf, st)) return e;
+        if (int e = launch_attention(qbuf, K_cache, Vt_cache, B, Ma, H * W, H * W, C, heads, scale, obuf, ws + 3 * buf, workspace_bytes - 3 * buf, st)) return e;
     } else {
-        if (int e = launch_attention(qbuf, K_ctx, Vt_ctx, B, Ma, n_ctx, n_ctx_stride, C, heads, scale, obuf, st)) return e;
+        if (int e = launch_attention(qbuf, K_ctx, Vt_ctx, B, Ma, n_ctx, n_ctx_stride, C, heads, scale, obuf, nullptr, 0, st)) return e;
     }
     IgemmArgs o = linear_args(obuf, Ma, B, C, Wo, bo, C);
     o.tile_idx = tile_idx; o.tile = tile; o.tiles_w = W / tile; o.Ho = H; o.Wo = W;

@@ -29,14 +29,19 @@ typedef __attribute__((ext_vector_type(8))) short bf16x8_t;   // MFMA operand (8
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
+typedef __bf16 hw_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2_t __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// two floats -> packed bf16 pair (lo in bits 0..15), round to nearest even: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ unsigned f2bf2(float lo, float hi) {
+    hw_f32x2_t v = {lo, hi};
+    hw_bf16x2_t r = __builtin_convertvector(v, hw_bf16x2_t);
+    return *reinterpret_cast<unsigned*>(&r);
 }
-__device__ __forceinline__ float silu_f(float u) { return u / (1.0f + __expf(-u)); }
+__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(f2bf2(f, 0.f) & 0xffffu); }
+// x * sigmoid(x); the reciprocal is the hardware approximation (1 ulp), far below bf16 resolution
+__device__ __forceinline__ float silu_f(float u) { return u * __builtin_amdgcn_rcpf(1.0f + __expf(-u)); }
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {

@@ -33,6 +33,7 @@ struct IgemmArgs {
     const bf16_t* s0; const bf16_t* s1; int S0, S1; const bf16_t* w2; const bf16_t* bias2; int K2;
     // ---- split-K (splits == 1: none)
     int splits; float* partial;
+    long long* dbg;                                     // development aid: per-workgroup phase timestamps (null = off)
 };
 
 // Scratch of the launcher: GroupNorm (scale, shift) table and the parked partial sums of split-K launches.
@@ -55,7 +56,13 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
 int launch_small_linear(const float* in, int B, int K, const void* W, const void* bias, int N, int silu_out, float* out,
                         hipStream_t st);
 int launch_iota(int* p, int n, hipStream_t st);
+// act[B,H,W,C0+C1] = GroupNorm(x0|x1) (+SiLU) with the given statistics at the active tiles and their one-pixel ring.
+int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, int H, int W, const float* mean, const float* rstd,
+                       const void* gamma, const void* beta, int G, int silu, const int* tile_idx, int n_active, int tile, void* act,
+                       hipStream_t st);
+// ws: scratch for the key-split partials (attention_workspace_bytes; null or too small = no key split)
+size_t attention_workspace_bytes(int B, int M, int n_keys, int C, int heads);
 int launch_attention(const void* q, const void* K, const void* Vt, int B, int M, int n_keys, int n_stride, int C,
-                     int heads, float scale, void* out, hipStream_t st);
+                     int heads, float scale, void* out, void* ws, size_t ws_bytes, hipStream_t st);
 
 }  // namespace fise

@@ -54,12 +54,13 @@ __device__ __forceinline__ void epilogue_store(const IgemmArgs& a, int gm, int b
 }
 
 // BK: K elements per step (64, or 32 for channel counts that are not multiples of 64)
-template <int BM, int BN, int WGM, int WGN, int BK>
-__global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
-    static_assert(WGM * WGN == 4, "four waves");
+// PRO: compiled with the GroupNorm(+SiLU) prologue (the other instantiation carries none of its code)
+template <int BM, int BN, int WGM, int WGN, int BK, bool PRO>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a) {
+    constexpr int NT = 64 * WGM * WGN;                 // threads: one wave per (WM x WN) sub-tile
     constexpr int LDT = BK + 8;                        // LDS row pitch in bf16: 16-byte aligned, not a power of two
     constexpr int TPR = BK / 8;                        // threads per tile row (16 bytes each)
-    constexpr int RP = 256 / TPR;                      // tile rows covered per pass
+    constexpr int RP = NT / TPR;                       // tile rows covered per pass
     constexpr int WM = BM / WGM, WN = BN / WGN;        // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;          // 32x32 MFMA blocks per wave
     static_assert(TM >= 1 && TN >= 1, "wave tile too small");
@@ -74,12 +75,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int rows = a.B * a.Ma;
+    long long* dbg = a.dbg ? a.dbg + 8 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) : nullptr;
+#define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
+    FISE_STAMP(0);
     const int m0 = blockIdx.x * BM;
     const int Cin = a.C0 + a.C1;
     const int pad = a.ksize >> 1;
 
     // ---- row table
-    for (int r = tid; r < BM; r += 256) {
+    for (int r = tid; r < BM; r += NT) {
         RowInfo ri; ri.b = 0; ri.y = 0; ri.x = 0; ri.ok = 0;
         const int gm = m0 + r;
         if (gm < rows) {
@@ -101,12 +105,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     // this tile, staged in LDS.  A range shorter than Cin is stored rotated: slot = (c - c_lo) mod Cin.
     const int b_first = m0 / a.Ma;
     int c_lo = 0, clen = Cin;
-    if (a.pro != PRO_NONE) {
+    if (PRO && a.pro != PRO_NONE) {
         const int k_lo = kc_begin * BK, k_hi = min(kc_end, nsteps1) * BK;
         if (k_hi - k_lo < Cin) { c_lo = k_lo % Cin; clen = max(k_hi - k_lo, 0); }
         const int b_last = min(a.B - 1, (m0 + BM - 1) / a.Ma);
         const int cpg = Cin / a.G;
-        for (int e = tid * 2; e < (b_last - b_first + 1) * clen; e += 512) {      // two entries (16 bytes) per thread
+        for (int e = tid * 2; e < (b_last - b_first + 1) * clen; e += 2 * NT) {   // two entries (16 bytes) per thread
             const int bb = b_first + e / clen;
             int c = c_lo + e % clen; if (c >= Cin) c -= Cin;
             if (a.gn_table) {
@@ -122,6 +126,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         }
     }
     __syncthreads();
+    FISE_STAMP(1);
 
     // ---- per-thread load slots: TPR threads per tile row, RP rows per pass
     const int seg = tid % TPR;                         // which 8-element segment of the K step
@@ -149,59 +154,90 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         brow[j] = wr; bok[j] = ok;
     }
 
-    // running (tap, channel) position of the load cursor in the main product
-    int tap = 0, cc = 0;
-    if (kc_begin < nsteps1) { const int k0 = kc_begin * BK; tap = k0 / Cin; cc = k0 % Cin; }
+    // ---- load cursor.  All address arithmetic that does not change from step to step is done here or
+    // when the cursor moves to the next tap; a step itself costs one multiply-add per A slot and one
+    // pointer bump per B slot (the K loop is otherwise bound by instruction issue, not by memory).
+    //   phase 0: main product (taps x channels of a0 | a1), phase 1: 1x1 side product (s0 | s1)
+    const bf16_t* p_a0 = a.a0; const bf16_t* p_a1 = a.a1;   // sources of the current phase
+    int p_C0 = a.C0, p_Ct = Cin;                            // channels of the first source / of both
+    bool side = false;
+    int tap = 0, cc = 0;                                    // tap index, channel cursor within the concatenation
+    int pix[AL];                                            // input pixel (or compact row) of the current tap, -1 = none
+    int opix[AL];                                           // output pixel: the side product reads its sources there
+    const bf16_t* bp[BL];                                   // weight pointer of the step about to be issued
+#pragma unroll
+    for (int j = 0; j < AL; ++j) opix[j] = aok[j] ? (ab[j] * a.Ho + ay[j]) * a.Wo + ax[j] : -1;
+    auto set_tap = [&]() {
+        const int ky = tap / a.ksize, kx = tap - ky * a.ksize;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            int p = -1;
+            if (aok[j]) {
+                if (a.a_compact) p = m0 + lrow + RP * j;
+                else if (a.ups) {
+                    const int uy = ay[j] + ky - pad, ux = ax[j] + kx - pad;
+                    if (uy >= 0 && uy < 2 * a.Hin && ux >= 0 && ux < 2 * a.Win) p = (ab[j] * a.Hin + (uy >> 1)) * a.Win + (ux >> 1);
+                } else {
+                    const int iy = ay[j] * a.stride + ky - pad, ix = ax[j] * a.stride + kx - pad;
+                    if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) p = (ab[j] * a.Hin + iy) * a.Win + ix;
+                }
+            }
+            pix[j] = p;
+        }
+    };
+    auto enter_side = [&](int c_start) {
+        side = true; p_a0 = a.s0; p_a1 = a.s1; p_C0 = a.S0; p_Ct = a.K2; cc = c_start;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) pix[j] = opix[j];
+#pragma unroll
+        for (int j = 0; j < BL; ++j) bp[j] = a.w2 + (bok[j] ? (size_t)brow[j] * a.K2 + c_start + seg * 8 : 0);
+    };
+    if (kc_begin < nsteps1) {
+        const int k0 = kc_begin * BK;
+        tap = k0 / Cin; cc = k0 - tap * Cin;
+        set_tap();
+#pragma unroll
+        for (int j = 0; j < BL; ++j) bp[j] = a.w + (bok[j] ? (size_t)brow[j] * a.K + k0 + seg * 8 : 0);
+    } else {
+        enter_side((kc_begin - nsteps1) * BK);
+    }
+    int kc_next = kc_begin;                                 // the step the cursor points at
 
     // register FIFO: stage s holds the raw data of K step (kc_begin + i) with i % PF == s
     uint4 ra[PF][AL], rb[PF][BL];
-    int st_cc[PF]; unsigned st_in[PF];                 // per stage: channel offset (for the prologue), in-image bits
+    int st_cc[PF]; unsigned st_in[PF];                 // per stage: slot in the GroupNorm table (-1: none), in-image bits
 
-    // Loads of K step kc into FIFO stage s.  Every slot issues exactly one 16-byte load (rows or taps
-    // that do not exist read a harmless in-bounds address and are zeroed when the stage is stashed),
-    // so the number of loads in flight is the same on every path and the waits stay partial.
-    auto issue = [&](int kc, int s) {
-        const bool side = kc >= nsteps1;
-        const int c2 = (kc - nsteps1) * BK;
-        const int ky = tap / a.ksize, kx = tap % a.ksize;
-        const int ccur = side ? c2 : cc;
-        const int split = side ? a.S0 : a.C0;
-        const bool second = ccur >= split;
-        const bf16_t* src = side ? (second ? a.s1 : a.s0) : (second ? a.a1 : a.a0);
-        const int Cs = side ? (second ? a.S1 : a.S0) : (second ? a.C1 : a.C0);
-        const int cs = (second ? ccur - split : ccur) + seg * 8;
-        const int Hs = side ? a.Ho : a.Hin, Ws = side ? a.Wo : a.Win;
+    // Loads of the next K step into FIFO stage s.  Every slot issues exactly one 16-byte load (rows or
+    // taps that do not exist, and steps past the end of the range, read a harmless in-bounds address
+    // and are zeroed or ignored later), so the number of loads in flight is the same on every path.
+    auto issue = [&](int s) {
+        const bool live = kc_next < kc_end;
+        const bool second = cc >= p_C0;
+        const bf16_t* src = second ? p_a1 : p_a0;
+        const int Cs = second ? p_Ct - p_C0 : p_C0;
+        const int cs = (second ? cc - p_C0 : cc) + seg * 8;
         unsigned inbits = 0;
 #pragma unroll
         for (int j = 0; j < AL; ++j) {
-            size_t off = 0; bool in = aok[j];
-            if (a.a_compact) {
-                off = (size_t)(m0 + lrow + RP * j) * Cs;
-            } else {
-                int iy, ix;
-                if (side) { iy = ay[j]; ix = ax[j]; }
-                else if (a.ups) {
-                    const int uy = ay[j] + ky - pad, ux = ax[j] + kx - pad;
-                    in = in && uy >= 0 && uy < 2 * a.Hin && ux >= 0 && ux < 2 * a.Win;
-                    iy = uy >> 1; ix = ux >> 1;
-                } else {
-                    iy = ay[j] * a.stride + ky - pad; ix = ax[j] * a.stride + kx - pad;
-                    in = in && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win;
-                }
-                off = (((size_t)ab[j] * Hs + iy) * Ws + ix) * Cs;
-            }
-            off = in ? off + cs : 0;
-            ra[s][j] = *reinterpret_cast<const uint4*>(src + off);
+            const bool in = live && pix[j] >= 0;
+            const unsigned off = in ? (unsigned)pix[j] * (unsigned)Cs + (unsigned)cs : 0u;
+            ra[s][j] = *reinterpret_cast<const uint4*>((in ? src : a.a0) + off);
             inbits |= (in ? 1u : 0u) << j;
         }
-        const bf16_t* wsrc = side ? a.w2 : a.w;
-        const size_t wk = side ? (size_t)a.K2 : (size_t)a.K;
-        const size_t wc = (side ? (size_t)c2 : (size_t)kc * BK) + seg * 8;
 #pragma unroll
-        for (int j = 0; j < BL; ++j) rb[s][j] = *reinterpret_cast<const uint4*>(wsrc + (bok[j] ? (size_t)brow[j] * wk + wc : 0));
+        for (int j = 0; j < BL; ++j) rb[s][j] = *reinterpret_cast<const uint4*>(live ? bp[j] : a.w);
         st_cc[s] = side ? -1 : (cc >= c_lo ? cc - c_lo : cc - c_lo + Cin);     // slot in the staged table
         st_in[s] = inbits;
-        if (!side) { cc += BK; if (cc >= Cin) { cc = 0; ++tap; } }
+        if (live) {
+            ++kc_next;
+#pragma unroll
+            for (int j = 0; j < BL; ++j) bp[j] += bok[j] ? BK : 0;
+            cc += BK;
+            if (!side) {
+                if (kc_next == nsteps1) { if (kc_next < kc_end) enter_side(0); }
+                else if (cc >= Cin) { cc = 0; ++tap; set_tap(); }
+            }
+        }
     };
     // registers of stage s -> LDS buffer `buf`, applying the GroupNorm(+SiLU) prologue to in-image elements
     auto stash = [&](int s, int buf) {
@@ -210,7 +246,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             uint4 v = ra[s][j];
             const bool in = (st_in[s] >> j) & 1u;
             if (!in) v = make_uint4(0, 0, 0, 0);
-            if (a.pro != PRO_NONE && st_cc[s] >= 0 && in) {
+            if (PRO && a.pro != PRO_NONE && st_cc[s] >= 0 && in) {
                 const float2* ss = gn_ss + (ab[j] - b_first) * clen + st_cc[s] + seg * 8;
                 unsigned w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -219,7 +255,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
                     float u0 = __uint_as_float(w4[e] << 16) * s0.x + s0.y;
                     float u1 = __uint_as_float(w4[e] & 0xffff0000u) * s1.x + s1.y;
                     if (a.pro == PRO_GN_SILU) { u0 = silu_f(u0); u1 = silu_f(u1); }
-                    w4[e] = (unsigned)f2bf(u0) | ((unsigned)f2bf(u1) << 16);
+                    w4[e] = f2bf2(u0, u1);
                 }
                 v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
@@ -238,10 +274,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // fill the FIFO (steps past the end re-read the last step: never used, keeps the load count uniform)
-    const int kc_last = kc_end - 1;
+    // fill the FIFO
 #pragma unroll
-    for (int s = 0; s < PF; ++s) issue(min(kc_begin + s, kc_last), s);
+    for (int s = 0; s < PF; ++s) issue(s);
+    FISE_STAMP(2);
 
     for (int kc0 = kc_begin; kc0 < kc_end; kc0 += PF) {
 #pragma unroll
@@ -250,7 +286,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             if (kc >= kc_end) break;                   // uniform across the workgroup
             const int buf = s & 1;                     // PF is even: the parity of kc - kc_begin
             stash(s, buf);
-            issue(min(kc + PF, kc_last), s);
+            if (kc == kc_begin) FISE_STAMP(3);
+            issue(s);
             lds_barrier();
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
@@ -269,11 +306,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             }
         }
     }
-    if (kc_begin >= kc_end) { /* an empty split contributes zeros */ }
+    FISE_STAMP(4);
 
     // ---- split-K: park this workgroup's partial sums as partial[z][row][weight row]; a second small
-    // kernel adds them up in split order and applies the epilogue (no cross-workgroup hand-over inside
-    // this kernel: that would need device-scope fences, which write back and invalidate the L2s).
+    // kernel adds them up in split order and applies the epilogue.  (Handing the partials over inside
+    // this kernel needs either device-scope fences, which write back and invalidate whole L2s, or
+    // L2-bypassing accesses, which measured slower than the extra launch.)
     if (a.splits > 1) {
         const int ncols = a.geglu ? 2 * a.N : a.N;
         float* P = a.partial + (size_t)blockIdx.z * rows * ncols;
@@ -297,6 +335,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
                     if (m0 + r < rows) P[(size_t)(m0 + r) * ncols + wr] = acc[i][j][e];
                 }
         }
+        FISE_STAMP(5);
         return;
     }
 
@@ -328,30 +367,51 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             }
         }
     }
+    FISE_STAMP(5);
+#undef FISE_STAMP
 }
 
-// Second half of a split-K launch: one thread per output element sums the parked partials in split
-// order (deterministic) and applies the epilogue.
+// Second half of a split-K launch: one thread per four output columns sums the parked partials in
+// split order (deterministic; 16-byte loads, four splits in flight) and applies the epilogue.
 __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const int rows = a.B * a.Ma;
+    const int nq = a.N / 4;                              // N % 4 == 0 (checked by the launcher)
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (long long)rows * a.N) return;
-    const int gm = (int)(i / a.N), col = (int)(i % a.N);
+    if (i >= (long long)rows * nq) return;
+    const int gm = (int)(i / nq), col = (int)(i % nq) * 4;
     const int ncols = a.geglu ? 2 * a.N : a.N;
     const size_t stride = (size_t)rows * ncols;
     const float* P = a.partial + (size_t)gm * ncols + col;
-    float v = a.bias ? bf2f(a.bias[col]) : 0.f;
-    if (a.bias2) v += bf2f(a.bias2[col]);
-    for (int z = 0; z < a.splits; ++z) v += P[z * stride];
-    if (a.geglu) {
-        float g = a.bias ? bf2f(a.bias[col + a.N]) : 0.f;
-        for (int z = 0; z < a.splits; ++z) g += P[z * stride + a.N];
-        v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
+    auto add = [](float4& d, const float4& x) { d.x += x.x; d.y += x.y; d.z += x.z; d.w += x.w; };
+    int z = 0;
+    for (; z + 4 <= a.splits; z += 4) {
+        const float4 p0 = *reinterpret_cast<const float4*>(P + (z + 0) * stride), p1 = *reinterpret_cast<const float4*>(P + (z + 1) * stride);
+        const float4 p2 = *reinterpret_cast<const float4*>(P + (z + 2) * stride), p3 = *reinterpret_cast<const float4*>(P + (z + 3) * stride);
+        add(v, p0); add(v, p1); add(v, p2); add(v, p3);
+        if (a.geglu) {
+            const float4 q0 = *reinterpret_cast<const float4*>(P + (z + 0) * stride + a.N), q1 = *reinterpret_cast<const float4*>(P + (z + 1) * stride + a.N);
+            const float4 q2 = *reinterpret_cast<const float4*>(P + (z + 2) * stride + a.N), q3 = *reinterpret_cast<const float4*>(P + (z + 3) * stride + a.N);
+            add(g, q0); add(g, q1); add(g, q2); add(g, q3);
+        }
+    }
+    for (; z < a.splits; ++z) {
+        add(v, *reinterpret_cast<const float4*>(P + z * stride));
+        if (a.geglu) add(g, *reinterpret_cast<const float4*>(P + z * stride + a.N));
     }
     int y = 0, x = gm % a.Ma;
     const int b = gm / a.Ma;
     if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
-    epilogue_store(a, gm, b, y, x, col, v);
+    const float vv[4] = {v.x, v.y, v.z, v.w}, gg[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float r = vv[q] + (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
+        if (a.geglu) {
+            const float gt = gg[q] + (a.bias ? bf2f(a.bias[col + q + a.N]) : 0.f);
+            r = r * (0.5f * gt * (1.0f + erff(gt * 0.70710678118654752f)));
+        }
+        epilogue_store(a, gm, b, y, x, col + q, r);
+    }
 }
 
 // (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given statistics
@@ -380,22 +440,25 @@ int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hip
     return FISE_OK;
 }
 
-// How many workgroups share the K loop of one output tile.  A CU can only pull a few tens of GB/s
-// on its own, so what matters is that every CU streams part of the operands: aim at two to three
-// workgroups per CU, keep at least two K steps per workgroup, and bound the parked partials.
+long long* g_igemm_dbg = nullptr;      // set through fise_debug_timing_buffer (development aid)
+
+// How many workgroups share the K loop of one output tile.  A CU pulls operands at a few tens of
+// GB/s whatever runs on it, so what matters most is that every CU streams part of the operands: aim
+// at roughly two workgroups per CU, keep at least two K steps per workgroup, and keep the parked
+// partials (written once, read once by the reduce launch) below the operand traffic.  Measured on
+// MI355X, this simple rule beat cost models that tried to price the second launch.
 template <int BM, int BN, int BK>
 static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) {
     if (!ws || !ws->partial) return 1;
     const int rows = a.B * a.Ma;
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
-    static const int target = [] { const char* e = getenv("FISE_SPLIT_TARGET"); return e ? atoi(e) : 640; }();
+    static const int target = [] { const char* e = getenv("FISE_SPLIT_TARGET"); return e ? atoi(e) : 480; }();
     if (tiles * 2 > target || nsteps < 4) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
     s = std::min(s, nsteps / 2);
     s = std::min<int>(s, (int)(ws->partial_bytes / out_bytes));
-    // partial traffic (written once, read once) should stay below the operand traffic of the launch
     const double op_bytes = 2.0 * (double)(a.K + a.K2) * ((double)ncols * ceil_div(rows, BM) + (double)rows * ceil_div(ncols, BN));
     while (s > 1 && 2.0 * s * out_bytes > op_bytes) --s;
     return std::max(s, 1);
@@ -405,8 +468,9 @@ template <int BM, int BN, int WGM, int WGN, int BK>
 static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipStream_t st) {
     const int rows = a.B * a.Ma;
     const int ncols = a.geglu ? 2 * a.N : a.N;
-    a.splits = pick_splits<BM, BN, BK>(a, ws, ncols);
+    a.splits = (a.N % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
     if (a.splits > 1) a.partial = ws->partial;
+    a.dbg = g_igemm_dbg;
     dim3 grid(ceil_div(rows, BM), ceil_div(ncols, BN), a.splits);
     size_t shmem = 0;
     if (a.pro != PRO_NONE) {
@@ -424,7 +488,7 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         if (shmem > kMaxDyn) return fail(FISE_ERR_SHAPE, "igemm: GroupNorm table of %zu bytes does not fit in LDS", shmem);
         static bool raised = false;                 // once per instantiation: static tiles + table may exceed 64 KB
         if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN, BK>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN, BK, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDyn) != hipSuccess)
                 return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
             raised = true;
@@ -433,10 +497,11 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     const double flops = 2.0 * rows * (double)ncols * ((double)a.K + a.K2);
     const double bytes = 2.0 * ((double)ncols * ((double)a.K + a.K2) + (double)rows * (a.C0 + a.C1 + a.S0 + a.S1) + (double)rows * a.N);
     ProfileScope prof(prof_kind, flops, bytes, st);
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK>), grid, dim3(256), shmem, st, a);
+    if (a.pro != PRO_NONE) hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, true>), grid, dim3(64 * WGM * WGN), shmem, st, a);
+    else hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, false>), grid, dim3(64 * WGM * WGN), 0, st, a);
     FISE_CHECK_LAUNCH("igemm");
     if (a.splits > 1) {
-        const long long n = (long long)rows * a.N;
+        const long long n = (long long)rows * (a.N / 4);
         hipLaunchKernelGGL(igemm_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
         FISE_CHECK_LAUNCH("igemm reduce");
     }
@@ -461,15 +526,20 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     if (a.nsect < 1 || a.nsect > 3 || a.nsect * a.sect_n != a.N) return fail(FISE_ERR_SHAPE, "igemm: sections");
     if (a.K2 != a.S0 + a.S1 || a.S0 % 32 || a.S1 % 32 || (a.K2 > 0 && (!a.w2 || !a.s0 || a.a_compact || a.stride != 1 || a.ups)))
         return fail(FISE_ERR_SHAPE, "igemm: side product");
-    const bool wide = rows >= 4096 && a.N >= 128;          // dense-sized problems: 128x128 tiles
+    static const int wide_rows = [] { const char* e = getenv("FISE_WIDE_ROWS"); return e ? atoi(e) : 4096; }();
+    const bool wide = rows >= wide_rows && a.N >= 128;     // dense-sized problems: 128x128 tiles
     if (a.geglu) {
-        if (wide) return launch_cfg<128, 128, 2, 2>(a, ws, PROF_IGEMM_WIDE, st);
+        if (wide) return launch_cfg<128, 128, 4, 2>(a, ws, PROF_IGEMM_WIDE, st);
         if (rows <= 32) return launch_cfg<32, 256, 1, 4>(a, ws, PROF_IGEMM_GEGLU, st);
         return launch_cfg<64, 128, 2, 2>(a, ws, PROF_IGEMM_GEGLU, st);
     }
-    if (wide) return launch_cfg<128, 128, 2, 2>(a, ws, PROF_IGEMM_WIDE, st);
+    if (wide) return launch_cfg<128, 128, 2, 4>(a, ws, PROF_IGEMM_WIDE, st);
     if (rows <= 32) return launch_cfg<32, 128, 1, 4>(a, ws, PROF_IGEMM, st);
     return launch_cfg<64, 64, 2, 2>(a, ws, PROF_IGEMM, st);
 }
 
 }  // namespace fise
+
+// Development aid, not part of the documented ABI: a device buffer of 8 x int64 per workgroup that
+// the gathered-GEMM kernels fill with wall-clock stamps of their phases (null switches it off).
+extern "C" void fise_debug_timing_buffer(void* dev) { fise::g_igemm_dbg = (long long*)dev; }

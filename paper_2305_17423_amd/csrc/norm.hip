@@ -1,6 +1,7 @@
 // Normalisation kernels: dense GroupNorm statistics (two-stage, deterministic),
 // masked GroupNorm+SiLU with given statistics, per-row LayerNorm of compact
 // token buffers.
+#include <algorithm>
 #include "igemm.h"
 
 namespace fise {
@@ -78,8 +79,68 @@ __global__ void masked_gn_silu_kernel(const T* __restrict__ x, const float* __re
     Elem<T>::st(y + off, silu_f(u));
 }
 
-// LayerNorm of rows -> compact out[rows, C] (bf16), one wave per row, two passes (mean,
-// then centred variance) in float.  With tile_idx the rows are gathered from a token map.
+// SiLU(GroupNorm(x)) with given statistics, written once for every pixel of the active tiles AND
+// their one-pixel ring (clipped to the image) into a scratch map act[B,H,W,C0+C1]: the 3x3
+// convolution that follows reads plain activations instead of re-evaluating the nonlinearity for
+// each of its nine taps and each of its column tiles.  Neighbouring tiles write identical values
+// to their shared ring.  One thread per (pixel, 8 channels).
+__global__ __launch_bounds__(256) void gn_act_halo_kernel(const bf16_t* __restrict__ x0, const bf16_t* __restrict__ x1, int C0,
+                                                          int C1, int H, int W, const float* __restrict__ mean,
+                                                          const float* __restrict__ rstd, const bf16_t* __restrict__ gamma,
+                                                          const bf16_t* __restrict__ beta, int G, int silu,
+                                                          const int* __restrict__ tile_idx, int tile, bf16_t* __restrict__ act) {
+    const int C = C0 + C1, chunks = C / 8, side = tile + 2;
+    const int t = tile_idx[blockIdx.x], b = blockIdx.y;
+    const int tiles_w = W / tile;
+    const int y0 = (t / tiles_w) * tile - 1, x0p = (t % tiles_w) * tile - 1;
+    const int items = side * side * chunks;
+    const int cpg = C / G;
+    for (int it = blockIdx.z * 256 + threadIdx.x; it < items; it += gridDim.z * 256) {
+        const int p = it / chunks, ch = it % chunks;
+        const int y = y0 + p / side, x = x0p + p % side;
+        if (y < 0 || y >= H || x < 0 || x >= W) continue;
+        const int c = ch * 8;
+        const size_t pix = ((size_t)b * H + y) * W + x;
+        const uint4 v = c < C0 ? *reinterpret_cast<const uint4*>(x0 + pix * C0 + c)
+                               : *reinterpret_cast<const uint4*>(x1 + pix * C1 + (c - C0));
+        const uint4 gv = *reinterpret_cast<const uint4*>(gamma + c), bv = *reinterpret_cast<const uint4*>(beta + c);
+        const unsigned xw[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w}, bw[4] = {bv.x, bv.y, bv.z, bv.w};
+        unsigned ow[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float r[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int g = (c + 2 * e + q) / cpg;
+                const float xv = q ? __uint_as_float(xw[e] & 0xffff0000u) : __uint_as_float(xw[e] << 16);
+                const float ga = q ? __uint_as_float(gw[e] & 0xffff0000u) : __uint_as_float(gw[e] << 16);
+                const float be = q ? __uint_as_float(bw[e] & 0xffff0000u) : __uint_as_float(bw[e] << 16);
+                const float sc = rstd[b * G + g] * ga;
+                float u = xv * sc + (be - mean[b * G + g] * sc);
+                if (silu) u = silu_f(u);
+                r[q] = u;
+            }
+            ow[e] = f2bf2(r[0], r[1]);
+        }
+        *reinterpret_cast<uint4*>(act + pix * C + c) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+}
+
+int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, int H, int W, const float* mean, const float* rstd,
+                       const void* gamma, const void* beta, int G, int silu, const int* tile_idx, int n_active, int tile, void* act,
+                       hipStream_t st) {
+    if (n_active <= 0) return FISE_OK;
+    const int items = (tile + 2) * (tile + 2) * ((C0 + C1) / 8);
+    const int z = std::max(1, std::min(64, ceil_div(items, 512)));
+    hipLaunchKernelGGL(gn_act_halo_kernel, dim3(n_active, B, z), dim3(256), 0, st, (const bf16_t*)x0, (const bf16_t*)x1, C0, C1, H, W,
+                       mean, rstd, (const bf16_t*)gamma, (const bf16_t*)beta, G, silu, tile_idx, tile, (bf16_t*)act);
+    FISE_CHECK_LAUNCH("gn activation with halo");
+    return FISE_OK;
+}
+
+// LayerNorm of rows -> compact out[rows, C] (bf16), one wave per row held in registers (C <= 2048):
+// one read, mean, centred variance, one write.  With tile_idx the rows are gathered from a token map.
+constexpr int LN_MAXJ = 32;
 template <typename T>
 __global__ __launch_bounds__(256) void ln_rows_kernel(const T* __restrict__ in, int rows, int C,
                                                       const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta,
@@ -96,21 +157,36 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const T* __restrict__ in, 
     } else {
         r = in + (size_t)row * C;
     }
+    float v[LN_MAXJ];
     float s = 0.f;
-    for (int c = lane; c < C; c += 64) s += Elem<T>::ld(r + c);
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int c = lane + 64 * j;
+        v[j] = c < C ? Elem<T>::ld(r + c) : 0.f;
+        s += v[j];
+    }
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
     const float mu = s / C;
     float q = 0.f;
-    for (int c = lane; c < C; c += 64) { const float d = Elem<T>::ld(r + c) - mu; q += d * d; }
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int c = lane + 64 * j;
+        const float d = c < C ? v[j] - mu : 0.f;
+        q += d * d;
+    }
     for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
     const float rs = rsqrtf(q / C + eps);
-    for (int c = lane; c < C; c += 64)
-        out[(size_t)row * C + c] = f2bf((Elem<T>::ld(r + c) - mu) * rs * bf2f(gamma[c]) + bf2f(beta[c]));
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int c = lane + 64 * j;
+        if (c < C) out[(size_t)row * C + c] = f2bf((v[j] - mu) * rs * bf2f(gamma[c]) + bf2f(beta[c]));
+    }
 }
 
 int launch_ln_rows(const void* in, int in_f32, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
                    const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st) {
     if (rows <= 0) return FISE_OK;
+    if (C > 64 * LN_MAXJ) return fail(FISE_ERR_SHAPE, "layernorm rows: C=%d > %d", C, 64 * LN_MAXJ);
     const dim3 grid(ceil_div(rows, 4)), block(256);
     if (in_f32)
         hipLaunchKernelGGL(ln_rows_kernel<float>, grid, block, 0, st, (const float*)in, rows, C, (const bf16_t*)gamma,

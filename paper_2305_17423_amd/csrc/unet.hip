@@ -239,12 +239,12 @@ WsLayout ws_layout(const fise_unet* u, int n_tiles, int base_tile, const int* le
         const bool dense = level_dense && level_dense[m.lvl];
         if (m.kind == K_TR) {
             fise_transformer_args t{};
-            t.B = d.B; t.H = d.H >> m.lvl; t.W = d.W >> m.lvl; t.C = m.cout; t.G = d.groups;
+            t.B = d.B; t.H = d.H >> m.lvl; t.W = d.W >> m.lvl; t.C = m.cout; t.G = d.groups; t.heads = d.heads;
             t.n_active = level_tiles(d, base_tile, n_tiles, dense); t.tile = base_tile >> m.lvl;
             blk = std::max(blk, transformer_ws_bytes(&t));
         } else if (m.kind == K_RES) {
             fise_resnet_args r{};
-            r.B = d.B; r.H = d.H >> m.lvl; r.W = d.W >> m.lvl; r.G = d.groups;
+            r.B = d.B; r.H = d.H >> m.lvl; r.W = d.W >> m.lvl; r.G = d.groups; r.C0 = m.cin; r.C1 = m.cskip; r.Cout = m.cout;
             blk = std::max(blk, resnet_ws_bytes(&r));
         }
     }

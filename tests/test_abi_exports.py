@@ -35,9 +35,9 @@ def test_host_side_validation_without_gpu():
     assert "tile" in fb.fise_last_error()
     assert L.fise_mask_detect(a, a, 7, 1, 8, 8, 4, 0.1, 4, a, a, a, 4, a, None) == -3       # dtype
     assert L.fise_mask_downsample(a, 7, 8, a, None) == -2
-    assert L.fise_attention_active(a, a, a, fb.FISE_F32, 1, 4, 8, 8, 32, 4, 1.0, a, None) == -3
-    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 8, 8, 30, 4, 1.0, a, None) == -2   # C % heads
-    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 9, 9, 32, 4, 1.0, a, None) == -4   # stride % 8
+    assert L.fise_attention_active(a, a, a, fb.FISE_F32, 1, 4, 8, 8, 32, 4, 1.0, a, None, 0, None) == -3
+    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 8, 8, 30, 4, 1.0, a, None, 0, None) == -2   # C % heads
+    assert L.fise_attention_active(a, a, a, fb.FISE_BF16, 1, 4, 9, 9, 32, 4, 1.0, a, None, 0, None) == -4   # stride % 8
     args = fb.fise_conv_args()
     assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -1
     args.x0 = args.w = a; args.y_cache = 0x2000; args.B = 1; args.H = args.W = 8; args.C0 = 32; args.Cout = 32

@@ -49,6 +49,13 @@ def test_attention_active(fb, B, M, N, C, heads):
     fb.fise_attention_active(dev(q, "bf16"), dev(K, "bf16"), vt_dev(V, ns, poison=True), heads, 1 / math.sqrt(C // heads), out, n_keys=N)
     err = rel_err(host(out), want)
     assert err <= TOL["bf16"], err
+    # with scratch the key range may be split over workgroups and merged: same result
+    nb = fb.fise_attention_active_workspace_bytes(B, M, N, C, heads)
+    ws = torch.full((max(nb, 256),), 0x7F, dtype=torch.uint8, device=DEV)
+    out2 = torch.zeros((B, M, C), dtype=torch.bfloat16, device=DEV)
+    fb.fise_attention_active(dev(q, "bf16"), dev(K, "bf16"), vt_dev(V, ns, poison=True), heads, 1 / math.sqrt(C // heads), out2, n_keys=N, workspace=ws)
+    err2 = rel_err(host(out2), want)
+    assert err2 <= TOL["bf16"], err2
 
 
 def test_attention_closed_forms_on_device(fb):
