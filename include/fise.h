@@ -340,7 +340,8 @@ int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cach
  * (host objects; no device memory).  fise_profile_read(kind, ...) waits for the
  * events and returns the summed event time (ms), algorithmic FLOPs and bytes
  * and the number of launches recorded for `kind` (0 = gathered GEMM, 1 = the
- * same with the GEGLU epilogue, 2 = attention, 3 = wide-tile gathered GEMM);
+ * same with the GEGLU epilogue, 2 = attention incl. its merge launch, 3 = wide-tile
+ * gathered GEMM, 4 = split-K reduce launches);
  * kind = -1 clears the log.  All pointers host.  Not thread safe.
  * ------------------------------------------------------------------------ */
 int fise_profile_enable(int on);

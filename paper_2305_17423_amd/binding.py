@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfise.so")
+LIB_PATH = os.environ.get("FISE_LIB", os.path.join(_HERE, "libfise.so"))
 
 FISE_F32, FISE_BF16 = 0, 1
 FISE_STATS_CACHED, FISE_STATS_FRESH = 0, 1

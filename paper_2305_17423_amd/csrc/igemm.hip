@@ -19,9 +19,13 @@
 #include "igemm.h"
 #include "profile.h"
 
+#ifndef FISE_PF
+#define FISE_PF 2
+#endif
+
 namespace fise {
 
-constexpr int PF = 4;             // prefetch distance in K steps
+constexpr int PF = FISE_PF;             // prefetch distance in K steps
 
 struct RowInfo { int b, y, x, ok; };
 
@@ -454,7 +458,8 @@ static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) 
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
     static const int target = [] { const char* e = getenv("FISE_SPLIT_TARGET"); return e ? atoi(e) : 480; }();
-    if (tiles * 2 > target || nsteps < 4) return 1;
+    static const int min_steps = [] { const char* e = getenv("FISE_SPLIT_MIN_STEPS"); return e ? atoi(e) : 4; }();
+    if (tiles * 2 > target || nsteps < min_steps) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
     s = std::min(s, nsteps / 2);
@@ -496,12 +501,15 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     }
     const double flops = 2.0 * rows * (double)ncols * ((double)a.K + a.K2);
     const double bytes = 2.0 * ((double)ncols * ((double)a.K + a.K2) + (double)rows * (a.C0 + a.C1 + a.S0 + a.S1) + (double)rows * a.N);
-    ProfileScope prof(prof_kind, flops, bytes, st);
-    if (a.pro != PRO_NONE) hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, true>), grid, dim3(64 * WGM * WGN), shmem, st, a);
-    else hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, false>), grid, dim3(64 * WGM * WGN), 0, st, a);
+    {
+        ProfileScope prof(prof_kind, flops, bytes, st);      // brackets the GEMM launch alone
+        if (a.pro != PRO_NONE) hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, true>), grid, dim3(64 * WGM * WGN), shmem, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, false>), grid, dim3(64 * WGM * WGN), 0, st, a);
+    }
     FISE_CHECK_LAUNCH("igemm");
     if (a.splits > 1) {
         const long long n = (long long)rows * (a.N / 4);
+        ProfileScope prof(PROF_REDUCE, 0.0, 2.0 * a.splits * (double)rows * ncols * 4.0, st);
         hipLaunchKernelGGL(igemm_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
         FISE_CHECK_LAUNCH("igemm reduce");
     }

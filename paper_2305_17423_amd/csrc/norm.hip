@@ -138,8 +138,9 @@ int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, in
     return FISE_OK;
 }
 
-// LayerNorm of rows -> compact out[rows, C] (bf16), one wave per row held in registers (C <= 2048):
-// one read, mean, centred variance, one write.  With tile_idx the rows are gathered from a token map.
+// LayerNorm of rows -> compact out[rows, C] (bf16).  General form: one wave per row held in
+// registers (C <= 2048): one read, mean, centred variance, one write.  With tile_idx the rows are
+// gathered from a token map.
 constexpr int LN_MAXJ = 32;
 template <typename T>
 __global__ __launch_bounds__(256) void ln_rows_kernel(const T* __restrict__ in, int rows, int C,
@@ -183,12 +184,57 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const T* __restrict__ in, 
     }
 }
 
+// Fast form for compact float rows with C = 20 * LPR (320 / 640 / 1280 at LPR = 16 / 32 / 64): LPR lanes
+// share a row, each holds 5 x float4 = 20 consecutive channels; 16-byte loads, 8-byte bf16 stores.
+template <int LPR>
+__global__ __launch_bounds__(256) void ln_rows20_kernel(const float* __restrict__ in, int rows, const bf16_t* __restrict__ gamma,
+                                                        const bf16_t* __restrict__ beta, float eps, bf16_t* __restrict__ out) {
+    constexpr int C = 20 * LPR, RPB = 256 / LPR;
+    const int row = blockIdx.x * RPB + threadIdx.x / LPR;
+    const int l = threadIdx.x % LPR;
+    if (row >= rows) return;                      // whole LPR-lane groups leave together
+    const float4* r = reinterpret_cast<const float4*>(in + (size_t)row * C + l * 20);
+    float4 v[5];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) { v[j] = r[j]; s += (v[j].x + v[j].y) + (v[j].z + v[j].w); }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mu = s / C;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const float a0 = v[j].x - mu, a1 = v[j].y - mu, a2 = v[j].z - mu, a3 = v[j].w - mu;
+        q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    const float rs = rsqrtf(q / C + eps);
+    const uint2* g2 = reinterpret_cast<const uint2*>(gamma + l * 20);
+    const uint2* b2 = reinterpret_cast<const uint2*>(beta + l * 20);
+    uint2* o2 = reinterpret_cast<uint2*>(out + (size_t)row * C + l * 20);
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const uint2 gv = g2[j], bv = b2[j];
+        const float y0 = (v[j].x - mu) * rs * __uint_as_float(gv.x << 16) + __uint_as_float(bv.x << 16);
+        const float y1 = (v[j].y - mu) * rs * __uint_as_float(gv.x & 0xffff0000u) + __uint_as_float(bv.x & 0xffff0000u);
+        const float y2 = (v[j].z - mu) * rs * __uint_as_float(gv.y << 16) + __uint_as_float(bv.y << 16);
+        const float y3 = (v[j].w - mu) * rs * __uint_as_float(gv.y & 0xffff0000u) + __uint_as_float(bv.y & 0xffff0000u);
+        o2[j] = make_uint2(f2bf2(y0, y1), f2bf2(y2, y3));
+    }
+}
+
 int launch_ln_rows(const void* in, int in_f32, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
                    const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st) {
     if (rows <= 0) return FISE_OK;
     if (C > 64 * LN_MAXJ) return fail(FISE_ERR_SHAPE, "layernorm rows: C=%d > %d", C, 64 * LN_MAXJ);
     const dim3 grid(ceil_div(rows, 4)), block(256);
-    if (in_f32)
+    if (in_f32 && !tile_idx && (C == 320 || C == 640 || C == 1280)) {
+        const float* x = (const float*)in; const bf16_t* g = (const bf16_t*)gamma; const bf16_t* b = (const bf16_t*)beta;
+        if (C == 320) hipLaunchKernelGGL(ln_rows20_kernel<16>, dim3(ceil_div(rows, 16)), block, 0, st, x, rows, g, b, eps, (bf16_t*)out);
+        else if (C == 640) hipLaunchKernelGGL(ln_rows20_kernel<32>, dim3(ceil_div(rows, 8)), block, 0, st, x, rows, g, b, eps, (bf16_t*)out);
+        else hipLaunchKernelGGL(ln_rows20_kernel<64>, dim3(ceil_div(rows, 4)), block, 0, st, x, rows, g, b, eps, (bf16_t*)out);
+    } else if (in_f32)
         hipLaunchKernelGGL(ln_rows_kernel<float>, grid, block, 0, st, (const float*)in, rows, C, (const bf16_t*)gamma,
                            (const bf16_t*)beta, eps, (bf16_t*)out, tile_idx, tile, tiles_w, H, W, Ma);
     else

