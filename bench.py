@@ -55,6 +55,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--seed", type=int, default=5000)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB elementwise copy (for scaling FETCH_SIZE / WRITE_SIZE counter readings)")
+    ap.add_argument("--density-sweep", action="store_true",
+                    help="log masked step time for blobs of 1/5/10/25/50 %% of the latent (stderr), then the normal run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1")
@@ -129,6 +133,21 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
+    if args.calibrate_copy:                      # a kernel of known traffic: reads 256 MiB, writes 256 MiB
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev); dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.density_sweep:
+        idx_s = torch.zeros(ntiles, dtype=torch.int32, device=dev)
+        for frac in (0.01, 0.05, 0.10, 0.25, 0.50):
+            px = wl.ellipse_pixels(np.random.default_rng(args.seed + int(frac * 1000)), H, W, frac)
+            tiles = np.flatnonzero(px.reshape(H // bt, bt, W // bt, bt).any(axis=(1, 3)).reshape(-1)).astype(np.int32)
+            idx_s[:tiles.size] = torch.from_numpy(tiles).to(dev)
+            for i in range(3):
+                step(i, int(tiles.size), idx_s)
+            log(f"[bench] blob {frac * 100:4.0f} % of pixels -> {tiles.size:2d}/{ntiles} tiles: masked step "
+                f"{timed(max(5, args.steps // 2), int(tiles.size), idx_s):.3f} ms")
     for i in range(args.warmup):
         step(i, na, idx)
     ms_masked = timed(args.steps, na, idx)

@@ -33,6 +33,7 @@ struct IgemmArgs {
     const bf16_t* s0; const bf16_t* s1; int S0, S1; const bf16_t* w2; const bf16_t* bias2; int K2;
     // ---- split-K (splits == 1: none)
     int splits; float* partial;
+    int gx, gy;                                         // tile grid (row tiles, column tiles); set by the launcher
     long long* dbg;                                     // development aid: per-workgroup phase timestamps (null = off)
 };
 

@@ -79,10 +79,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int rows = a.B * a.Ma;
-    long long* dbg = a.dbg ? a.dbg + 8 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) : nullptr;
+    // ---- workgroup -> (row tile bx, column tile by, K split bz).  The grid is one-dimensional and the
+    // hardware deals consecutive workgroups round-robin to the 8 XCDs, each with an L2 of its own.
+    // Workgroup w is therefore given position (w % 8) * (total / 8) + w / 8 of the (bz, by, bx) order
+    // with bx fastest: every XCD works on one contiguous run of that order, so a slice of the weight
+    // matrix is pulled into one L2 (two at a run boundary) instead of all eight.
+    int bx, by, bz;
+    {
+        const int total = a.gx * a.gy * a.splits, chunk = total >> 3;
+        int w = blockIdx.x;
+        if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
+        bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
+    }
+    long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
 #define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
     FISE_STAMP(0);
-    const int m0 = blockIdx.x * BM;
+    const int m0 = bx * BM;
     const int Cin = a.C0 + a.C1;
     const int pad = a.ksize >> 1;
 
@@ -103,7 +115,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     int kc_begin = 0, kc_end = nsteps_total;
     if (a.splits > 1) {
         const int per = (nsteps_total + a.splits - 1) / a.splits;
-        kc_begin = blockIdx.z * per; kc_end = min(nsteps_total, kc_begin + per);
+        kc_begin = bz * per; kc_end = min(nsteps_total, kc_begin + per);
     }
     // ---- GroupNorm (scale, shift) of the channels this K range touches, for the batch elements of
     // this tile, staged in LDS.  A range shorter than Cin is stored rotated: slot = (c - c_lo) mod Cin.
@@ -150,10 +162,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         int wr; bool ok = col < BN;
         if (a.geglu) {
             const int wv = col / WN, jj = col % WN, half = jj / (WN / 2), cc = jj % (WN / 2);
-            const int oc = blockIdx.y * (BN / 2) + wv * (WN / 2) + cc;
+            const int oc = by * (BN / 2) + wv * (WN / 2) + cc;
             ok = ok && oc < a.N; wr = oc + half * a.N;
         } else {
-            wr = blockIdx.y * BN + col; ok = ok && wr < a.N;
+            wr = by * BN + col; ok = ok && wr < a.N;
         }
         brow[j] = wr; bok[j] = ok;
     }
@@ -318,16 +330,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     // L2-bypassing accesses, which measured slower than the extra launch.)
     if (a.splits > 1) {
         const int ncols = a.geglu ? 2 * a.N : a.N;
-        float* P = a.partial + (size_t)blockIdx.z * rows * ncols;
+        float* P = a.partial + (size_t)bz * rows * ncols;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             int wr;
             if (a.geglu) {
                 const int half = j / (TN / 2 > 0 ? TN / 2 : 1), jj = j % (TN / 2 > 0 ? TN / 2 : 1);
-                const int oc = blockIdx.y * (BN / 2) + (wave % WGN) * (WN / 2) + jj * 32 + (lane & 31);
+                const int oc = by * (BN / 2) + (wave % WGN) * (WN / 2) + jj * 32 + (lane & 31);
                 wr = oc < a.N ? oc + half * a.N : -1;
             } else {
-                wr = blockIdx.y * BN + wn0 + j * 32 + (lane & 31);
+                wr = by * BN + wn0 + j * 32 + (lane & 31);
                 if (wr >= a.N) wr = -1;
             }
             if (wr < 0) continue;
@@ -349,8 +361,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     for (int j = 0; j < TN; ++j) {
         if (j >= n_out_blocks) break;
         int col;
-        if (a.geglu) col = blockIdx.y * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
-        else col = blockIdx.y * BN + wn0 + j * 32 + (lane & 31);
+        if (a.geglu) col = by * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
+        else col = by * BN + wn0 + j * 32 + (lane & 31);
         if (col >= a.N) continue;
         float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
         if (a.bias2) bias_v += bf2f(a.bias2[col]);
@@ -376,41 +388,47 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
 }
 
 // Second half of a split-K launch: one thread per four output columns sums the parked partials in
-// split order (deterministic; 16-byte loads, four splits in flight) and applies the epilogue.
+// split order (deterministic) and applies the epilogue.  All loads of a thread (up to 16 splits x 16
+// bytes, twice that with the GEGLU gate) are issued before the first add, so the kernel pays one
+// memory round trip rather than one per split.
+constexpr int RED_MAXS = 16;
+template <bool GEGLU>
 __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const int rows = a.B * a.Ma;
     const int nq = a.N / 4;                              // N % 4 == 0 (checked by the launcher)
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (long long)rows * nq) return;
     const int gm = (int)(i / nq), col = (int)(i % nq) * 4;
-    const int ncols = a.geglu ? 2 * a.N : a.N;
+    const int ncols = GEGLU ? 2 * a.N : a.N;
     const size_t stride = (size_t)rows * ncols;
     const float* P = a.partial + (size_t)gm * ncols + col;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
-    auto add = [](float4& d, const float4& x) { d.x += x.x; d.y += x.y; d.z += x.z; d.w += x.w; };
-    int z = 0;
-    for (; z + 4 <= a.splits; z += 4) {
-        const float4 p0 = *reinterpret_cast<const float4*>(P + (z + 0) * stride), p1 = *reinterpret_cast<const float4*>(P + (z + 1) * stride);
-        const float4 p2 = *reinterpret_cast<const float4*>(P + (z + 2) * stride), p3 = *reinterpret_cast<const float4*>(P + (z + 3) * stride);
-        add(v, p0); add(v, p1); add(v, p2); add(v, p3);
-        if (a.geglu) {
-            const float4 q0 = *reinterpret_cast<const float4*>(P + (z + 0) * stride + a.N), q1 = *reinterpret_cast<const float4*>(P + (z + 1) * stride + a.N);
-            const float4 q2 = *reinterpret_cast<const float4*>(P + (z + 2) * stride + a.N), q3 = *reinterpret_cast<const float4*>(P + (z + 3) * stride + a.N);
-            add(g, q0); add(g, q1); add(g, q2); add(g, q3);
-        }
-    }
-    for (; z < a.splits; ++z) {
-        add(v, *reinterpret_cast<const float4*>(P + z * stride));
-        if (a.geglu) add(g, *reinterpret_cast<const float4*>(P + z * stride + a.N));
-    }
     int y = 0, x = gm % a.Ma;
     const int b = gm / a.Ma;
-    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
+    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);      // its load overlaps the ones below
+    float4 pv[RED_MAXS], pg[GEGLU ? RED_MAXS : 1];
+#pragma unroll
+    for (int z = 0; z < RED_MAXS; ++z) {
+        const int zz = z < a.splits ? z : 0;              // slots past the split count re-read split 0 and are ignored
+        pv[z] = *reinterpret_cast<const float4*>(P + zz * stride);
+        if (GEGLU) pg[z] = *reinterpret_cast<const float4*>(P + zz * stride + a.N);
+    }
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
+#pragma unroll
+    for (int z = 0; z < RED_MAXS; ++z)
+        if (z < a.splits) {
+            v.x += pv[z].x; v.y += pv[z].y; v.z += pv[z].z; v.w += pv[z].w;
+            if (GEGLU) { g.x += pg[z].x; g.y += pg[z].y; g.z += pg[z].z; g.w += pg[z].w; }
+        }
+    for (int z = RED_MAXS; z < a.splits; ++z) {           // more than RED_MAXS splits: the rest one by one
+        const float4 p = *reinterpret_cast<const float4*>(P + z * stride);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        if (GEGLU) { const float4 q = *reinterpret_cast<const float4*>(P + z * stride + a.N); g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w; }
+    }
     const float vv[4] = {v.x, v.y, v.z, v.w}, gg[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         float r = vv[q] + (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
-        if (a.geglu) {
+        if (GEGLU) {
             const float gt = gg[q] + (a.bias ? bf2f(a.bias[col + q + a.N]) : 0.f);
             r = r * (0.5f * gt * (1.0f + erff(gt * 0.70710678118654752f)));
         }
@@ -476,7 +494,8 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     a.splits = (a.N % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
     if (a.splits > 1) a.partial = ws->partial;
     a.dbg = g_igemm_dbg;
-    dim3 grid(ceil_div(rows, BM), ceil_div(ncols, BN), a.splits);
+    a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
+    dim3 grid((unsigned)(a.gx * a.gy * a.splits));
     size_t shmem = 0;
     if (a.pro != PRO_NONE) {
         const int span = std::min(a.B, (BM - 1) / a.Ma + 2);
@@ -510,7 +529,8 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     if (a.splits > 1) {
         const long long n = (long long)rows * (a.N / 4);
         ProfileScope prof(PROF_REDUCE, 0.0, 2.0 * a.splits * (double)rows * ncols * 4.0, st);
-        hipLaunchKernelGGL(igemm_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+        if (a.geglu) hipLaunchKernelGGL(igemm_reduce_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(igemm_reduce_kernel<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
         FISE_CHECK_LAUNCH("igemm reduce");
     }
     return FISE_OK;
