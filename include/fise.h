@@ -339,12 +339,18 @@ int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cach
  * attention kernels is bracketed by two HIP events on the caller's stream
  * (host objects; no device memory).  fise_profile_read(kind, ...) waits for the
  * events and returns the summed event time (ms), algorithmic FLOPs and bytes
- * and the number of launches recorded for `kind` (0 = gathered GEMM, 1 = the
- * same with the GEGLU epilogue, 2 = attention incl. its merge launch, 3 = wide-tile
- * gathered GEMM, 4 = split-K reduce launches);
- * kind = -1 clears the log.  All pointers host.  Not thread safe.
+ * and the number of launches recorded for `kind`:
+ *   0 gathered GEMM, 64x64 tiles        1 gathered GEMM with the GEGLU epilogue
+ *   2 attention (main kernel)           3 gathered GEMM, 128x128 tiles
+ *   4 split-K reduce launches           5 gathered GEMM, 32x128 tiles (<= 32 rows)
+ *   6 gathered GEMM with the GroupNorm prologue / 32-wide K steps
+ *   7 attention merge launches          8 empty brackets (fise_profile_calibrate)
+ * kind = -1 clears the log.  fise_profile_calibrate records n brackets with no
+ * launch inside on `stream`: their average is what a bracket itself adds to every
+ * figure above.  All pointers host.  Not thread safe.
  * ------------------------------------------------------------------------ */
 int fise_profile_enable(int on);
+int fise_profile_calibrate(int n, void* stream);
 int fise_profile_read(int kind, double* total_ms, double* total_flops, double* total_bytes, int* launches);
 
 #ifdef __cplusplus

@@ -101,6 +101,7 @@ _SIGS = {
     "fise_unet_context_kv": (i32, [vp, vp, vp, vp, vp, sz, vp]),
     "fise_masked_unet_step": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), vp, sz, vp]),
     "fise_profile_enable": (i32, [i32]),
+    "fise_profile_calibrate": (i32, [i32, vp]),
     "fise_profile_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]),
     "fise_unet_num_modules": (i32, [vp]),
     "fise_unet_module_name": (i32, [vp, i32, C.c_char_p]),
@@ -402,6 +403,10 @@ def fise_masked_unet_modules(u, weights, cache, latent, t_sin, ctxkv, tile_idx, 
 
 def fise_profile_enable(on):
     _ck(lib().fise_profile_enable(1 if on else 0))
+
+
+def fise_profile_calibrate(n, stream=None):
+    _ck(lib().fise_profile_calibrate(int(n), _stream(stream)))
 
 
 def fise_profile_read(kind):

@@ -262,6 +262,7 @@ int launch_attention(const void* q, const void* K, const void* Vt, int B, int M,
     if (splits > 1 && (!ws || ws_bytes < attention_workspace_bytes(B, M, n_keys, C, heads))) splits = 1;
     float* part_o = (float*)ws;
     float* part_ml = splits > 1 ? (float*)((char*)ws + align256((size_t)splits * B * M * C * sizeof(float))) : nullptr;
+    {
     ProfileScope prof(PROF_ATTENTION, 4.0 * B * (double)M * n_keys * C,
                       2.0 * ((double)B * n_keys * C * 2 + 2.0 * B * M * C), st);
 #define FISE_AT(KDV, DBV) launch_at<KDV, DBV>(q, K, Vt, B, M, n_keys, n_stride, C, heads, d, scale, splits, out, part_o, part_ml, st)
@@ -274,9 +275,11 @@ int launch_attention(const void* q, const void* K, const void* Vt, int B, int M,
     else if (kd <= 10) FISE_AT(10, 5);
     else return fail(FISE_ERR_SHAPE, "attention: head dim %d > 160", d);
 #undef FISE_AT
+    }
     FISE_CHECK_LAUNCH("attention");
     if (splits > 1) {
         const long long n = (long long)B * M * C;
+        ProfileScope prof(PROF_ATTENTION_MERGE, 0.0, (double)splits * B * M * C * 4.0 + 2.0 * B * M * C, st);
         hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part_o, part_ml, B, M, C,
                            heads, d, splits, (bf16_t*)out);
         FISE_CHECK_LAUNCH("attention merge");

@@ -22,6 +22,9 @@
 #ifndef FISE_PF
 #define FISE_PF 2
 #endif
+#ifndef FISE_NST
+#define FISE_NST 3
+#endif
 
 namespace fise {
 
@@ -32,6 +35,13 @@ struct RowInfo { int b, y, x, ok; };
 // Barrier for LDS hand-over only: waits for this wave's LDS traffic, not for its global loads in
 // flight (a full __syncthreads() would drain the prefetch FIFO at every step).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Waits until at most N of this wave's vector memory loads are outstanding, then joins the workgroup barrier.
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
 // Last stage of the epilogue for output element (row gm = (b, y, x), column col) whose value v already
 // holds the accumulated sum, biases and the GEGLU gate: time projection, residual, store by section.
@@ -54,6 +64,92 @@ __device__ __forceinline__ void epilogue_store(const IgemmArgs& a, int gm, int b
         outp[pix * a.sect_n + scol] = f2bf(v);
     } else {
         outp[((size_t)b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v);
+    }
+}
+
+
+// Row table of a tile: output row m0 + r -> (batch element, y, x) of its active pixel (or compact token).
+template <int BM, int NT>
+__device__ __forceinline__ void build_row_table(const IgemmArgs& a, int m0, int rows, RowInfo* rinfo, int tid) {
+    for (int r = tid; r < BM; r += NT) {
+        RowInfo ri; ri.b = 0; ri.y = 0; ri.x = 0; ri.ok = 0;
+        const int gm = m0 + r;
+        if (gm < rows) {
+            ri.ok = 1; ri.b = gm / a.Ma;
+            if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, ri.y, ri.x);
+            else ri.x = gm % a.Ma;                      // compact rows: token = position in the batch element
+        }
+        rinfo[r] = ri;
+    }
+}
+
+// Weight row behind tile column `col` of column tile `by` (-1: past the last output column).
+// GEGLU: the first half of a wave's columns are value rows, the second half the matching gate rows.
+template <int BN, int WN>
+__device__ __forceinline__ int weight_row(const IgemmArgs& a, int by, int col) {
+    if (col >= BN) return -1;
+    if (a.geglu) {
+        const int wv = col / WN, jj = col % WN, half = jj / (WN / 2), cc = jj % (WN / 2);
+        const int oc = by * (BN / 2) + wv * (WN / 2) + cc;
+        return oc < a.N ? oc + half * a.N : -1;
+    }
+    const int wr = by * BN + col;
+    return wr < a.N ? wr : -1;
+}
+
+// What a workgroup does with its accumulators.  Split-K: park them as partial[bz][row][weight row]; a
+// second small kernel adds them up in split order and applies the epilogue.  (Handing the partials
+// over inside the GEMM kernel needs either device-scope fences, which write back and invalidate
+// whole L2s, or L2-bypassing accesses, which measured slower than the extra launch.)  Otherwise:
+// bias, GEGLU gate, time projection, residual, store.
+template <int BM, int BN, int WGM, int WGN>
+__device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32], const RowInfo* rinfo,
+                                            int m0, int by, int bz, int rows, int lane, int wave) {
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    if (a.splits > 1) {
+        const int ncols = a.geglu ? 2 * a.N : a.N;
+        float* P = a.partial + (size_t)bz * rows * ncols;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int wr = weight_row<BN, WN>(a, by, wn0 + j * 32 + (lane & 31));
+            if (wr < 0) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    if (m0 + r < rows) P[(size_t)(m0 + r) * ncols + wr] = acc[i][j][e];
+                }
+        }
+        return;
+    }
+    constexpr int n_out_blocks = TN >= 2 ? TN / 2 : 1;    // GEGLU pairs block j (value) with block j + TN/2 (gate)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        if (a.geglu && j >= n_out_blocks) break;
+        int col;
+        if (a.geglu) col = by * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
+        else col = by * BN + wn0 + j * 32 + (lane & 31);
+        if (col >= a.N) continue;
+        float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
+        if (a.bias2) bias_v += bf2f(a.bias2[col]);
+        const float bias_g = (a.geglu && a.bias) ? bf2f(a.bias[col + a.N]) : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const RowInfo ri = rinfo[r];
+                if (!ri.ok) continue;
+                float v = acc[i][j][e] + bias_v;
+                if (a.geglu) {
+                    const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
+                    v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
+                }
+                epilogue_store(a, m0 + r, ri.b, ri.y, ri.x, col, v);
+            }
+        }
     }
 }
 
@@ -98,17 +194,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     const int Cin = a.C0 + a.C1;
     const int pad = a.ksize >> 1;
 
-    // ---- row table
-    for (int r = tid; r < BM; r += NT) {
-        RowInfo ri; ri.b = 0; ri.y = 0; ri.x = 0; ri.ok = 0;
-        const int gm = m0 + r;
-        if (gm < rows) {
-            ri.ok = 1; ri.b = gm / a.Ma;
-            if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, ri.y, ri.x);
-            else ri.x = gm % a.Ma;                      // compact rows: token = position in the batch element
-        }
-        rinfo[r] = ri;
-    }
+    build_row_table<BM, NT>(a, m0, rows, rinfo, tid);
     // ---- K range of this workgroup
     const int nsteps1 = a.K / BK;                      // main product
     const int nsteps_total = nsteps1 + a.K2 / BK;      // + the 1x1 side product
@@ -154,20 +240,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         const RowInfo ri = rinfo[in ? lrow + RP * j : 0];
         aok[j] = in && ri.ok; ab[j] = ri.b; ay[j] = ri.y; ax[j] = ri.x;
     }
-    // weight row of tile column j (GEGLU: first half of a wave's columns = value rows, second half = gate rows)
-    int brow[BL]; bool bok[BL];
+    int brow[BL]; bool bok[BL];                        // weight row of tile column j
 #pragma unroll
     for (int j = 0; j < BL; ++j) {
-        const int col = lrow + RP * j;
-        int wr; bool ok = col < BN;
-        if (a.geglu) {
-            const int wv = col / WN, jj = col % WN, half = jj / (WN / 2), cc = jj % (WN / 2);
-            const int oc = by * (BN / 2) + wv * (WN / 2) + cc;
-            ok = ok && oc < a.N; wr = oc + half * a.N;
-        } else {
-            wr = by * BN + col; ok = ok && wr < a.N;
-        }
-        brow[j] = wr; bok[j] = ok;
+        const int wr = weight_row<BN, WN>(a, by, lrow + RP * j);
+        brow[j] = wr < 0 ? 0 : wr; bok[j] = wr >= 0;
     }
 
     // ---- load cursor.  All address arithmetic that does not change from step to step is done here or
@@ -324,67 +401,244 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     }
     FISE_STAMP(4);
 
-    // ---- split-K: park this workgroup's partial sums as partial[z][row][weight row]; a second small
-    // kernel adds them up in split order and applies the epilogue.  (Handing the partials over inside
-    // this kernel needs either device-scope fences, which write back and invalidate whole L2s, or
-    // L2-bypassing accesses, which measured slower than the extra launch.)
-    if (a.splits > 1) {
-        const int ncols = a.geglu ? 2 * a.N : a.N;
-        float* P = a.partial + (size_t)bz * rows * ncols;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int wr;
-            if (a.geglu) {
-                const int half = j / (TN / 2 > 0 ? TN / 2 : 1), jj = j % (TN / 2 > 0 ? TN / 2 : 1);
-                const int oc = by * (BN / 2) + (wave % WGN) * (WN / 2) + jj * 32 + (lane & 31);
-                wr = oc < a.N ? oc + half * a.N : -1;
-            } else {
-                wr = by * BN + wn0 + j * 32 + (lane & 31);
-                if (wr >= a.N) wr = -1;
-            }
-            if (wr < 0) continue;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                    if (m0 + r < rows) P[(size_t)(m0 + r) * ncols + wr] = acc[i][j][e];
-                }
-        }
-        FISE_STAMP(5);
-        return;
-    }
-
-    // ---- epilogue
-    const int n_out_blocks = a.geglu ? TN / 2 : TN;       // GEGLU pairs block j (value) with block j + TN/2 (gate)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        if (j >= n_out_blocks) break;
-        int col;
-        if (a.geglu) col = by * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
-        else col = by * BN + wn0 + j * 32 + (lane & 31);
-        if (col >= a.N) continue;
-        float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
-        if (a.bias2) bias_v += bf2f(a.bias2[col]);
-        const float bias_g = (a.geglu && a.bias) ? bf2f(a.bias[col + a.N]) : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                const RowInfo ri = rinfo[r];
-                if (!ri.ok) continue;
-                float v = acc[i][j][e] + bias_v;
-                if (a.geglu) {
-                    const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
-                    v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
-                }
-                epilogue_store(a, m0 + r, ri.b, ri.y, ri.x, col, v);
-            }
-        }
-    }
+    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
     FISE_STAMP(5);
 #undef FISE_STAMP
+}
+
+
+// ---------------------------------------------------------------------------
+// The same contraction with operands moved HBM/L2 -> LDS by the memory pipeline itself
+// (buffer loads with the LDS bit): no staging registers, no LDS stores, and all per-load
+// address arithmetic in the instruction (scalar base descriptor + per-lane 32-bit offset +
+// scalar K offset).  A K step costs a wave (BM + BN) / (8 waves) loads, its share of LDS reads
+// and the MFMAs.  Used for every launch without a GroupNorm prologue whose channel counts are
+// multiples of 64; the register-staged kernel above covers the rest.
+//
+// LDS: a ring of NST stages, each (BM + BN) rows of 64 bf16 (128 bytes, no padding).  One load
+// instruction of a wave fills 8 consecutive rows: lane l writes 16 bytes at row l / 8, slot l % 8
+// (the hardware fixes that order).  Which 16 bytes of the row a lane fetches is free, so slot p
+// of row r holds K segment p ^ ((r >> 1) & 7): the MFMA operand reads (32 rows x one segment per
+// half wave) then touch every bank equally.
+// Rows that do not exist (past the last row, taps outside the image, weight rows past N) carry an
+// offset beyond the descriptor's size: the load returns zeros and touches no memory.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int NST>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)    // the buffer-descriptor type and builtins exist in the device pass only
+    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    constexpr int RB = 8 * NW;                          // tile rows filled by one load slot of the workgroup
+    static_assert(BM % RB == 0 && BN % RB == 0, "tile rows must split evenly over the waves");
+    constexpr int AL = BM / RB, BL = BN / RB;           // load slots per thread and K step
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+    constexpr int STAGE = (BM + BN) * 128;              // bytes
+    constexpr unsigned OOB = 0x80000000u;               // beyond any descriptor (sizes are below 2 GiB)
+    constexpr int SRD_FLAGS = 0x00020000;               // raw buffer, 32-bit data format
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+    __shared__ RowInfo rinfo[BM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rows = a.B * a.Ma;
+    int bx, by, bz;                                     // see igemm_kernel: XCD-aware workgroup order
+    {
+        const int total = a.gx * a.gy * a.splits, chunk = total >> 3;
+        int w = blockIdx.x;
+        if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
+        bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
+    }
+    long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
+#define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
+    FISE_STAMP(0);
+    const int m0 = bx * BM;
+    const int Cin = a.C0 + a.C1;
+    const int pad = a.ksize >> 1;
+    build_row_table<BM, NT>(a, m0, rows, rinfo, tid);
+
+    const int nsteps1 = a.K / 64;                       // main product
+    const int nsteps_total = nsteps1 + a.K2 / 64;       // + the 1x1 side product
+    int kc_begin = 0, kc_end = nsteps_total;
+    if (a.splits > 1) {
+        const int per = (nsteps_total + a.splits - 1) / a.splits;
+        kc_begin = bz * per; kc_end = min(nsteps_total, kc_begin + per);
+    }
+    __syncthreads();
+    FISE_STAMP(1);
+
+    // ---- descriptors of the operand arrays
+    const unsigned npix_in = a.a_compact ? (unsigned)rows : (unsigned)(a.B * a.Hin * a.Win);
+    const unsigned npix_out = (unsigned)(a.B * a.Ho * a.Wo);
+    const __amdgpu_buffer_rsrc_t srd_a0 = __builtin_amdgcn_make_buffer_rsrc((void*)a.a0, 0, (int)(npix_in * a.C0 * 2u), SRD_FLAGS);
+    const __amdgpu_buffer_rsrc_t srd_a1 = __builtin_amdgcn_make_buffer_rsrc((void*)a.a1, 0, (int)(a.a1 ? npix_in * a.C1 * 2u : 0u), SRD_FLAGS);
+    const __amdgpu_buffer_rsrc_t srd_s0 = __builtin_amdgcn_make_buffer_rsrc((void*)a.s0, 0, (int)(a.s0 ? npix_out * a.S0 * 2u : 0u), SRD_FLAGS);
+    const __amdgpu_buffer_rsrc_t srd_s1 = __builtin_amdgcn_make_buffer_rsrc((void*)a.s1, 0, (int)(a.s1 ? npix_out * a.S1 * 2u : 0u), SRD_FLAGS);
+    const unsigned wrows = (unsigned)(a.geglu ? 2 * a.N : a.N);
+    const __amdgpu_buffer_rsrc_t srd_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(wrows * (unsigned)a.K * 2u), SRD_FLAGS);
+    const __amdgpu_buffer_rsrc_t srd_w2 = __builtin_amdgcn_make_buffer_rsrc((void*)a.w2, 0, (int)(a.w2 ? wrows * (unsigned)a.K2 * 2u : 0u), SRD_FLAGS);
+
+    // ---- per-thread load slots: slot j of this wave fills tile rows j * RB + wave * 8 .. + 8
+    const int lr = lane >> 3;                           // row within the 8
+    int ab[AL], ay[AL], ax[AL]; bool aok[AL]; unsigned aseg[AL];
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+        const int r = j * RB + wave * 8 + lr;
+        const RowInfo ri = rinfo[r];
+        aok[j] = ri.ok; ab[j] = ri.b; ay[j] = ri.y; ax[j] = ri.x;
+        aseg[j] = (unsigned)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
+    }
+    int brow[BL]; unsigned bseg[BL];
+#pragma unroll
+    for (int j = 0; j < BL; ++j) {
+        const int r = j * RB + wave * 8 + lr;
+        brow[j] = weight_row<BN, WN>(a, by, r);
+        bseg[j] = (unsigned)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
+    }
+
+    // ---- load cursor (wave-uniform apart from the per-lane offsets va / vb)
+    //   phase 0: main product, K = taps x (channels of a0 | a1); phase 1: 1x1 side product over s0 | s1
+    bool side = false;
+    int tap = 0, cc = 0;                                // tap, channel cursor within the concatenation
+    int kc_next = kc_begin;
+    int pix[AL], opix[AL];                              // input pixel of the current tap / output pixel (-1: none)
+    unsigned va[AL], vb[BL];                            // byte offsets of the lanes' rows in the current source / weights
+    unsigned soff_a = 0, soff_b = 0;                    // byte offsets of the K step within a row
+    __amdgpu_buffer_rsrc_t cur_a = srd_a0, cur_b = srd_w;
+#pragma unroll
+    for (int j = 0; j < AL; ++j) opix[j] = aok[j] ? (ab[j] * a.Ho + ay[j]) * a.Wo + ax[j] : -1;
+    auto set_tap = [&]() {
+        const int ky = tap / a.ksize, kx = tap - ky * a.ksize;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            int p = -1;
+            if (aok[j]) {
+                if (a.a_compact) p = m0 + j * RB + wave * 8 + lr;
+                else if (a.ups) {
+                    const int uy = ay[j] + ky - pad, ux = ax[j] + kx - pad;
+                    if (uy >= 0 && uy < 2 * a.Hin && ux >= 0 && ux < 2 * a.Win) p = (ab[j] * a.Hin + (uy >> 1)) * a.Win + (ux >> 1);
+                } else {
+                    const int iy = ay[j] * a.stride + ky - pad, ix = ax[j] * a.stride + kx - pad;
+                    if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) p = (ab[j] * a.Hin + iy) * a.Win + ix;
+                }
+            }
+            pix[j] = p;
+        }
+    };
+    // source, row offsets and K offset of the A operand for the cursor position (side, cc)
+    auto set_source = [&]() {
+        const int c0 = side ? a.S0 : a.C0, ct = side ? a.K2 : Cin;
+        const bool second = cc >= c0;
+        const unsigned Cs = (unsigned)(second ? ct - c0 : c0);
+        cur_a = side ? (second ? srd_s1 : srd_s0) : (second ? srd_a1 : srd_a0);
+        soff_a = (unsigned)(second ? cc - c0 : cc) * 2u;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) va[j] = pix[j] >= 0 ? (unsigned)pix[j] * Cs * 2u + aseg[j] : OOB;
+    };
+    auto set_weights = [&](int kstep) {                 // kstep: K step within the current phase
+        const unsigned Kw = (unsigned)(side ? a.K2 : a.K);
+        cur_b = side ? srd_w2 : srd_w;
+        soff_b = (unsigned)kstep * 128u;
+#pragma unroll
+        for (int j = 0; j < BL; ++j) vb[j] = brow[j] >= 0 ? (unsigned)brow[j] * Kw * 2u + bseg[j] : OOB;
+    };
+    auto enter_side = [&](int kstep) {
+        side = true; cc = kstep * 64;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) pix[j] = opix[j];
+        set_source(); set_weights(kstep);
+    };
+    if (kc_begin < nsteps1) {
+        const int k0 = kc_begin * 64;
+        tap = k0 / Cin; cc = k0 - tap * Cin;
+        set_tap(); set_source(); set_weights(kc_begin);
+    } else {
+        enter_side(kc_begin - nsteps1);
+    }
+
+    // Loads of the next K step into ring stage st.  Every call issues exactly AL + BL loads per thread
+    // (past the end of the K range they are all out of range: zeros, no memory traffic), so the
+    // count of loads in flight is known at every point of the loop.
+    auto issue = [&](int st) {
+        const bool live = kc_next < kc_end;
+        unsigned char* base = ring + st * STAGE + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < AL; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(cur_a, (__attribute__((address_space(3))) void*)(base + j * RB * 128), 16,
+                                                     live ? va[j] : OOB, soff_a, 0, 0);
+#pragma unroll
+        for (int j = 0; j < BL; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(cur_b, (__attribute__((address_space(3))) void*)(base + (BM + j * RB) * 128), 16,
+                                                     live ? vb[j] : OOB, soff_b, 0, 0);
+        if (live) {
+            ++kc_next; cc += 64; soff_a += 128u; soff_b += 128u;
+            if (!side) {
+                if (kc_next == nsteps1) { if (kc_next < kc_end) enter_side(0); }
+                else if (cc >= Cin) { cc = 0; ++tap; set_tap(); set_source(); }
+                else if (cc == a.C0) set_source();
+            } else if (cc == a.S0 && cc < a.K2) set_source();
+        }
+    };
+
+    // ---- LDS read offsets of the MFMA operands within a stage (row r, segment ks * 2 + lane / 32, swizzled)
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    unsigned rda[TM][4], rdb[TN][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int r = wm0 + i * 32 + (lane & 31), t = (lane >> 5) ^ ((r >> 1) & 7);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) rda[i][ks] = (unsigned)(r * 128 + (((ks * 2) ^ t) * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int r = wn0 + j * 32 + (lane & 31), t = (lane >> 5) ^ ((r >> 1) & 7);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) rdb[j][ks] = (unsigned)((BM + r) * 128 + (((ks * 2) ^ t) * 16));
+    }
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s);         // NST - 1 steps in flight
+    FISE_STAMP(2);
+
+    for (int kc0 = kc_begin; kc0 < kc_end; kc0 += NST) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            if (kc0 + s >= kc_end) break;               // uniform across the workgroup
+            // the loads of this step are the oldest (NST - 1) * (AL + BL) in flight per thread: wait until only
+            // the younger ones remain, then meet the other waves (their rows of the stage have landed too,
+            // and everybody is done reading the stage that is refilled next)
+            wait_loads<(NST - 2) * (AL + BL)>();
+            if (kc0 + s == kc_begin) FISE_STAMP(3);
+            issue((s + NST - 1) % NST);
+            const unsigned char* stage = ring + s * STAGE;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(stage + rda[i][ks]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(stage + rdb[j][ks]);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+    wait_loads<0>();                                    // the trailing out-of-range loads still target the ring
+    FISE_STAMP(4);
+    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
+    FISE_STAMP(5);
+#undef FISE_STAMP
+#endif
 }
 
 // Second half of a split-K launch: one thread per four output columns sums the parked partials in
@@ -520,8 +774,26 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     }
     const double flops = 2.0 * rows * (double)ncols * ((double)a.K + a.K2);
     const double bytes = 2.0 * ((double)ncols * ((double)a.K + a.K2) + (double)rows * (a.C0 + a.C1 + a.S0 + a.S1) + (double)rows * a.N);
-    {
+    // LDS-direct kernel: needs 64-wide K steps, no prologue, and every operand array below 2 GiB (32-bit
+    // buffer offsets with the top bit reserved for "no such row")
+    constexpr size_t kLim = (size_t)1 << 31;
+    const size_t npix_in = a.a_compact ? (size_t)rows : (size_t)a.B * a.Hin * a.Win, npix_out = (size_t)a.B * a.Ho * a.Wo;
+    const bool dma = BK == 64 && a.pro == PRO_NONE && npix_in * std::max(a.C0, a.C1) * 2 < kLim &&
+                     npix_out * std::max(a.S0, a.S1) * 2 < kLim && (size_t)ncols * std::max(a.K, a.K2) * 2 < kLim;
+    if (dma) {
+        constexpr int NST = FISE_NST;
+        constexpr int ring = NST * (BM + BN) * 128;
+        static bool raised = false;                     // once per instantiation
+        if (!raised && ring > 48 * 1024) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, ring) != hipSuccess)
+                return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
+            raised = true;
+        }
         ProfileScope prof(prof_kind, flops, bytes, st);      // brackets the GEMM launch alone
+        hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, WGM, WGN, NST>), grid, dim3(64 * WGM * WGN), ring, st, a);
+    } else {
+        ProfileScope prof(PROF_IGEMM_STAGED, flops, bytes, st);
         if (a.pro != PRO_NONE) hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, true>), grid, dim3(64 * WGM * WGN), shmem, st, a);
         else hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, false>), grid, dim3(64 * WGM * WGN), 0, st, a);
     }
@@ -562,7 +834,7 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
         return launch_cfg<64, 128, 2, 2>(a, ws, PROF_IGEMM_GEGLU, st);
     }
     if (wide) return launch_cfg<128, 128, 2, 4>(a, ws, PROF_IGEMM_WIDE, st);
-    if (rows <= 32) return launch_cfg<32, 128, 1, 4>(a, ws, PROF_IGEMM, st);
+    if (rows <= 32) return launch_cfg<32, 128, 1, 4>(a, ws, PROF_IGEMM_THIN, st);
     return launch_cfg<64, 64, 2, 2>(a, ws, PROF_IGEMM, st);
 }
 

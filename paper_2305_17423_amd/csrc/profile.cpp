@@ -38,6 +38,15 @@ extern "C" int fise_profile_enable(int on) {
     return FISE_OK;
 }
 
+extern "C" int fise_profile_calibrate(int n, void* stream) {
+    if (n < 0) return fail(FISE_ERR_SHAPE, "fise_profile_calibrate: n=%d", n);
+    const bool was = g_profile_on;
+    g_profile_on = true;
+    for (int i = 0; i < n; ++i) { ProfileScope empty(PROF_EMPTY, 0.0, 0.0, (hipStream_t)stream); }
+    g_profile_on = was;
+    return FISE_OK;
+}
+
 extern "C" int fise_profile_read(int kind, double* total_ms, double* total_flops, double* total_bytes, int* launches) {
     if (!total_ms || !total_flops || !total_bytes || !launches) return fail(FISE_ERR_NULL, "fise_profile_read: null pointer");
     if (kind < -1 || kind >= PROF_KINDS) return fail(FISE_ERR_SHAPE, "fise_profile_read: kind %d", kind);

@@ -5,7 +5,17 @@
 
 namespace fise {
 
-enum { PROF_IGEMM = 0, PROF_IGEMM_GEGLU = 1, PROF_ATTENTION = 2, PROF_IGEMM_WIDE = 3, PROF_REDUCE = 4, PROF_KINDS = 5 };
+// one kind per kernel family, so that a kind's average can be set against a profiler's per-kernel figure
+enum { PROF_IGEMM = 0,          // LDS-direct gathered GEMM, 64x64 tiles
+       PROF_IGEMM_GEGLU = 1,    // the same with the GEGLU epilogue (64x128 / 32x256 tiles)
+       PROF_ATTENTION = 2,      // active-query attention (without its merge launch)
+       PROF_IGEMM_WIDE = 3,     // 128x128 tiles (dense-sized problems)
+       PROF_REDUCE = 4,         // split-K reduce + epilogue
+       PROF_IGEMM_THIN = 5,     // 32x128 tiles (at most 32 rows)
+       PROF_IGEMM_STAGED = 6,   // register-staged gathered GEMM (GroupNorm prologue, 32-wide K steps)
+       PROF_ATTENTION_MERGE = 7,
+       PROF_EMPTY = 8,          // nothing between the two events: the bracket's own cost
+       PROF_KINDS = 9 };
 
 extern bool g_profile_on;
 void profile_begin(int kind, double flops, double bytes, hipStream_t st);
