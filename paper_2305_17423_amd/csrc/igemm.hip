@@ -43,15 +43,21 @@ __device__ __forceinline__ void wait_loads() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// Last stage of the epilogue for output element (row gm = (b, y, x), column col) whose value v already
-// holds the accumulated sum, biases and the GEGLU gate: time projection, residual, store by section.
-__device__ __forceinline__ void epilogue_store(const IgemmArgs& a, int gm, int b, int y, int x, int col, float v) {
+// Epilogue terms that depend on the output position: time projection and residual for output element
+// (row gm = (b, y, x), column col).
+__device__ __forceinline__ float epilogue_terms(const IgemmArgs& a, int gm, int b, int y, int x, int col) {
+    float v = 0.f;
     if (a.temb) v += a.temb[b * a.temb_stride + col];
-    const size_t pix = ((size_t)b * a.Ho + y) * a.Wo + x;
     if (a.res) {
         if (a.res_compact == 2) v += reinterpret_cast<const float*>(a.res)[(size_t)gm * a.N + col];
-        else v += bf2f(a.res_compact ? a.res[(size_t)gm * a.N + col] : a.res[pix * a.N + col]);
+        else if (a.res_compact) v += bf2f(a.res[(size_t)gm * a.N + col]);
+        else v += bf2f(a.res[(((size_t)b * a.Ho + y) * a.Wo + x) * a.N + col]);
     }
+    return v;
+}
+
+// Store of the finished value v of output element (row gm = (b, y, x), column col), by section.
+__device__ __forceinline__ void epilogue_put(const IgemmArgs& a, int gm, int b, int y, int x, int col, float v) {
     const int sect = col / a.sect_n, scol = col % a.sect_n;
     bf16_t* outp = a.out[sect];
     const int omode = a.out_mode[sect];
@@ -61,12 +67,33 @@ __device__ __forceinline__ void epilogue_store(const IgemmArgs& a, int gm, int b
     } else if (omode == OUT_COMPACT) {
         outp[(size_t)gm * a.sect_n + scol] = f2bf(v);
     } else if (omode == OUT_MAP) {
-        outp[pix * a.sect_n + scol] = f2bf(v);
+        outp[(((size_t)b * a.Ho + y) * a.Wo + x) * a.sect_n + scol] = f2bf(v);
     } else {
         outp[((size_t)b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v);
     }
 }
 
+// Four consecutive columns col .. col + 3 of one section (col % 4 == 0, section widths are multiples of 4).
+__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, int b, int y, int x, int col, const float (&v)[4]) {
+    const int sect = col / a.sect_n, scol = col % a.sect_n;
+    bf16_t* outp = a.out[sect];
+    const int omode = a.out_mode[sect];
+    if (omode == OUT_TOKENS_T) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            outp[((size_t)b * a.sect_n + scol + q) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v[q]);
+        return;
+    }
+    const uint2 packed = make_uint2(f2bf2(v[0], v[1]), f2bf2(v[2], v[3]));
+    if (omode == OUT_COMPACT_F32) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(outp) + (size_t)gm * a.sect_n + scol) = make_float4(v[0], v[1], v[2], v[3]);
+        if (a.mirror) *reinterpret_cast<uint2*>(a.mirror + (size_t)gm * a.sect_n + scol) = packed;
+    } else if (omode == OUT_COMPACT) {
+        *reinterpret_cast<uint2*>(outp + (size_t)gm * a.sect_n + scol) = packed;
+    } else {
+        *reinterpret_cast<uint2*>(outp + (((size_t)b * a.Ho + y) * a.Wo + x) * a.sect_n + scol) = packed;
+    }
+}
 
 // Row table of a tile: output row m0 + r -> (batch element, y, x) of its active pixel (or compact token).
 template <int BM, int NT>
@@ -147,7 +174,7 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                     const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
                     v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
                 }
-                epilogue_store(a, m0 + r, ri.b, ri.y, ri.x, col, v);
+                epilogue_put(a, m0 + r, ri.b, ri.y, ri.x, col, v + epilogue_terms(a, m0 + r, ri.b, ri.y, ri.x, col));
             }
         }
     }
@@ -426,6 +453,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
 template <int BM, int BN, int WGM, int WGN, int NST>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)    // the buffer-descriptor type and builtins exist in the device pass only
+    // Kernel arguments arrive through scalar loads that the compiler places where a field is first used:
+    // left alone, the set-up below turns into dozens of dependent round trips to the scalar cache.
+    // Naming every field the set-up and the K loop need as an operand of an empty asm statement right
+    // here makes their loads one batch with one wait.
+    asm volatile("" ::"s"(a.a0), "s"(a.a1), "s"(a.C0), "s"(a.C1), "s"(a.a_compact), "s"(a.Hin), "s"(a.Win), "s"(a.ksize), "s"(a.stride),
+                 "s"(a.ups), "s"(a.tile_idx), "s"(a.tile), "s"(a.tiles_w), "s"(a.Ho), "s"(a.Wo));
+    asm volatile("" ::"s"(a.B), "s"(a.Ma), "s"(a.w), "s"(a.N), "s"(a.K), "s"(a.geglu), "s"(a.s0), "s"(a.s1), "s"(a.S0), "s"(a.S1),
+                 "s"(a.w2), "s"(a.K2), "s"(a.splits), "s"(a.partial), "s"(a.gx), "s"(a.gy));
     constexpr int NW = WGM * WGN, NT = 64 * NW;
     constexpr int RB = 8 * NW;                          // tile rows filled by one load slot of the workgroup
     static_assert(BM % RB == 0 && BN % RB == 0, "tile rows must split evenly over the waves");
@@ -642,23 +677,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
 }
 
 // Second half of a split-K launch: one thread per four output columns sums the parked partials in
-// split order (deterministic) and applies the epilogue.  All loads of a thread (up to 16 splits x 16
-// bytes, twice that with the GEGLU gate) are issued before the first add, so the kernel pays one
-// memory round trip rather than one per split.
+// split order (deterministic) and applies the epilogue.  A kernel this small lives on memory round
+// trips, so everything is requested up front: the pixel of the row, then biases, time projection and
+// residual, then all partials (up to 16 splits x 16 bytes, twice that with the GEGLU gate), and only
+// then the first add.
 constexpr int RED_MAXS = 16;
 template <bool GEGLU>
 __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const int rows = a.B * a.Ma;
-    const int nq = a.N / 4;                              // N % 4 == 0 (checked by the launcher)
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (long long)rows * nq) return;
-    const int gm = (int)(i / nq), col = (int)(i % nq) * 4;
+    const int gm = blockIdx.y * 4 + (threadIdx.x >> 6);  // 4 rows per workgroup; 64 threads x 4 columns per row and block
+    const int col = (blockIdx.x * 64 + (threadIdx.x & 63)) * 4;
+    if (gm >= rows || col >= a.N) return;                // N % 4 == 0 (checked by the launcher)
     const int ncols = GEGLU ? 2 * a.N : a.N;
     const size_t stride = (size_t)rows * ncols;
     const float* P = a.partial + (size_t)gm * ncols + col;
     int y = 0, x = gm % a.Ma;
     const int b = gm / a.Ma;
-    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);      // its load overlaps the ones below
+    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
+    float t[4], tg[4];                                   // terms added to the value / gate sums
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        t[q] = (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
+        tg[q] = (GEGLU && a.bias) ? bf2f(a.bias[col + q + a.N]) : 0.f;
+    }
+    float post[4];                                       // added after the gate
+#pragma unroll
+    for (int q = 0; q < 4; ++q) post[q] = epilogue_terms(a, gm, b, y, x, col + q);
     float4 pv[RED_MAXS], pg[GEGLU ? RED_MAXS : 1];
 #pragma unroll
     for (int z = 0; z < RED_MAXS; ++z) {
@@ -678,16 +722,15 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
         v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
         if (GEGLU) { const float4 q = *reinterpret_cast<const float4*>(P + z * stride + a.N); g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w; }
     }
-    const float vv[4] = {v.x, v.y, v.z, v.w}, gg[4] = {g.x, g.y, g.z, g.w};
+    float r[4] = {v.x + t[0], v.y + t[1], v.z + t[2], v.w + t[3]};
+    if (GEGLU) {
+        const float gg[4] = {g.x + tg[0], g.y + tg[1], g.z + tg[2], g.w + tg[3]};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        float r = vv[q] + (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
-        if (GEGLU) {
-            const float gt = gg[q] + (a.bias ? bf2f(a.bias[col + q + a.N]) : 0.f);
-            r = r * (0.5f * gt * (1.0f + erff(gt * 0.70710678118654752f)));
-        }
-        epilogue_store(a, gm, b, y, x, col + q, r);
+        for (int q = 0; q < 4; ++q) r[q] = r[q] * (0.5f * gg[q] * (1.0f + erff(gg[q] * 0.70710678118654752f)));
     }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] += post[q];
+    epilogue_put4(a, gm, b, y, x, col, r);
 }
 
 // (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given statistics
@@ -745,7 +788,7 @@ template <int BM, int BN, int WGM, int WGN, int BK>
 static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipStream_t st) {
     const int rows = a.B * a.Ma;
     const int ncols = a.geglu ? 2 * a.N : a.N;
-    a.splits = (a.N % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
+    a.splits = (a.N % 4 == 0 && a.sect_n % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
     if (a.splits > 1) a.partial = ws->partial;
     a.dbg = g_igemm_dbg;
     a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
@@ -799,10 +842,10 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     }
     FISE_CHECK_LAUNCH("igemm");
     if (a.splits > 1) {
-        const long long n = (long long)rows * (a.N / 4);
-        ProfileScope prof(PROF_REDUCE, 0.0, 2.0 * a.splits * (double)rows * ncols * 4.0, st);
-        if (a.geglu) hipLaunchKernelGGL(igemm_reduce_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL(igemm_reduce_kernel<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+        const dim3 rgrid((unsigned)ceil_div(a.N / 4, 64), (unsigned)ceil_div(rows, 4));
+        ProfileScope prof(PROF_REDUCE, 0.0, (double)a.splits * rows * ncols * 4.0 + 2.0 * rows * a.N, st);
+        if (a.geglu) hipLaunchKernelGGL(igemm_reduce_kernel<true>, rgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a);
         FISE_CHECK_LAUNCH("igemm reduce");
     }
     return FISE_OK;

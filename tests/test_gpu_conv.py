@@ -70,6 +70,15 @@ CASES = [
     ("scalar-cin4", 2, 16, 16, 4, 0, 32, 3, 1, 0, 4, False, 0, False, False, 0.2),
     ("deep-1280-few-rows", 2, 8, 8, 1280, 1280, 1280, 3, 1, 0, 1, True, 1, True, False, 0.2),     # long K, split over workgroups
     ("deep-16x16", 2, 16, 16, 1280, 640, 1280, 3, 1, 0, 2, True, 1, True, False, 0.2),
+    # no prologue and channel counts in multiples of 64: the LDS-direct kernel (zero fill at the borders, two
+    # sources, ragged rows and columns, long split K)
+    ("direct-concat-temb-res", 2, 16, 16, 64, 128, 192, 3, 1, 0, 2, False, 0, True, True, 0.2),
+    ("direct-c1-concat", 2, 16, 16, 128, 64, 64, 1, 1, 0, 4, False, 0, False, True, 0.15),
+    ("direct-ragged-n", 1, 16, 16, 64, 0, 72, 3, 1, 0, 4, False, 0, False, True, 0.1),
+    ("direct-t1-ragged-rows", 1, 8, 8, 128, 0, 128, 3, 1, 0, 1, False, 0, True, False, 0.3),
+    ("direct-deep", 2, 8, 8, 1280, 1280, 1280, 3, 1, 0, 1, False, 0, True, True, 0.2),
+    ("direct-ds-concat", 2, 32, 32, 64, 64, 128, 3, 2, 0, 4, False, 0, False, False, 0.1),
+    ("direct-us-256", 2, 8, 8, 256, 0, 256, 3, 1, 1, 4, False, 0, False, False, 0.1),
 ]
 
 
