@@ -26,8 +26,8 @@ __device__ __forceinline__ void at_lds_barrier() { asm volatile("s_waitcnt lgkmc
 template <int KD, int DB>          // KD: 16-wide steps over the head dim; DB: 32-row blocks of the output head dim
 __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ Vt, int B, int M, int n_keys, int n_stride,
-                                                        int C, int d, float scale_log2e, int splits, bf16_t* __restrict__ out,
-                                                        float* __restrict__ part_o, float* __restrict__ part_ml) {
+                                                        int C, int d, float scale_log2e, int splits, int nqt, int heads,
+                                                        bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
     constexpr int DP = KD * 16;
     constexpr int KP = DP + 8;            // K tile pitch (bf16)
     constexpr int VP = AT_BKV + 8;        // V^T tile pitch
@@ -38,8 +38,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
     __shared__ __attribute__((aligned(16))) bf16_t Vs[DB * 32][VP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5, l32 = lane & 31;
-    const int h = blockIdx.y, b = blockIdx.z / splits, sp = blockIdx.z % splits;
-    const int qrow = blockIdx.x * AT_BQ + wave * AT_QW + l32;
+    // Workgroup -> (query tile qt, head h, batch element b, key split sp).  The grid is one-dimensional
+    // and consecutive workgroups go round-robin to the 8 XCDs (one L2 each): workgroup w takes position
+    // (w % 8) * (total / 8) + w / 8 of the (b, sp, h, qt) order, qt fastest, so the query tiles that
+    // stream the same K / V slice run on one XCD and the slice is fetched from HBM once, not eight times.
+    int qt, h, b, sp;
+    {
+        const int total = nqt * heads * B * splits, chunk = total >> 3;
+        int w = blockIdx.x;
+        if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
+        qt = w % nqt; int t = w / nqt;
+        h = t % heads; t /= heads;
+        sp = t % splits; b = t / splits;
+    }
+    const int qrow = qt * AT_BQ + wave * AT_QW + l32;
     const bool qok = qrow < M;
     const int dchunks = d / 8;
 
@@ -204,7 +216,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                 if (r < d) po[r] = oacc[i][e];
             }
         if (hl == 0) {
-            float* pm = part_ml + ((((size_t)sp * B + b) * gridDim.y + h) * M + qrow) * 2;
+            float* pm = part_ml + ((((size_t)sp * B + b) * heads + h) * M + qrow) * 2;
             pm[0] = m_run; pm[1] = l_run;
         }
     }
@@ -233,10 +245,11 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __res
 template <int KD, int DB>
 static void launch_at(const void* q, const void* K, const void* Vt, int B, int M, int n_keys, int n_stride, int C, int heads,
                       int d, float scale, int splits, void* out, float* part_o, float* part_ml, hipStream_t st) {
-    dim3 grid(ceil_div(M, AT_BQ), heads, B * splits);
+    const int nqt = ceil_div(M, AT_BQ);
+    dim3 grid((unsigned)(nqt * heads * B * splits));
     hipLaunchKernelGGL((attention_kernel<KD, DB>), grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)K,
-                       (const bf16_t*)Vt, B, M, n_keys, n_stride, C, d, scale * 1.4426950408889634f, splits, (bf16_t*)out,
-                       part_o, part_ml);
+                       (const bf16_t*)Vt, B, M, n_keys, n_stride, C, d, scale * 1.4426950408889634f, splits, nqt, heads,
+                       (bf16_t*)out, part_o, part_ml);
 }
 
 static int attention_splits(int B, int M, int n_keys, int heads) {

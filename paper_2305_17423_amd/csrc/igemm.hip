@@ -480,7 +480,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
     {
         const int total = a.gx * a.gy * a.splits, chunk = total >> 3;
         int w = blockIdx.x;
+#ifndef FISE_NO_XCD_REMAP
         if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
+#endif
         bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
     }
     long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
@@ -653,19 +655,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
             if (kc0 + s == kc_begin) FISE_STAMP(3);
             issue((s + NST - 1) % NST);
             const unsigned char* stage = ring + s * STAGE;
+            // all operand fragments of the step are requested before the first MFMA: the LDS round trips
+            // overlap each other and the matrix pipe instead of alternating with it
+            bf16x8_t fa[4][TM], fb[4][TN];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(stage + rda[i][ks]);
+                for (int i = 0; i < TM; ++i) fa[ks][i] = *reinterpret_cast<const bf16x8_t*>(stage + rda[i][ks]);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(stage + rdb[j][ks]);
+                for (int j = 0; j < TN; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8_t*>(stage + rdb[j][ks]);
+            }
+            __builtin_amdgcn_sched_barrier(0);          // keep the scheduler from pairing each read with its MFMA again
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-            }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
         }
     }
     wait_loads<0>();                                    // the trailing out-of-range loads still target the ring
@@ -772,8 +779,7 @@ static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) 
     const int rows = a.B * a.Ma;
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
-    static const int target = [] { const char* e = getenv("FISE_SPLIT_TARGET"); return e ? atoi(e) : 480; }();
-    static const int min_steps = [] { const char* e = getenv("FISE_SPLIT_MIN_STEPS"); return e ? atoi(e) : 4; }();
+    constexpr int target = 480, min_steps = 4;          // measured optimum is flat between 384 and 480 workgroups
     if (tiles * 2 > target || nsteps < min_steps) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
@@ -869,14 +875,12 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     if (a.nsect < 1 || a.nsect > 3 || a.nsect * a.sect_n != a.N) return fail(FISE_ERR_SHAPE, "igemm: sections");
     if (a.K2 != a.S0 + a.S1 || a.S0 % 32 || a.S1 % 32 || (a.K2 > 0 && (!a.w2 || !a.s0 || a.a_compact || a.stride != 1 || a.ups)))
         return fail(FISE_ERR_SHAPE, "igemm: side product");
-    static const int wide_rows = [] { const char* e = getenv("FISE_WIDE_ROWS"); return e ? atoi(e) : 4096; }();
-    const bool wide = rows >= wide_rows && a.N >= 128;     // dense-sized problems: 128x128 tiles
+    const bool wide = rows >= 4096 && a.N >= 128;          // dense-sized problems: 64x128 tiles, 8 waves
     if (a.geglu) {
-        if (wide) return launch_cfg<128, 128, 4, 2>(a, ws, PROF_IGEMM_WIDE, st);
         if (rows <= 32) return launch_cfg<32, 256, 1, 4>(a, ws, PROF_IGEMM_GEGLU, st);
         return launch_cfg<64, 128, 2, 2>(a, ws, PROF_IGEMM_GEGLU, st);
     }
-    if (wide) return launch_cfg<128, 128, 2, 4>(a, ws, PROF_IGEMM_WIDE, st);
+    if (wide) return launch_cfg<64, 128, 2, 4>(a, ws, PROF_IGEMM_WIDE, st);
     if (rows <= 32) return launch_cfg<32, 128, 1, 4>(a, ws, PROF_IGEMM_THIN, st);
     return launch_cfg<64, 64, 2, 2>(a, ws, PROF_IGEMM, st);
 }
