@@ -102,7 +102,7 @@ size_t transformer_ws_bytes(const fise_transformer_args* a) {
 }
 
 int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st) {
-    const int B = a->B, H = a->H, W = a->W, C = a->C, Ma = a->n_active * a->tile * a->tile, rows = B * Ma;
+    const int B = a->B, H = a->H, W = a->W, C = a->C, Ma = a->n_active * a->tile * a->tile;
     const TrWs wl = tr_ws(B, H, W, C, a->G, a->heads, a->n_active, a->tile);
     char* ws = (char*)workspace;
     float* hb = (float*)(ws + wl.h);                 // residual stream of the active tokens, float
@@ -121,9 +121,13 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     IgemmArgs pin = conv_args(a->x, nullptr, C, 0, B, H, W, H, W, 1, 1, 0, a->pin_w, a->pin_b, C, a->tile_idx, a->n_active, a->tile, hb);
     set_gn(pin, a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, a->G, false);
     pin.out_mode[0] = OUT_COMPACT_F32;
+    // every GEMM that completes the residual stream also emits the LayerNorm the next sub-block starts with
+    auto with_ln = [&](IgemmArgs& g, const void* gamma, const void* beta) {
+        g.ln_gamma = (const bf16_t*)gamma; g.ln_beta = (const bf16_t*)beta; g.ln_eps = 1e-5f; g.ln_out = nb;
+    };
+    with_ln(pin, a->ln1_g, a->ln1_b);
     if (int e = launch_igemm(pin, iw, st)) return e;
     // self-attention: LN -> stacked QKV (K, V rows scattered into the caches) -> attention -> out-proj + residual
-    if (int e = launch_ln_rows(hb, 1, rows, C, a->ln1_g, a->ln1_b, 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
     IgemmArgs qkv = lin(nb, C, a->qkv_w, nullptr, 3 * C);
     qkv.nsect = 3; qkv.sect_n = C;
     qkv.out[0] = qb; qkv.out_mode[0] = OUT_COMPACT;
@@ -131,17 +135,15 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     qkv.out[2] = (bf16_t*)a->Vt_cache; qkv.out_mode[2] = OUT_TOKENS_T;
     if (int e = launch_igemm(qkv, iw, st)) return e;
     if (int e = launch_attention(qb, a->K_cache, a->Vt_cache, B, Ma, H * W, H * W, C, a->heads, scale, ob, ws + wl.at, wl.at_bytes, st)) return e;
-    IgemmArgs o1 = lin(ob, C, a->o1_w, a->o1_b, C); into_h(o1);
+    IgemmArgs o1 = lin(ob, C, a->o1_w, a->o1_b, C); into_h(o1); with_ln(o1, a->ln2_g, a->ln2_b);
     if (int e = launch_igemm(o1, iw, st)) return e;
     // cross-attention against the context K/V
-    if (int e = launch_ln_rows(hb, 1, rows, C, a->ln2_g, a->ln2_b, 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
     IgemmArgs q2 = lin(nb, C, a->q2_w, nullptr, C); q2.out[0] = qb;
     if (int e = launch_igemm(q2, iw, st)) return e;
     if (int e = launch_attention(qb, a->K_ctx, a->Vt_ctx, B, Ma, a->n_ctx, a->n_ctx_stride, C, a->heads, scale, ob, nullptr, 0, st)) return e;
-    IgemmArgs o2 = lin(ob, C, a->o2_w, a->o2_b, C); into_h(o2);
+    IgemmArgs o2 = lin(ob, C, a->o2_w, a->o2_b, C); into_h(o2); with_ln(o2, a->ln3_g, a->ln3_b);
     if (int e = launch_igemm(o2, iw, st)) return e;
     // feed-forward: LN -> first GEMM with the GEGLU gate in its epilogue -> second GEMM + residual
-    if (int e = launch_ln_rows(hb, 1, rows, C, a->ln3_g, a->ln3_b, 1e-5f, nb, nullptr, 1, 1, 1, 1, 1, st)) return e;
     IgemmArgs f1 = lin(nb, C, a->ff1_w, a->ff1_b, 4 * C); f1.geglu = 1; f1.out[0] = fb;
     if (int e = launch_igemm(f1, iw, st)) return e;
     IgemmArgs f2 = lin(fb, 4 * C, a->ff2_w, a->ff2_b, C); into_h(f2);

@@ -28,6 +28,9 @@ struct IgemmArgs {
     int nsect, sect_n;                                  // N = nsect * sect_n; section s goes to out[s]
     bf16_t* out[3]; int out_mode[3];
     bf16_t* mirror;                                     // OUT_COMPACT_F32 only: also store a bf16 copy here (may be null)
+    // ---- optional LayerNorm of the finished rows (one OUT_COMPACT_F32 section, N = sect_n): ln_out[rows, N] bf16.
+    // Fused into the split-K reduce launch where the shape allows, otherwise a separate launch.
+    const bf16_t* ln_gamma; const bf16_t* ln_beta; float ln_eps; bf16_t* ln_out;
     // ---- optional side product accumulated into the same tile: 1x1 conv of the raw maps s0 | s1
     // [B,Ho,Wo,S*] at the output pixel with weights w2 [N, K2] and bias2 (K2 = S0 + S1, 0 = none)
     const bf16_t* s0; const bf16_t* s1; int S0, S1; const bf16_t* w2; const bf16_t* bias2; int K2;

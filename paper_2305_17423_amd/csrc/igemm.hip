@@ -740,6 +740,77 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     epilogue_put4(a, gm, b, y, x, col, r);
 }
 
+// Split-K reduce fused with the LayerNorm that follows a residual-stream GEMM: LPR lanes share a row of
+// N = 20 * LPR columns (320 / 640 / 1280), each lane owns 20 consecutive columns as 5 x float4.  The
+// lanes sum the partials in split order on top of bias and residual, store the float row (the new
+// residual stream), then normalise it in registers (two passes, fp32) and store the bf16 LayerNorm row.
+template <int LPR>
+__global__ __launch_bounds__(256) void igemm_reduce_ln_kernel(const IgemmArgs a) {
+    constexpr int C = 20 * LPR, RPB = 256 / LPR;
+    const int rows = a.B * a.Ma;
+    const int row = blockIdx.x * RPB + threadIdx.x / LPR;
+    const int l = threadIdx.x % LPR;
+    if (row >= rows) return;                      // whole LPR-lane groups leave together
+    const size_t off = (size_t)row * C + l * 20;
+    float4 v[5];
+    {
+        const uint2* b2 = a.bias ? reinterpret_cast<const uint2*>(a.bias + l * 20) : nullptr;
+        const float4* r4 = a.res ? reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + off) : nullptr;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            v[j] = r4 ? r4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (b2) {
+                const uint2 bv = b2[j];
+                v[j].x += __uint_as_float(bv.x << 16); v[j].y += __uint_as_float(bv.x & 0xffff0000u);
+                v[j].z += __uint_as_float(bv.y << 16); v[j].w += __uint_as_float(bv.y & 0xffff0000u);
+            }
+        }
+    }
+    const float4* P = reinterpret_cast<const float4*>(a.partial + off);
+    const size_t stride4 = (size_t)rows * C / 4;
+#pragma unroll 4
+    for (int z = 0; z < a.splits; ++z) {
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const float4 p = P[z * stride4 + j];
+            v[j].x += p.x; v[j].y += p.y; v[j].z += p.z; v[j].w += p.w;
+        }
+    }
+    float4* h4 = reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out[0]) + off);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) { h4[j] = v[j]; s += (v[j].x + v[j].y) + (v[j].z + v[j].w); }
+    if (a.mirror) {
+        uint2* m2 = reinterpret_cast<uint2*>(a.mirror + off);
+#pragma unroll
+        for (int j = 0; j < 5; ++j) m2[j] = make_uint2(f2bf2(v[j].x, v[j].y), f2bf2(v[j].z, v[j].w));
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mu = s / C;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const float a0 = v[j].x - mu, a1 = v[j].y - mu, a2 = v[j].z - mu, a3 = v[j].w - mu;
+        q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    const float rs = rsqrtf(q / C + a.ln_eps);
+    const uint2* g2 = reinterpret_cast<const uint2*>(a.ln_gamma + l * 20);
+    const uint2* b2 = reinterpret_cast<const uint2*>(a.ln_beta + l * 20);
+    uint2* o2 = reinterpret_cast<uint2*>(a.ln_out + off);
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const uint2 gv = g2[j], bv = b2[j];
+        const float y0 = (v[j].x - mu) * rs * __uint_as_float(gv.x << 16) + __uint_as_float(bv.x << 16);
+        const float y1 = (v[j].y - mu) * rs * __uint_as_float(gv.x & 0xffff0000u) + __uint_as_float(bv.x & 0xffff0000u);
+        const float y2 = (v[j].z - mu) * rs * __uint_as_float(gv.y << 16) + __uint_as_float(bv.y << 16);
+        const float y3 = (v[j].w - mu) * rs * __uint_as_float(gv.y & 0xffff0000u) + __uint_as_float(bv.y & 0xffff0000u);
+        o2[j] = make_uint2(f2bf2(y0, y1), f2bf2(y2, y3));
+    }
+}
+
 // (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given statistics
 __global__ void gn_table_kernel(const float* __restrict__ mean, const float* __restrict__ rstd, const bf16_t* __restrict__ gamma,
                                 const bf16_t* __restrict__ beta, int B, int Cin, int G, float2* __restrict__ out) {
@@ -847,6 +918,21 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         else hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, false>), grid, dim3(64 * WGM * WGN), 0, st, a);
     }
     FISE_CHECK_LAUNCH("igemm");
+    // LayerNorm of the finished rows: inside the reduce launch when there is one and the row shape is one the
+    // fused kernel is built for, otherwise as a launch of its own after the rows are complete
+    const bool ln = a.ln_out != nullptr;
+    if (ln && (a.nsect != 1 || a.out_mode[0] != OUT_COMPACT_F32 || a.geglu || !a.ln_gamma || !a.ln_beta))
+        return fail(FISE_ERR_SHAPE, "igemm: LayerNorm output needs one float compact section");
+    const bool ln_fused = ln && a.splits > 1 && !a.temb && !a.bias2 && (!a.res || a.res_compact == 2) &&
+                          (a.N == 320 || a.N == 640 || a.N == 1280);
+    if (ln_fused) {
+        ProfileScope prof(PROF_REDUCE, 0.0, (double)a.splits * rows * ncols * 4.0 + 10.0 * rows * a.N, st);
+        if (a.N == 320) hipLaunchKernelGGL(igemm_reduce_ln_kernel<16>, dim3(ceil_div(rows, 16)), dim3(256), 0, st, a);
+        else if (a.N == 640) hipLaunchKernelGGL(igemm_reduce_ln_kernel<32>, dim3(ceil_div(rows, 8)), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(igemm_reduce_ln_kernel<64>, dim3(ceil_div(rows, 4)), dim3(256), 0, st, a);
+        FISE_CHECK_LAUNCH("igemm reduce + layernorm");
+        return FISE_OK;
+    }
     if (a.splits > 1) {
         const dim3 rgrid((unsigned)ceil_div(a.N / 4, 64), (unsigned)ceil_div(rows, 4));
         ProfileScope prof(PROF_REDUCE, 0.0, (double)a.splits * rows * ncols * 4.0 + 2.0 * rows * a.N, st);
@@ -854,6 +940,7 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         else hipLaunchKernelGGL(igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a);
         FISE_CHECK_LAUNCH("igemm reduce");
     }
+    if (ln) return launch_ln_rows(a.out[0], 1, rows, a.N, a.ln_gamma, a.ln_beta, a.ln_eps, a.ln_out, nullptr, 1, 1, 1, 1, 1, st);
     return FISE_OK;
 }
 
