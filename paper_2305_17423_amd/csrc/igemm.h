@@ -37,6 +37,7 @@ struct IgemmArgs {
     // ---- split-K (splits == 1: none)
     int splits; float* partial;
     int gx, gy;                                         // tile grid (row tiles, column tiles); set by the launcher
+    int need_pix;                                       // set by the launcher: the epilogue addresses a map (else rows only)
     long long* dbg;                                     // development aid: per-workgroup phase timestamps (null = off)
 };
 

@@ -103,7 +103,7 @@ __device__ __forceinline__ void build_row_table(const IgemmArgs& a, int m0, int 
         const int gm = m0 + r;
         if (gm < rows) {
             ri.ok = 1; ri.b = gm / a.Ma;
-            if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, ri.y, ri.x);
+            if (a.tile_idx && (a.need_pix || !a.a_compact)) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, ri.y, ri.x);
             else ri.x = gm % a.Ma;                      // compact rows: token = position in the batch element
         }
         rinfo[r] = ri;
@@ -686,9 +686,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
 // Second half of a split-K launch: one thread per four output columns sums the parked partials in
 // split order (deterministic) and applies the epilogue.  A kernel this small lives on memory round
 // trips, so everything is requested up front: the pixel of the row, then biases, time projection and
-// residual, then all partials (up to 16 splits x 16 bytes, twice that with the GEGLU gate), and only
-// then the first add.
-constexpr int RED_MAXS = 16;
+// residual, then the partials (16 bytes per split, twice that with the GEGLU gate, four splits in flight).
 template <bool GEGLU>
 __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const int rows = a.B * a.Ma;
@@ -700,7 +698,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const float* P = a.partial + (size_t)gm * ncols + col;
     int y = 0, x = gm % a.Ma;
     const int b = gm / a.Ma;
-    if (a.tile_idx) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
+    if (a.tile_idx && a.need_pix) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
     float t[4], tg[4];                                   // terms added to the value / gate sums
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -710,21 +708,9 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     float post[4];                                       // added after the gate
 #pragma unroll
     for (int q = 0; q < 4; ++q) post[q] = epilogue_terms(a, gm, b, y, x, col + q);
-    float4 pv[RED_MAXS], pg[GEGLU ? RED_MAXS : 1];
-#pragma unroll
-    for (int z = 0; z < RED_MAXS; ++z) {
-        const int zz = z < a.splits ? z : 0;              // slots past the split count re-read split 0 and are ignored
-        pv[z] = *reinterpret_cast<const float4*>(P + zz * stride);
-        if (GEGLU) pg[z] = *reinterpret_cast<const float4*>(P + zz * stride + a.N);
-    }
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
-#pragma unroll
-    for (int z = 0; z < RED_MAXS; ++z)
-        if (z < a.splits) {
-            v.x += pv[z].x; v.y += pv[z].y; v.z += pv[z].z; v.w += pv[z].w;
-            if (GEGLU) { g.x += pg[z].x; g.y += pg[z].y; g.z += pg[z].z; g.w += pg[z].w; }
-        }
-    for (int z = RED_MAXS; z < a.splits; ++z) {           // more than RED_MAXS splits: the rest one by one
+#pragma unroll 4
+    for (int z = 0; z < a.splits; ++z) {                  // split order: deterministic; four splits in flight
         const float4 p = *reinterpret_cast<const float4*>(P + z * stride);
         v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
         if (GEGLU) { const float4 q = *reinterpret_cast<const float4*>(P + z * stride + a.N); g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w; }
@@ -869,6 +855,8 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     if (a.splits > 1) a.partial = ws->partial;
     a.dbg = g_igemm_dbg;
     a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
+    a.need_pix = a.res && a.res_compact == 0;
+    for (int sct = 0; sct < a.nsect; ++sct) a.need_pix |= a.out_mode[sct] == OUT_MAP || a.out_mode[sct] == OUT_TOKENS_T;
     dim3 grid((unsigned)(a.gx * a.gy * a.splits));
     size_t shmem = 0;
     if (a.pro != PRO_NONE) {
