@@ -450,7 +450,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
 // Rows that do not exist (past the last row, taps outside the image, weight rows past N) carry an
 // offset beyond the descriptor's size: the load returns zeros and touches no memory.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int NST>
+// LINEAR: compact A rows, one source, no side product (the per-token linears): the cursor is a single K offset.
+template <int BM, int BN, int WGM, int WGN, int NST, bool LINEAR>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)    // the buffer-descriptor type and builtins exist in the device pass only
     // Kernel arguments arrive through scalar loads that the compiler places where a field is first used:
@@ -584,7 +585,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
         for (int j = 0; j < AL; ++j) pix[j] = opix[j];
         set_source(); set_weights(kstep);
     };
-    if (kc_begin < nsteps1) {
+    if constexpr (LINEAR) {
+        cur_a = srd_a0; soff_a = (unsigned)kc_begin * 128u;
+#pragma unroll
+        for (int j = 0; j < AL; ++j) va[j] = aok[j] ? (unsigned)(m0 + j * RB + wave * 8 + lr) * (unsigned)a.C0 * 2u + aseg[j] : OOB;
+        set_weights(kc_begin);
+    } else if (kc_begin < nsteps1) {
         const int k0 = kc_begin * 64;
         tap = k0 / Cin; cc = k0 - tap * Cin;
         set_tap(); set_source(); set_weights(kc_begin);
@@ -607,7 +613,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
             __builtin_amdgcn_raw_ptr_buffer_load_lds(cur_b, (__attribute__((address_space(3))) void*)(base + (BM + j * RB) * 128), 16,
                                                      live ? vb[j] : OOB, soff_b, 0, 0);
         if (live) {
-            ++kc_next; cc += 64; soff_a += 128u; soff_b += 128u;
+            ++kc_next; soff_a += 128u; soff_b += 128u;
+            if constexpr (LINEAR) return;
+            cc += 64;
             if (!side) {
                 if (kc_next == nsteps1) { if (kc_next < kc_end) enter_side(0); }
                 else if (cc >= Cin) { cc = 0; ++tap; set_tap(); set_source(); }
@@ -893,13 +901,18 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         constexpr int ring = NST * (BM + BN) * 128;
         static bool raised = false;                     // once per instantiation
         if (!raised && ring > 48 * 1024) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, ring) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, ring) != hipSuccess)
                 return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
             raised = true;
         }
         ProfileScope prof(prof_kind, flops, bytes, st);      // brackets the GEMM launch alone
-        hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, WGM, WGN, NST>), grid, dim3(64 * WGM * WGN), ring, st, a);
+        if (a.a_compact && a.K2 == 0)
+            hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, WGM, WGN, NST, true>), grid, dim3(64 * WGM * WGN), ring, st, a);
+        else
+            hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, WGM, WGN, NST, false>), grid, dim3(64 * WGM * WGN), ring, st, a);
     } else {
         ProfileScope prof(PROF_IGEMM_STAGED, flops, bytes, st);
         if (a.pro != PRO_NONE) hipLaunchKernelGGL((igemm_kernel<BM, BN, WGM, WGN, BK, true>), grid, dim3(64 * WGM * WGN), shmem, st, a);
