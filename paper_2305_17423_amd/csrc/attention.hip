@@ -144,25 +144,30 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
             }
         }
-        // ---- online softmax (this lane: query l32; keys kb*32 + (e/4)*8 + hl*4 + e%4)
-        float mx = m_run;
+        // ---- online softmax (this lane: query l32; keys kb*32 + (e/4)*8 + hl*4 + e%4).  The scale is positive,
+        // so the running maximum is taken over the raw scores and the scale rides on the exponent's
+        // multiply-add; keys that do not exist can only be in the last block of the range.
+        if (k0 + AT_BKV > n_keys) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (k0 + kb * 32 + (e >> 2) * 8 + hl * 4 + (e & 3) >= n_keys) s[kb][e] = -INFINITY;
+        }
+        float mraw = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = k0 + kb * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
-                const float v = key < n_keys ? s[kb][e] * scale_log2e : -INFINITY;
-                s[kb][e] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+            for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[kb][e]);
+        mraw = fmaxf(mraw, __shfl_xor(mraw, 32));
+        const float mx = fmaxf(m_run, mraw * scale_log2e);
         const float alpha = exp2f(m_run - mx);            // first block: exp2(-inf) = 0
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(s[kb][e] - mx);
+                const float p = exp2f(fmaf(s[kb][e], scale_log2e, -mx));
                 s[kb][e] = p;
                 psum += p;
             }
@@ -179,9 +184,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {
-                bf16x8_t pf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (short)f2bf(s[kb][8 * jj + e]);
+                uint4 pw;                                  // eight probabilities as packed bf16 pairs
+                pw.x = f2bf2(s[kb][8 * jj + 0], s[kb][8 * jj + 1]); pw.y = f2bf2(s[kb][8 * jj + 2], s[kb][8 * jj + 3]);
+                pw.z = f2bf2(s[kb][8 * jj + 4], s[kb][8 * jj + 5]); pw.w = f2bf2(s[kb][8 * jj + 6], s[kb][8 * jj + 7]);
+                const bf16x8_t pf = *reinterpret_cast<bf16x8_t*>(&pw);
                 const int kbase = kb * 32 + 16 * jj + hl * 4;
 #pragma unroll
                 for (int i = 0; i < DB; ++i) {

@@ -844,7 +844,13 @@ static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) 
     const int rows = a.B * a.Ma;
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
-    constexpr int target = 480, min_steps = 4;          // measured optimum is flat between 384 and 480 workgroups
+#ifndef FISE_SPLIT_TARGET
+#define FISE_SPLIT_TARGET 480
+#endif
+#ifndef FISE_SPLIT_MIN_STEPS
+#define FISE_SPLIT_MIN_STEPS 4
+#endif
+    constexpr int target = FISE_SPLIT_TARGET, min_steps = FISE_SPLIT_MIN_STEPS;   // measured optimum is flat between 384 and 480 workgroups
     if (tiles * 2 > target || nsteps < min_steps) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
