@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--seed", type=int, default=5000)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB elementwise copy (for scaling FETCH_SIZE / WRITE_SIZE counter readings)")
+    ap.add_argument("--level-sweep", action="store_true",
+                    help="log per-module masked times by block kind, level and blob size, with the dense time (stderr)")
     ap.add_argument("--density-sweep", action="store_true",
                     help="log masked step time for blobs of 1/5/10/25/50 %% of the latent (stderr), then the normal run")
     args = ap.parse_args()
@@ -159,6 +161,37 @@ def main():
                 step(i, int(tiles.size), idx_s)
             log(f"[bench] blob {frac * 100:4.0f} % of pixels -> {tiles.size:2d}/{ntiles} tiles: masked step "
                 f"{timed(max(5, args.steps // 2), int(tiles.size), idx_s):.3f} ms")
+    if args.level_sweep:
+        # One representative module per (kind, level): time it alone, teacher-forced on the cache, for blobs of growing
+        # size and for the full tile list.  Answers where masked stops paying at each level's shape.
+        names = fb.fise_unet_module_names(u)
+        picks = [("ResNet 64x64 C320", "down.0.res.1"), ("ResNet 32x32 C640", "down.1.res.1"), ("ResNet 16x16 C1280", "down.2.res.1"),
+                 ("ResNet 8x8 C1280", "mid.res.0"), ("transformer 64x64 C320", "down.0.tr.1"), ("transformer 32x32 C640", "down.1.tr.1"),
+                 ("transformer 16x16 C1280", "down.2.tr.1"), ("transformer 8x8 C1280", "mid.tr.0")]
+        fracs = (0.01, 0.05, 0.10, 0.25, 0.50)
+        lists = []
+        for frac in fracs:
+            px = wl.ellipse_pixels(np.random.default_rng(args.seed + int(frac * 1000)), H, W, frac)
+            tl = np.flatnonzero(px.reshape(H // bt, bt, W // bt, bt).any(axis=(1, 3)).reshape(-1)).astype(np.int32)
+            buf = torch.zeros(ntiles, dtype=torch.int32, device=dev); buf[:tl.size] = torch.from_numpy(tl).to(dev)
+            lists.append((f"{frac * 100:.0f}%->{tl.size}t", int(tl.size), buf))
+        lists.append(("dense", ntiles, full))
+
+        def time_module(mi, n_act, index, reps=20):
+            for _ in range(3):
+                fb.fise_masked_unet_modules(u, Wd, caches[0], lat_new, t_sin_all[0], kv_new, index, n_act, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fb.fise_masked_unet_modules(u, Wd, caches[0], lat_new, t_sin_all[0], kv_new, index, n_act, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+        log("[bench] module time in us by blob size (pixels -> active 8x8-base tiles of 64):")
+        log("[bench] " + " " * 26 + "".join(f"{lbl:>11s}" for lbl, _, _ in lists))
+        for label, mod in picks:
+            ts = [time_module(names.index(mod), n_act, index) for _, n_act, index in lists]
+            log(f"[bench] {label:26s}" + "".join(f"{t:11.1f}" for t in ts))
     for i in range(args.warmup):
         step(i, na, idx)
     ms_masked = timed(args.steps, na, idx)
