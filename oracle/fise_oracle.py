@@ -401,6 +401,26 @@ def masked_attention_block(x_map, ln_g, ln_b, wq, wk, wv, wo, bo, heads, K_cache
     return y_cache
 
 
+def masked_attention_restricted(x_map, ln_g, ln_b, wq, wk, wv, wo, bo, heads, idx, tile, y_cache, dtype):
+    """The keys-restricted reading of Approximate Attention ("only calculate the
+    results using non-zero regions"): active queries attend to the keys and
+    values of the *active* tokens only; nothing outside the mask is read, so no
+    K/V cache is involved.  y = x + (Attn(LN(x)) Wo^T + bo) at active tokens,
+    scattered into y_cache.  K and V of the active tokens are stored tensors
+    (rounded to the storage dtype) before the products, as in the cached form."""
+    B, H, W, C = x_map.shape
+    ys, xs = active_pixels(idx, tile, W)
+    if ys.size == 0:
+        return y_cache
+    xa = np.asarray(x_map, F64)[:, ys, xs, :]
+    n = layernorm(xa, np.asarray(ln_g, F64), np.asarray(ln_b, F64))
+    k = round_store(linear(n, wk), dtype)
+    v = round_store(linear(n, wv), dtype)
+    o = attention_active(linear(n, wq), k, v, heads)
+    y_cache[:, ys, xs, :] = round_store(xa + linear(o, wo, bo), dtype)
+    return y_cache
+
+
 def context_kv(ctx, wk, wv, dtype):
     """K, V of the text context, computed once per conditioning and stored."""
     return round_store(linear(ctx, wk), dtype), round_store(linear(ctx, wv), dtype)

@@ -355,6 +355,51 @@ def test_masked_attention_block_refreshes_kv_and_matches_dense_rows():
     np.testing.assert_allclose(y_new.reshape(B, H * W, C), want.numpy(), atol=1e-10)
 
 
+def test_keys_restricted_attention_pins():
+    """Active queries x active keys.  Pins: (a) the library's attention on the gathered active tokens alone
+    (torch layer_norm + scaled_dot_product_attention over M keys, not H*W); (b) full mask == the cached form with
+    every key; (c) one active token: softmax over a single key is 1, so y = x + (LN(x) Wv^T) Wo^T + bo, whatever
+    Wq and Wk are; (d) inactive positions keep the cache bit for bit; (e) tokens outside the mask are never read."""
+    rng = np.random.default_rng(16)
+    B, H, W, C, heads, t = 2, 4, 6, 8, 2, 1
+    x = wl.normal(rng, (B, H, W, C)).astype(np.float64)
+    g = 1 + 0.1 * rng.standard_normal(C); b0 = 0.1 * rng.standard_normal(C)
+    wq, wk, wv, wo = (rng.standard_normal((C, C)) * 0.3 for _ in range(4)); bo = rng.standard_normal(C)
+    idx = np.array([2, 3, 9, 14, 20], np.int32)
+    ys, xs = fo.active_pixels(idx, t, W)
+    cache = rng.standard_normal((B, H, W, C))
+    y = fo.masked_attention_restricted(x, g, b0, wq, wk, wv, wo, bo, heads, idx, t, cache.copy(), "f64")
+    # (a)
+    xa = torch.from_numpy(x[:, ys, xs, :])
+    n = F.layer_norm(xa, (C,), torch.from_numpy(g), torch.from_numpy(b0))
+    qh, kh, vh = ((n @ torch.from_numpy(m).T).reshape(B, idx.size, heads, C // heads).permute(0, 2, 1, 3) for m in (wq, wk, wv))
+    o = F.scaled_dot_product_attention(qh, kh, vh).permute(0, 2, 1, 3).reshape(B, idx.size, C)
+    want = xa + o @ torch.from_numpy(wo).T + torch.from_numpy(bo)
+    np.testing.assert_allclose(y[:, ys, xs, :], want.numpy(), atol=1e-11)
+    # (d)
+    act = np.zeros((H, W), bool); act[ys, xs] = True
+    np.testing.assert_array_equal(y[:, ~act], cache[:, ~act])
+    # (e)
+    x2 = x.copy(); x2[:, ~act] = rng.standard_normal((B, (~act).sum(), C))
+    y2 = fo.masked_attention_restricted(x2, g, b0, wq, wk, wv, wo, bo, heads, idx, t, cache.copy(), "f64")
+    np.testing.assert_array_equal(y2, y)
+    # (b)
+    full = fo.full_index(H, W, t)
+    yf = fo.masked_attention_restricted(x, g, b0, wq, wk, wv, wo, bo, heads, full, t, np.zeros((B, H, W, C)), "f64")
+    Kc = np.zeros((B, H * W, C)); Vc = np.zeros((B, H * W, C))
+    yc = fo.masked_attention_block(x, g, b0, wq, wk, wv, wo, bo, heads, Kc, Vc, None, None, full, t, np.zeros((B, H, W, C)), "f64")
+    np.testing.assert_allclose(yf, yc, atol=1e-12)
+    # (c)
+    one = np.array([7], np.int32)
+    y1 = fo.masked_attention_restricted(x, g, b0, wq, wk, wv, wo, bo, heads, one, t, cache.copy(), "f64")
+    py, px = fo.active_pixels(one, t, W)
+    n1 = fo.layernorm(x[:, py, px, :], g, b0)
+    np.testing.assert_allclose(y1[:, py, px, :], x[:, py, px, :] + (n1 @ wv.T) @ wo.T + bo, atol=1e-12)
+    # empty mask: untouched
+    y0 = fo.masked_attention_restricted(x, g, b0, wq, wk, wv, wo, bo, heads, np.zeros(0, np.int32), t, cache.copy(), "f64")
+    np.testing.assert_array_equal(y0, cache)
+
+
 # ---------------------------------------------------------------- Otsu / APSC
 def test_otsu_objective_is_between_class_variance_and_two_cluster_case():
     rng = np.random.default_rng(16)
