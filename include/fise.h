@@ -334,6 +334,20 @@ int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cach
                              int first_module, int n_modules,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* The keys-restricted reading of the same sub-layer (Approximate Attention:
+ * "only calculate the results using non-zero regions" read as restricting the
+ * keys too): each active query attends to the keys and values of the ACTIVE
+ * tokens of its batch element only.  No K/V cache is read or written; cost is
+ * O(M_a^2) instead of O(M_a * H*W).  y = x + Attn(LayerNorm(x)) Wo^T + bo at
+ * active tokens, scattered into y_cache; everything else as fise_masked_attention
+ * (device pointers, bf16, caller-owned workspace of the stated size, n_active == 0
+ * touches nothing, validation errors before any launch). */
+size_t fise_masked_attention_restricted_workspace_bytes(int B, int C, int n_active, int tile);
+int fise_masked_attention_restricted(const void* x, const void* ln_gamma, const void* ln_beta, const void* Wq, const void* Wk,
+                                     const void* Wv, const void* Wo, const void* bo, int dtype, int B, int H, int W, int C,
+                                     int heads, const int32_t* tile_idx, int n_active, int tile, void* y_cache,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * Tracing.  With profiling enabled every launch of the gathered-GEMM and
  * attention kernels is bracketed by two HIP events on the caller's stream

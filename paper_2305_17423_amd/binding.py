@@ -84,6 +84,9 @@ _SIGS = {
     "fise_context_kv_workspace_bytes": (sz, [i32, i32, i32, i32]),
     "fise_context_kv": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]),
     "fise_masked_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
+    "fise_masked_attention_restricted_workspace_bytes": (sz, [i32, i32, i32, i32]),
+    "fise_masked_attention_restricted": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp,
+                                               vp, sz, vp]),
     "fise_masked_attention": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp,
                                     i32, i32, vp, i32, i32, vp, vp, sz, vp]),
     "fise_masked_resnet_block_workspace_bytes": (sz, [C.POINTER(fise_resnet_args)]),
@@ -268,6 +271,18 @@ def fise_context_kv(ctx, Wk, Wv, K_ctx, Vt_ctx, stream=None):
     B, n_ctx, Dc = ctx.shape
     _ck(lib().fise_context_kv(_p(ctx), _p(Wk), _p(Wv), _dt(ctx), B, n_ctx, Dc, Wk.shape[0], Vt_ctx.shape[2], _p(K_ctx),
                               _p(Vt_ctx), None, 0, _stream(stream)))
+
+
+def fise_masked_attention_restricted_workspace_bytes(B, Cc, n_active, tile):
+    return lib().fise_masked_attention_restricted_workspace_bytes(B, Cc, n_active, tile)
+
+
+def fise_masked_attention_restricted(x, ln_gamma, ln_beta, Wq, Wk, Wv, Wo, bo, heads, tile_idx, n_active, tile, y_cache,
+                                     workspace, stream=None):
+    B, H, W, Cc = x.shape
+    _ck(lib().fise_masked_attention_restricted(_p(x), _p(ln_gamma), _p(ln_beta), _p(Wq), _p(Wk), _p(Wv), _p(Wo), _p(bo), _dt(x), B,
+                                               H, W, Cc, heads, _p(tile_idx), n_active, tile, _p(y_cache), _p(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def fise_masked_attention_workspace_bytes(B, Cc, n_active, tile):

@@ -297,3 +297,63 @@ extern "C" int fise_masked_attention(const void* x, const void* ln_gamma, const 
     o.out[0] = (bf16_t*)y_cache; o.out_mode[0] = OUT_MAP;
     return launch_igemm(o, iw, st);
 }
+
+// ---- keys-restricted attention: active queries x keys / values of the active tokens only
+static size_t restricted_vt_stride(int Ma) { return (size_t)((Ma + 7) / 8 * 8); }
+
+extern "C" size_t fise_masked_attention_restricted_workspace_bytes(int B, int C, int n_active, int tile) {
+    if (B < 1 || C < 1 || n_active < 0 || tile < 1) return 0;
+    const int Ma = n_active * tile * tile;
+    const size_t rows = (size_t)B * Ma;
+    return 4 * align256(rows * C * sizeof(bf16_t)) + align256((size_t)B * C * restricted_vt_stride(Ma) * sizeof(bf16_t)) +
+           attention_workspace_bytes(B, Ma, Ma, C, 8) + 256;
+}
+
+extern "C" int fise_masked_attention_restricted(const void* x, const void* ln_gamma, const void* ln_beta, const void* Wq,
+                                                const void* Wk, const void* Wv, const void* Wo, const void* bo, int dtype, int B,
+                                                int H, int W, int C, int heads, const int32_t* tile_idx, int n_active, int tile,
+                                                void* y_cache, void* workspace, size_t workspace_bytes, void* stream) {
+    const char* fn = "fise_masked_attention_restricted";
+    if (!x || !ln_gamma || !ln_beta || !Wq || !Wk || !Wv || !Wo || !y_cache) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    if (dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "%s: bf16 only", fn);
+    if (B < 1 || H < 1 || W < 1 || C < 1 || heads < 1 || C % heads || tile < 1 || H % tile || W % tile)
+        return fail(FISE_ERR_SHAPE, "%s: B%d H%d W%d C%d heads%d tile%d", fn, B, H, W, C, heads, tile);
+    const int d = C / heads;
+    if (C % 32 || d % 8 || d > 160) return fail(FISE_ERR_ALIGN, "%s: C=%d (multiple of 32), head dim %d (multiple of 8, <= 160)", fn, C, d);
+    if (n_active < 0 || n_active > (H / tile) * (W / tile)) return fail(FISE_ERR_CAPACITY, "%s: n_active %d", fn, n_active);
+    if (n_active == 0) return FISE_OK;
+    if (!tile_idx) return fail(FISE_ERR_NULL, "%s: null tile_idx", fn);
+    if (!workspace || workspace_bytes < fise_masked_attention_restricted_workspace_bytes(B, C, n_active, tile))
+        return fail(FISE_ERR_CAPACITY, "%s: workspace too small", fn);
+    if (y_cache == x) return fail(FISE_ERR_SHAPE, "%s: y_cache aliases x", fn);
+
+    hipStream_t st = as_stream(stream);
+    const IgemmWorkspace* iw = nullptr;
+    const int Ma = n_active * tile * tile, rows = B * Ma;
+    const int vstride = (int)restricted_vt_stride(Ma);
+    const size_t buf = align256((size_t)rows * C * sizeof(bf16_t));
+    const size_t vbuf = align256((size_t)B * C * vstride * sizeof(bf16_t));
+    char* ws = (char*)workspace;
+    bf16_t* nbuf = (bf16_t*)ws; bf16_t* qbuf = (bf16_t*)(ws + buf); bf16_t* kbuf = (bf16_t*)(ws + 2 * buf);
+    bf16_t* obuf = (bf16_t*)(ws + 3 * buf); bf16_t* vtbuf = (bf16_t*)(ws + 4 * buf);
+    char* atws = ws + 4 * buf + vbuf;
+    const float scale = 1.0f / sqrtf((float)d);
+
+    if (int e = launch_ln_rows(x, 0, rows, C, ln_gamma, ln_beta, 1e-5f, nbuf, tile_idx, tile, W / tile, H, W, Ma, st)) return e;
+    // Q, K as compact rows; V as compact transposed columns [B, C, vstride] (row r of batch b -> column r): these
+    // launches address rows only, so they carry no tile list
+    IgemmArgs g = linear_args(nbuf, Ma, B, C, Wq, nullptr, C);
+    g.out[0] = qbuf;
+    if (int e = launch_igemm(g, iw, st)) return e;
+    g.w = (const bf16_t*)Wk; g.out[0] = kbuf;
+    if (int e = launch_igemm(g, iw, st)) return e;
+    g.w = (const bf16_t*)Wv; g.out[0] = vtbuf; g.out_mode[0] = OUT_TOKENS_T; g.Ho = 1; g.Wo = vstride;
+    if (int e = launch_igemm(g, iw, st)) return e;
+    if (int e = launch_attention(qbuf, kbuf, vtbuf, B, Ma, Ma, vstride, C, heads, scale, obuf, atws,
+                                 workspace_bytes - (size_t)(atws - ws), st)) return e;
+    IgemmArgs o = linear_args(obuf, Ma, B, C, Wo, bo, C);
+    o.tile_idx = tile_idx; o.tile = tile; o.tiles_w = W / tile; o.Ho = H; o.Wo = W;
+    o.res = (const bf16_t*)x; o.res_compact = 0;
+    o.out[0] = (bf16_t*)y_cache; o.out_mode[0] = OUT_MAP;
+    return launch_igemm(o, iw, st);
+}

@@ -128,3 +128,48 @@ def test_masked_attention_layer(fb, C, heads, H, W, t, frac, cross):
     assert rel_err(gV[:, av], Vw[:, av]) <= TOL[dt] and np.array_equal(gV[:, ~av], V0[:, ~av])
     fb.fise_masked_attention(*args)                                             # idempotent (K/V refresh included)
     assert np.array_equal(host(y), got) and np.array_equal(host(Kd), gK)
+
+
+@pytest.mark.parametrize("C,heads,H,W,t,frac", [(320, 8, 64, 64, 4, 0.10), (320, 8, 64, 64, 4, 0.02), (640, 8, 32, 32, 4, 0.25),
+                                                 (1280, 8, 8, 8, 1, 0.3), (64, 4, 8, 8, 2, 0.3)])
+def test_keys_restricted_attention_layer(fb, C, heads, H, W, t, frac):
+    """Active queries x active keys (no K/V cache): element by element against the oracle, cache kept elsewhere,
+    idempotent, full mask == the cached form with every key, empty mask touches nothing.  Also prints how far the
+    restricted form is from the full-key form on this synthetic input (information, not a check)."""
+    rng = np.random.default_rng(4300 + C + int(frac * 100))
+    B, dt = 2, "bf16"
+    x_old = wl.normal(rng, (B, H, W, C), 1.0, dt)
+    pixm = wl.ellipse_pixels(rng, H, W, frac)
+    x_new = wl.perturb(rng, x_old, pixm, 1.0, dt)
+    _, idx = fo.tiles_from_pixels(pixm, t)
+    full = fo.full_index(H, W, t)
+    g = wl.normal(rng, (C,), 0.02, dt, mean=1.0); b0 = wl.normal(rng, (C,), 0.02, dt)
+    s = 1 / math.sqrt(C)
+    wq, wk, wv, wo = (wl.normal(rng, (C, C), s, dt) for _ in range(4))
+    bo = wl.normal(rng, (C,), 0.02, dt)
+    y_cache = wl.normal(rng, (B, H, W, C), 1.0, dt)
+    want = fo.masked_attention_restricted(x_new, g, b0, wq, wk, wv, wo, bo, heads, idx, t, y_cache.astype(np.float64).copy(), dt)
+    y = dev(y_cache, dt)
+    ws = torch.full((fb.fise_masked_attention_restricted_workspace_bytes(B, C, full.size, t),), 0xFF, dtype=torch.uint8, device=DEV)
+    args = (dev(x_new, dt), dev(g, dt), dev(b0, dt), dev(wq, dt), dev(wk, dt), dev(wv, dt), dev(wo, dt), dev(bo, dt), heads)
+    fb.fise_masked_attention_restricted(*args, idx_dev(idx), idx.size, t, y, ws)
+    act = active_mask(idx, t, H, W)
+    got = host(y)
+    e = check_map(got, want, y_cache.astype(np.float64), act, TOL[dt], "keys-restricted")
+    fb.fise_masked_attention_restricted(*args, idx_dev(idx), idx.size, t, y, ws)
+    assert np.array_equal(host(y), got)                                        # idempotent
+    y0 = dev(y_cache, dt)
+    fb.fise_masked_attention_restricted(*args, idx_dev(idx), 0, t, y0, ws)
+    assert np.array_equal(host(y0), y_cache)                                   # empty mask
+    # full mask: every key is active, so this is ordinary attention = the cached form driven with the full list
+    Kf = np.zeros((B, H * W, C)); Vf = np.zeros((B, H * W, C))
+    wantf = fo.masked_attention_block(x_new, g, b0, wq, wk, wv, wo, bo, heads, Kf, Vf, None, None, full, t, np.zeros((B, H, W, C)), dt)
+    yf = torch.zeros((B, H, W, C), dtype=torch.bfloat16, device=DEV)
+    fb.fise_masked_attention_restricted(*args, idx_dev(full), full.size, t, yf, ws)
+    assert rel_err(host(yf), wantf) <= TOL[dt]
+    # information: distance between the two readings at the active positions (full keys from the old generation's cache)
+    K0 = np.zeros((B, H * W, C)); V0 = np.zeros((B, H * W, C))
+    fo.masked_attention_block(x_old, g, b0, wq, wk, wv, wo, bo, heads, K0, V0, None, None, full, t, np.zeros((B, H, W, C)), dt)
+    allk = fo.masked_attention_block(x_new, g, b0, wq, wk, wv, wo, bo, heads, K0, V0, None, None, idx, t, y_cache.astype(np.float64).copy(), dt)
+    print(f"C={C} {H}x{W} {idx.size} tiles: device vs oracle {e:.2e}; restricted vs all-keys reading (oracle) "
+          f"{rel_err(want[:, act], allk[:, act]):.2e}")
