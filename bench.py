@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--frac", type=float, default=0.10, help="fraction of latent pixels inside the blob")
     ap.add_argument("--tile", type=int, default=8)
-    ap.add_argument("--caches", type=int, default=10, help="distinct per-timestep caches cycled through (260 MB each)")
+    ap.add_argument("--caches", type=int, default=50, help="distinct per-timestep caches cycled through (260 MB each; 50 = one cache per denoising step of an edit)")
     ap.add_argument("--small", action="store_true", help="a narrow UNet for quick checks (not the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
