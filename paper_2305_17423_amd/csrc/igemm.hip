@@ -8,12 +8,13 @@
 // maps at the same pixel (the ResNet shortcut), accumulated into the same tile.
 //
 // The masked problems are small (a few GFLOP, often a few dozen rows against tens
-// of MB of weights), so the kernel is built to keep memory requests in flight
-// rather than to maximise MFMA issue: the K loop moves 64 elements per step, global
-// loads run PF steps ahead of the MFMAs in a register FIFO, LDS tiles are double
-// buffered with one barrier per step, several workgroups share a CU, and long K
-// loops are split over workgroups (partials parked in a workspace, summed in split
-// order by the last workgroup of a tile so the result is deterministic).
+// of MB of weights), so both kernels here are built to keep memory requests in
+// flight rather than to maximise MFMA issue: the K loop moves 64 elements per step,
+// loads run ahead of the MFMAs (igemm_dma_kernel: straight into an LDS ring;
+// igemm_kernel: through a register FIFO, which lets it apply a GroupNorm prologue),
+// several workgroups share a CU, and long K loops are split over workgroups
+// (partials parked in a workspace and summed in split order by a second launch, so
+// the result is deterministic).
 #include <algorithm>
 #include <cstdlib>
 #include "igemm.h"
@@ -214,8 +215,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
         bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
     }
+#ifdef FISE_DEBUG_STAMPS      // development aid: wall-clock stamps of the workgroup's phases
     long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
 #define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
+#else
+#define FISE_STAMP(i) do { } while (0)
+#endif
     FISE_STAMP(0);
     const int m0 = bx * BM;
     const int Cin = a.C0 + a.C1;
@@ -486,8 +491,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
 #endif
         bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
     }
+#ifdef FISE_DEBUG_STAMPS      // development aid: wall-clock stamps of the workgroup's phases
     long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
 #define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
+#else
+#define FISE_STAMP(i) do { } while (0)
+#endif
     FISE_STAMP(0);
     const int m0 = bx * BM;
     const int Cin = a.C0 + a.C1;
@@ -831,7 +840,9 @@ int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hip
     return FISE_OK;
 }
 
-long long* g_igemm_dbg = nullptr;      // set through fise_debug_timing_buffer (development aid)
+#ifdef FISE_DEBUG_STAMPS
+long long* g_igemm_dbg = nullptr;      // set through fise_debug_timing_buffer
+#endif
 
 // How many workgroups share the K loop of one output tile.  A CU pulls operands at a few tens of
 // GB/s whatever runs on it, so what matters most is that every CU streams part of the operands: aim
@@ -867,7 +878,9 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     const int ncols = a.geglu ? 2 * a.N : a.N;
     a.splits = (a.N % 4 == 0 && a.sect_n % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
     if (a.splits > 1) a.partial = ws->partial;
+#ifdef FISE_DEBUG_STAMPS
     a.dbg = g_igemm_dbg;
+#endif
     a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
     a.need_pix = a.res && a.res_compact == 0;
     for (int sct = 0; sct < a.nsect; ++sct) a.need_pix |= a.out_mode[sct] == OUT_MAP || a.out_mode[sct] == OUT_TOKENS_T;
@@ -981,6 +994,8 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
 
 }  // namespace fise
 
+#ifdef FISE_DEBUG_STAMPS
 // Development aid, not part of the documented ABI: a device buffer of 8 x int64 per workgroup that
 // the gathered-GEMM kernels fill with wall-clock stamps of their phases (null switches it off).
 extern "C" void fise_debug_timing_buffer(void* dev) { fise::g_igemm_dbg = (long long*)dev; }
+#endif
