@@ -77,59 +77,92 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         for (int e = 0; e < 16; ++e) oacc[i][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // register staging of one key block (unconditional loads of harmless addresses where nothing exists)
-    uint4 rk[KL], rv[VL];
-    auto fetch = [&](int blk) {
+    // ---- register staging of key blocks.  Thread slot j covers chunk e = tid + 256 j of the block's real data:
+    // K rows of d / 8 chunks (key e / dchunks, chunk e % dchunks), V^T rows of 8 chunks (row e / 8 < d, keys
+    // (e % 8) * 8 ..).  Everything that depends only on the slot is worked out once; a block costs one pointer
+    // bump and one load per slot.  The padding of the LDS tiles (head-dim columns / rows past d) is zeroed once
+    // and never written again.  Keys that do not exist can only occur in the last block of the whole range: that
+    // block alone takes the guarded path (keys past n_keys read nothing and are stored as zeros).
+    constexpr int PFD = (KL + VL <= 6) ? 2 : 1;       // key blocks in flight (small heads can afford two in registers)
+    uint4 rk[PFD][KL], rv[PFD][VL];
+    const bf16_t* pk[KL]; const bf16_t* pv[VL];        // source of the slot in key block 0
+    int kkey[KL], vkey[VL];                            // first key of the slot within a block (-1: slot unused)
+    bf16_t* sk[KL]; bf16_t* sv[VL];                    // destination in the LDS tiles
+#pragma unroll
+    for (int j = 0; j < KL; ++j) {
+        const int e = tid + 256 * j;
+        const int kk = e / dchunks, c8 = e - kk * dchunks;
+        const bool used = e < AT_BKV * dchunks;
+        kkey[j] = used ? kk : -1;
+        pk[j] = K + (used ? ((size_t)b * n_keys + kk) * C + h * d + c8 * 8 : 0);
+        sk[j] = &Ks[used ? kk : 0][used ? c8 * 8 : 0];
+    }
+#pragma unroll
+    for (int j = 0; j < VL; ++j) {
+        const int e = tid + 256 * j;
+        const int r = e >> 3, c8 = e & 7;
+        const bool used = r < d;
+        vkey[j] = used ? c8 * 8 : -1;
+        pv[j] = Vt + (used ? ((size_t)b * C + h * d + r) * n_stride + c8 * 8 : 0);
+        sv[j] = &Vs[used ? r : 0][used ? c8 * 8 : 0];
+    }
+    for (int e = tid; e < AT_BKV * KP / 8; e += 256) reinterpret_cast<uint4*>(&Ks[0][0])[e] = make_uint4(0, 0, 0, 0);
+    for (int e = tid; e < DB * 32 * VP / 8; e += 256) reinterpret_cast<uint4*>(&Vs[0][0])[e] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    auto fetch = [&](int blk, int slot) {
         const int k0 = blk * AT_BKV;
+        if (k0 + AT_BKV <= n_keys) {                     // uniform: a block of existing keys
 #pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            const int e = tid + 256 * j;
-            const int kk = e / (DP / 8), c8 = e % (DP / 8);
-            const bool ok = e < KCH && k0 + kk < n_keys && c8 < dchunks;
-            rk[j] = *reinterpret_cast<const uint4*>(K + (ok ? ((size_t)b * n_keys + k0 + kk) * C + h * d + c8 * 8 : 0));
-        }
+            for (int j = 0; j < KL; ++j) rk[slot][j] = *reinterpret_cast<const uint4*>(pk[j] + (size_t)k0 * C);
 #pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int e = tid + 256 * j;
-            const int r = e / (AT_BKV / 8), c8 = e % (AT_BKV / 8);
-            const bool ok = e < VCH && r < d && k0 + c8 * 8 < n_keys;
-            rv[j] = *reinterpret_cast<const uint4*>(Vt + (ok ? ((size_t)b * C + h * d + r) * n_stride + k0 + c8 * 8 : 0));
+            for (int j = 0; j < VL; ++j) rv[slot][j] = *reinterpret_cast<const uint4*>(pv[j] + k0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < KL; ++j) {
+                const bool ok = kkey[j] >= 0 && k0 + kkey[j] < n_keys;
+                rk[slot][j] = ok ? *reinterpret_cast<const uint4*>(pk[j] + (size_t)k0 * C) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < VL; ++j) {
+                const int key = k0 + vkey[j];
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (vkey[j] >= 0 && key < n_keys) {
+                    v = *reinterpret_cast<const uint4*>(pv[j] + k0);
+                    const int nvalid = n_keys - key;          // keys of this chunk that exist; the rest become zeros
+                    if (nvalid < 8) {
+                        unsigned w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            if (t >= nvalid) w4[t >> 1] &= (t & 1) ? 0x0000ffffu : 0xffff0000u;
+                        v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+                    }
+                }
+                rv[slot][j] = v;
+            }
         }
     };
-    auto stash = [&](int blk) {
-        const int k0 = blk * AT_BKV;
+    auto stash = [&](int slot) {
 #pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            const int e = tid + 256 * j;
-            const int kk = e / (DP / 8), c8 = e % (DP / 8);
-            const bool ok = k0 + kk < n_keys && c8 < dchunks;
-            if (e < KCH) *reinterpret_cast<uint4*>(&Ks[kk][c8 * 8]) = ok ? rk[j] : make_uint4(0, 0, 0, 0);
-        }
+        for (int j = 0; j < KL; ++j)
+            if (kkey[j] >= 0) *reinterpret_cast<uint4*>(sk[j]) = rk[slot][j];
 #pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int e = tid + 256 * j;
-            const int r = e / (AT_BKV / 8), c8 = e % (AT_BKV / 8);
-            const int key = k0 + c8 * 8;
-            uint4 v = rv[j];
-            if (!(r < d && key < n_keys)) v = make_uint4(0, 0, 0, 0);
-            else if (n_keys - key < 8) {                     // zero the keys that do not exist
-                const int nvalid = n_keys - key;
-                unsigned w4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    if (t >= nvalid) w4[t >> 1] &= (t & 1) ? 0x0000ffffu : 0xffff0000u;
-                v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-            }
-            if (e < VCH) *reinterpret_cast<uint4*>(&Vs[r][c8 * 8]) = v;
-        }
+        for (int j = 0; j < VL; ++j)
+            if (vkey[j] >= 0) *reinterpret_cast<uint4*>(sv[j]) = rv[slot][j];
     };
 
-    if (blk0 < blk1) fetch(blk0);
-    for (int blk = blk0; blk < blk1; ++blk) {
+    if (blk0 < blk1) {
+#pragma unroll
+        for (int s = 0; s < PFD; ++s) fetch(min(blk0 + s, blk1 - 1), s);
+    }
+    for (int blk0u = blk0; blk0u < blk1; blk0u += PFD) {
+#pragma unroll
+      for (int slot = 0; slot < PFD; ++slot) {
+        const int blk = blk0u + slot;
+        if (blk >= blk1) break;                            // uniform across the workgroup
         const int k0 = blk * AT_BKV;
         at_lds_barrier();                                  // previous block fully consumed
-        stash(blk);
-        fetch(min(blk + 1, blk1 - 1));                     // next block in flight during the MFMAs below
+        stash(slot);
+        fetch(min(blk + PFD, blk1 - 1), slot);             // PFD blocks ahead, in flight during the MFMAs below
         at_lds_barrier();
 
         // ---- S^T = K Q^T for two 32-key blocks
@@ -161,13 +194,13 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
             for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[kb][e]);
         mraw = fmaxf(mraw, __shfl_xor(mraw, 32));
         const float mx = fmaxf(m_run, mraw * scale_log2e);
-        const float alpha = exp2f(m_run - mx);            // first block: exp2(-inf) = 0
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mx);   // first block: exp2(-inf) = 0
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(fmaf(s[kb][e], scale_log2e, -mx));
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][e], scale_log2e, -mx));   // v_exp_f32: results below 2^-126 flush to 0
                 s[kb][e] = p;
                 psum += p;
             }
@@ -197,6 +230,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                     oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&v), pf, oacc[i], 0, 0, 0);
                 }
             }
+      }
     }
 
     // ---- store: lane holds query l32, head-dim rows i*32 + (e/4)*8 + hl*4 + e%4
