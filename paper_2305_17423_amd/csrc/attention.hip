@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         // ---- online softmax (this lane: query l32; keys kb*32 + (e/4)*8 + hl*4 + e%4).  The scale is positive,
         // so the running maximum is taken over the raw scores and the scale rides on the exponent's
         // multiply-add; keys that do not exist can only be in the last block of the range.
-        if (k0 + AT_BKV > n_keys) {
+        if (__builtin_amdgcn_readfirstlane(k0 + AT_BKV > n_keys)) {      // scalar condition: a real branch, not 32 selects
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
