@@ -38,7 +38,7 @@ def run_detect(fb, x_old, x_new, thr, tile, dtype, capacity=None):
 @pytest.mark.parametrize("seed,dtype,shape,tile,kind", [
     (1001, "f32", (1, 32, 32, 64), 4, "rect"),          # config 1
     (1002, "f32", (1, 32, 32, 64), 4, "rect"),
-    (2001, "bf16", (2, 64, 64, 320), 8, "ellipse"),     # worst case of the survey: 320 channels, batch 2
+    (2001, "bf16", (2, 64, 64, 320), 8, "ellipse"),     # the widest map the step differences: 320 channels, batch 2
     (2002, "bf16", (2, 64, 64, 4), 8, "ellipse"),       # latent
     (2003, "bf16", (2, 24, 40, 5), 4, "ellipse"),       # ragged channel count, non-square
     (2004, "f32", (3, 16, 16, 70), 2, "ellipse"),
