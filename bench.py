@@ -255,7 +255,7 @@ def main():
                                 "config 5: SD-1.5-shaped UNet step, batch 2, latent 64x64x4, context 77x768, seeded blob, "
                                 "8x8 base tiles; mask detect + masked step per timed step"),
                    "pixel_fraction": float(pix.mean()), "active_tile_fraction": na / ntiles, "tile": bt, "caches_cycled": ncache},
-        "masked_ms": ms_masked, "dense_ms": ms_dense, "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None,
+        "masked_ms": ms_masked, "dense_ms": ms_dense, "end_to_end_ms": ms_masked * args.steps, "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None,
         "unet_calls_per_s": 1e3 / ms_masked, "useful_tflops": flops_masked / ms_masked / 1e9,
         "masked_gflop": flops_masked / 1e9, "dense_gflop": flops_dense / 1e9,
         "dense_tflops": (flops_dense / ms_dense / 1e9) if ms_dense else None,
