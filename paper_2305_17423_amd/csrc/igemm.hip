@@ -670,7 +670,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
             // and everybody is done reading the stage that is refilled next)
             wait_loads<(NST - 2) * (AL + BL)>();
             if (kc0 + s == kc_begin) FISE_STAMP(3);
-            issue((s + NST - 1) % NST);
             const unsigned char* stage = ring + s * STAGE;
             // all operand fragments of the step are requested before the first MFMA: the LDS round trips
             // overlap each other and the matrix pipe instead of alternating with it
@@ -683,6 +682,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
                 for (int j = 0; j < TN; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8_t*>(stage + rdb[j][ks]);
             }
             __builtin_amdgcn_sched_barrier(0);          // keep the scheduler from pairing each read with its MFMA again
+            issue((s + NST - 1) % NST);                 // next loads and the cursor's scalar work ride on the LDS latency
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
