@@ -106,17 +106,24 @@ __global__ __launch_bounds__(256) void gn_act_halo_kernel(const bf16_t* __restri
         const uint4 gv = *reinterpret_cast<const uint4*>(gamma + c), bv = *reinterpret_cast<const uint4*>(beta + c);
         const unsigned xw[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w}, bw[4] = {bv.x, bv.y, bv.z, bv.w};
         unsigned ow[4];
+        // the 8 channels of a chunk lie in one group or straddle one boundary (cpg >= 8 here; else divide per channel)
+        const int g0 = c / cpg, edge = (g0 + 1) * cpg;
+        const int g1 = min(g0 + 1, G - 1);
+        const float mu0 = mean[b * G + g0], rs0 = rstd[b * G + g0], mu1 = mean[b * G + g1], rs1 = rstd[b * G + g1];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             float r[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const int g = (c + 2 * e + q) / cpg;
+                const int cc = c + 2 * e + q;
+                float mu, rs;
+                if (cpg >= 8) { const bool hi = cc >= edge; mu = hi ? mu1 : mu0; rs = hi ? rs1 : rs0; }
+                else { const int g = cc / cpg; mu = mean[b * G + g]; rs = rstd[b * G + g]; }
                 const float xv = q ? __uint_as_float(xw[e] & 0xffff0000u) : __uint_as_float(xw[e] << 16);
                 const float ga = q ? __uint_as_float(gw[e] & 0xffff0000u) : __uint_as_float(gw[e] << 16);
                 const float be = q ? __uint_as_float(bw[e] & 0xffff0000u) : __uint_as_float(bw[e] << 16);
-                const float sc = rstd[b * G + g] * ga;
-                float u = xv * sc + (be - mean[b * G + g] * sc);
+                const float sc = rs * ga;
+                float u = xv * sc + (be - mu * sc);
                 if (silu) u = silu_f(u);
                 r[q] = u;
             }
