@@ -250,3 +250,48 @@ def test_sd15_unet_module_by_module(fb, capsys):
         with capsys.disabled():
             print(msg, flush=True)
     run_module_by_module(fb, uo.sd15_desc(), 5020, 0.02, 8, 0.1, say)
+
+
+def test_masked_step_under_graph_capture(fb):
+    """The step allocates nothing, clears nothing with a memset node and never synchronises, so a caller can capture
+    it into a HIP graph.  Each replay (with eager work and synchronisations of the test in between, and the cache
+    reset to its state before the step) must reproduce the eager result bit for bit."""
+    d = uo.tiny_desc(H=32, W=32, base=64)
+    g = torch.Generator(device="cpu").manual_seed(77)
+    u = fb.fise_unet_create(d)
+    H, W, bt, B = d["H"], d["W"], 8, d["B"]
+    ntiles = (H // bt) * (W // bt)
+    Wd = (0.04 * torch.randn(fb.fise_unet_weight_elems(u), generator=g)).to(torch.bfloat16).to(DEV)
+    lat = torch.randn(B, H, W, d["in_ch"], generator=g).to(torch.bfloat16).to(DEV)
+    ctx = torch.randn(B, d["n_ctx"], d["ctx_dim"], generator=g).to(torch.bfloat16).to(DEV)
+    tsd = dev(uo.timestep_embedding(np.full(B, 300.0), d["base"]).astype(np.float32))
+    kv = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_unet_context_kv(u, Wd, ctx, kv)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, ntiles, bt), dtype=torch.uint8, device=DEV)
+    full = idx_dev(fo.full_index(H, W, bt))
+    cache0 = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_masked_unet_step(u, Wd, cache0, lat, tsd, kv, full, ntiles, bt, fb.FISE_STATS_FRESH, None, ws)   # a dense cache
+    lat2 = lat.clone(); lat2[:, 4:13, 9:20, :] += 1.0
+    idx = idx_dev(np.array([1, 2, 5, 6, 9], np.int32)); na = 5
+    eager = cache0.clone()
+    fb.fise_masked_unet_step(u, Wd, eager, lat2, tsd, kv, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
+    torch.cuda.synchronize()
+    assert not torch.equal(eager, cache0)
+
+    work = cache0.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        fb.fise_masked_unet_step(u, Wd, work, lat2, tsd, kv, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)      # warm-up on this stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            fb.fise_masked_unet_step(u, Wd, work, lat2, tsd, kv, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        work.copy_(cache0)
+        ws.random_(0, 255)                                   # the workspace holds anything between calls
+        scratch = torch.randn(1 << 20, device=DEV).sum().item()          # unrelated eager work + a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(work, eager), f"replay {rep} differs from the eager step ({scratch:.1f})"
+    fb.fise_unet_destroy(u)
