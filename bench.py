@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--tile", type=int, default=8)
     ap.add_argument("--caches", type=int, default=50, help="distinct per-timestep caches cycled through (260 MB each; 50 = one cache per denoising step of an edit)")
     ap.add_argument("--small", action="store_true", help="a narrow UNet for quick checks (not the headline workload)")
+    ap.add_argument("--latent", type=int, default=64, help="latent edge (64 = the headline workload; 96 = 768x768 images)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--seed", type=int, default=5000)
@@ -84,7 +85,7 @@ def main():
         sys.exit("bench.py: no GPU")
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    d = SMALL if args.small else SD15
+    d = SMALL if args.small else dict(SD15, H=args.latent, W=args.latent)
     B, H, W, bt = d["B"], d["H"], d["W"], args.tile
     rng = np.random.default_rng(args.seed)
     gen = torch.Generator(device=dev); gen.manual_seed(args.seed)
@@ -252,8 +253,8 @@ def main():
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_masked,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": ("small UNet (not the headline workload)" if args.small else
-                                "config 5: SD-1.5-shaped UNet step, batch 2, latent 64x64x4, context 77x768, seeded blob, "
-                                "8x8 base tiles; mask detect + masked step per timed step"),
+                                f"config 5: SD-1.5-shaped UNet step, batch 2, latent {args.latent}x{args.latent}x4, context 77x768, "
+                                "seeded blob, 8x8 base tiles; mask detect + masked step per timed step"),
                    "pixel_fraction": float(pix.mean()), "active_tile_fraction": na / ntiles, "tile": bt, "caches_cycled": ncache},
         "masked_ms": ms_masked, "dense_ms": ms_dense, "end_to_end_ms": ms_masked * args.steps, "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None,
         "unet_calls_per_s": 1e3 / ms_masked, "useful_tflops": flops_masked / ms_masked / 1e9,
