@@ -57,23 +57,6 @@ __device__ __forceinline__ float epilogue_terms(const IgemmArgs& a, int gm, int 
     return v;
 }
 
-// Store of the finished value v of output element (row gm = (b, y, x), column col), by section.
-__device__ __forceinline__ void epilogue_put(const IgemmArgs& a, int gm, int b, int y, int x, int col, float v) {
-    const int sect = col / a.sect_n, scol = col % a.sect_n;
-    bf16_t* outp = a.out[sect];
-    const int omode = a.out_mode[sect];
-    if (omode == OUT_COMPACT_F32) {
-        reinterpret_cast<float*>(outp)[(size_t)gm * a.sect_n + scol] = v;
-        if (a.mirror) a.mirror[(size_t)gm * a.sect_n + scol] = f2bf(v);
-    } else if (omode == OUT_COMPACT) {
-        outp[(size_t)gm * a.sect_n + scol] = f2bf(v);
-    } else if (omode == OUT_MAP) {
-        outp[(((size_t)b * a.Ho + y) * a.Wo + x) * a.sect_n + scol] = f2bf(v);
-    } else {
-        outp[((size_t)b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v);
-    }
-}
-
 // Four consecutive columns col .. col + 3 of one section (col % 4 == 0, section widths are multiples of 4).
 __device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, int b, int y, int x, int col, const float (&v)[4]) {
     const int sect = col / a.sect_n, scol = col % a.sect_n;
@@ -153,6 +136,7 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         return;
     }
     constexpr int n_out_blocks = TN >= 2 ? TN / 2 : 1;    // GEGLU pairs block j (value) with block j + TN/2 (gate)
+    const size_t HW = (size_t)a.Ho * a.Wo;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         if (a.geglu && j >= n_out_blocks) break;
@@ -160,11 +144,25 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         if (a.geglu) col = by * (BN / 2) + (wave % WGN) * (WN / 2) + j * 32 + (lane & 31);
         else col = by * BN + wn0 + j * 32 + (lane & 31);
         if (col >= a.N) continue;
+        // everything that depends on the column alone, once: biases, section, destination, residual / projection bases
         float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
         if (a.bias2) bias_v += bf2f(a.bias2[col]);
         const float bias_g = (a.geglu && a.bias) ? bf2f(a.bias[col + a.N]) : 0.f;
+        const int sect = col / a.sect_n, scol = col - sect * a.sect_n;
+        bf16_t* const outp = a.out[sect];
+        const int omode = a.out_mode[sect];
+        // Two passes per 32-row block: first every load (time projection, residual), then every store.  The
+        // output may alias the residual (the residual stream is updated in place), so in a single pass the
+        // compiler has to keep each load behind the previous store and the 16 round trips add up.
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            float t[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const RowInfo ri = rinfo[r];
+                t[e] = ri.ok ? epilogue_terms(a, m0 + r, ri.b, ri.y, ri.x, col) : 0.f;
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
@@ -175,7 +173,18 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                     const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
                     v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
                 }
-                epilogue_put(a, m0 + r, ri.b, ri.y, ri.x, col, v + epilogue_terms(a, m0 + r, ri.b, ri.y, ri.x, col));
+                v += t[e];
+                const size_t gm = (size_t)(m0 + r);
+                if (omode == OUT_COMPACT_F32) {
+                    reinterpret_cast<float*>(outp)[gm * a.sect_n + scol] = v;
+                    if (a.mirror) a.mirror[gm * a.sect_n + scol] = f2bf(v);
+                } else if (omode == OUT_COMPACT) {
+                    outp[gm * a.sect_n + scol] = f2bf(v);
+                } else if (omode == OUT_MAP) {
+                    outp[(((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x) * a.sect_n + scol] = f2bf(v);
+                } else {
+                    outp[((size_t)ri.b * a.sect_n + scol) * HW + (size_t)ri.y * a.Wo + ri.x] = f2bf(v);
+                }
             }
         }
     }
