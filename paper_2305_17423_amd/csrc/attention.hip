@@ -233,7 +233,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
       }
     }
 
-    // ---- store: lane holds query l32, head-dim rows i*32 + (e/4)*8 + hl*4 + e%4
+    // ---- store: lane holds query l32, head-dim rows i*32 + (e/4)*8 + hl*4 + e%4: four consecutive elements of e are
+    // four consecutive channels (d is a multiple of 8, so a group of four is inside the head or outside it as a whole)
     if (!qok) return;
     if (splits == 1) {
         const float inv = 1.0f / l_run;
@@ -241,9 +242,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int r = i * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
-                if (r < d) o[r] = f2bf(oacc[i][e] * inv);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int r = i * 32 + q4 * 8 + hl * 4;
+                if (r < d)
+                    *reinterpret_cast<uint2*>(o + r) = make_uint2(f2bf2(oacc[i][4 * q4] * inv, oacc[i][4 * q4 + 1] * inv),
+                                                                  f2bf2(oacc[i][4 * q4 + 2] * inv, oacc[i][4 * q4 + 3] * inv));
             }
     } else {
         // unnormalised partial of this key range: O[sp][b][qrow][h*d + r], (m, l)[sp][b][h][qrow]
@@ -251,9 +254,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int r = i * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
-                if (r < d) po[r] = oacc[i][e];
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int r = i * 32 + q4 * 8 + hl * 4;
+                if (r < d)
+                    *reinterpret_cast<float4*>(po + r) = make_float4(oacc[i][4 * q4], oacc[i][4 * q4 + 1], oacc[i][4 * q4 + 2], oacc[i][4 * q4 + 3]);
             }
         if (hl == 0) {
             float* pm = part_ml + ((((size_t)sp * B + b) * heads + h) * M + qrow) * 2;
