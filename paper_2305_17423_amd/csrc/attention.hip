@@ -267,23 +267,32 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
 }
 
 // out[b,m,c] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s), splits visited in index order.
+// One thread per four channels (d is a multiple of 8: the four share a head, hence the weights).
 __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                               int B, int M, int C, int heads, int d, int splits,
                                                               bf16_t* __restrict__ out) {
+    const int C4 = C / 4;
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (long long)B * M * C) return;
-    const int c = (int)(i % C), m = (int)((i / C) % M), b = (int)(i / ((long long)C * M));
+    if (i >= (long long)B * M * C4) return;
+    const int c = (int)(i % C4) * 4, m = (int)((i / C4) % M), b = (int)(i / ((long long)C4 * M));
     const int h = c / d;
+    const size_t ml_stride = (size_t)B * heads * M * 2, o_stride = (size_t)B * M * C;
+    const float* ml0 = part_ml + (((size_t)b * heads + h) * M + m) * 2;
+    const float* o0 = part_o + ((size_t)b * M + m) * C + c;
     float mx = -INFINITY;
-    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, part_ml[((((size_t)s * B + b) * heads + h) * M + m) * 2]);
-    float num = 0.f, den = 0.f;
+    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml0[s * ml_stride]);
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+#pragma unroll 4
     for (int s = 0; s < splits; ++s) {
-        const float* ml = part_ml + ((((size_t)s * B + b) * heads + h) * M + m) * 2;
-        const float w = exp2f(ml[0] - mx);                 // an empty split has m = -inf: weight 0
-        num += w * part_o[(((size_t)s * B + b) * M + m) * C + c];
-        den += w * ml[1];
+        const float2 ml = *reinterpret_cast<const float2*>(ml0 + s * ml_stride);
+        const float4 o = *reinterpret_cast<const float4*>(o0 + s * o_stride);
+        const float w = __builtin_amdgcn_exp2f(ml.x - mx);  // an empty split has m = -inf: weight 0
+        num.x += w * o.x; num.y += w * o.y; num.z += w * o.z; num.w += w * o.w;
+        den += w * ml.y;
     }
-    out[i] = f2bf(num / den);
+    const float inv = 1.0f / den;
+    *reinterpret_cast<uint2*>(out + ((size_t)b * M + m) * C + c) = make_uint2(f2bf2(num.x * inv, num.y * inv), f2bf2(num.z * inv, num.w * inv));
 }
 
 template <int KD, int DB>
@@ -335,7 +344,7 @@ int launch_attention(const void* q, const void* K, const void* Vt, int B, int M,
     }
     FISE_CHECK_LAUNCH("attention");
     if (splits > 1) {
-        const long long n = (long long)B * M * C;
+        const long long n = (long long)B * M * (C / 4);
         ProfileScope prof(PROF_ATTENTION_MERGE, 0.0, (double)splits * B * M * C * 4.0 + 2.0 * B * M * C, st);
         hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part_o, part_ml, B, M, C,
                            heads, d, splits, (bf16_t*)out);
