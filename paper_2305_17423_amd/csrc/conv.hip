@@ -56,6 +56,53 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
     Elem<T>::st(y + o, acc);
 }
 
+// The 4-channel latent under a 3x3 kernel (the UNet's input convolution): the 36 input
+// values of one pixel are loaded once and shared by four output channels, whose 36 weights
+// each are contiguous.  Same accumulation order as the scalar kernel above.
+__global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __restrict__ x, int B, int H, int W,
+                                                             const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+                                                             int Cout, const float* __restrict__ temb, const bf16_t* residual,
+                                                             const int* __restrict__ tile_idx, int Ma, int tile, bf16_t* y) {
+    const int q4 = Cout >> 2;
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)B * Ma * q4) return;
+    const int co = (int)(i % q4) * 4;
+    const int m = (int)((i / q4) % Ma);
+    const int b = (int)(i / ((long long)q4 * Ma));
+    int oy, ox;
+    active_pixel(tile_idx, m, tile, W / tile, oy, ox);
+    float xin[36];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int iy = oy + t / 3 - 1, ix = ox + t % 3 - 1;
+        uint2 v = make_uint2(0u, 0u);
+        if (iy >= 0 && iy < H && ix >= 0 && ix < W) v = *(const uint2*)(x + (((size_t)b * H + iy) * W + ix) * 4);
+        xin[t * 4 + 0] = __uint_as_float(v.x << 16); xin[t * 4 + 1] = __uint_as_float(v.x & 0xffff0000u);
+        xin[t * 4 + 2] = __uint_as_float(v.y << 16); xin[t * 4 + 3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+    const size_t o = (((size_t)b * H + oy) * W + ox) * Cout + co;
+    float acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint2* wr = (const uint2*)(w + (size_t)(co + j) * 36);   // 72 B per channel: 8-byte aligned
+        float a = 0.f;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const uint2 v = wr[t];
+            a = fmaf(xin[t * 4 + 0], __uint_as_float(v.x << 16), a);
+            a = fmaf(xin[t * 4 + 1], __uint_as_float(v.x & 0xffff0000u), a);
+            a = fmaf(xin[t * 4 + 2], __uint_as_float(v.y << 16), a);
+            a = fmaf(xin[t * 4 + 3], __uint_as_float(v.y & 0xffff0000u), a);
+        }
+        if (bias) a += Elem<bf16_t>::ld(bias + co + j);
+        if (temb) a += temb[b * Cout + co + j];
+        if (residual) a += Elem<bf16_t>::ld(residual + o + j);
+        acc[j] = a;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) Elem<bf16_t>::st(y + o + j, acc[j]);
+}
+
 static int validate(const fise_conv_args* a, int& Ho, int& Wo) {
     if (!a) return fail(FISE_ERR_NULL, "fise_masked_conv: null args");
     if (!a->x0 || !a->w || !a->y_cache) return fail(FISE_ERR_NULL, "fise_masked_conv: null x / w / y_cache");
@@ -103,6 +150,16 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     if (int e = validate(a, Ho, Wo)) return e;
     if (a->n_active == 0) return FISE_OK;
     if (!mfma_path(a)) {
+        if (a->dtype == FISE_BF16 && a->C0 == 4 && a->C1 == 0 && a->ksize == 3 && a->stride == 1 && !a->upsample &&
+            !a->gn_mean && a->Cout % 4 == 0) {
+            const int Ma = a->n_active * a->tile * a->tile;
+            const long long total = (long long)a->B * Ma * (a->Cout / 4);
+            hipLaunchKernelGGL(conv_latent3x3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                               (const bf16_t*)a->x0, a->B, a->H, a->W, (const bf16_t*)a->w, (const bf16_t*)a->bias, a->Cout,
+                               a->temb, (const bf16_t*)a->residual, a->tile_idx, Ma, a->tile, (bf16_t*)a->y_cache);
+            FISE_CHECK_LAUNCH("fise_masked_conv(latent 3x3)");
+            return FISE_OK;
+        }
         if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st);
         else launch_scalar<bf16_t>(a, Ho, Wo, st);
         FISE_CHECK_LAUNCH("fise_masked_conv(scalar)");

@@ -68,6 +68,8 @@ CASES = [
     ("narrow-out", 2, 16, 16, 64, 0, 4, 3, 1, 0, 4, True, 1, False, False, 0.2),
     ("ragged-n", 1, 16, 16, 32, 0, 72, 3, 1, 0, 4, False, 0, False, True, 0.1),
     ("scalar-cin4", 2, 16, 16, 4, 0, 32, 3, 1, 0, 4, False, 0, False, False, 0.2),
+    ("latent-temb-res", 2, 16, 16, 4, 0, 320, 3, 1, 0, 2, False, 0, True, True, 0.2),          # the 4-channel 3x3 kernel
+    ("scalar-cin4-ds", 2, 16, 16, 4, 0, 32, 3, 2, 0, 4, False, 0, False, False, 0.2),          # generic scalar kernel
     ("deep-1280-few-rows", 2, 8, 8, 1280, 1280, 1280, 3, 1, 0, 1, True, 1, True, False, 0.2),     # long K, split over workgroups
     ("deep-16x16", 2, 16, 16, 1280, 640, 1280, 3, 1, 0, 2, True, 1, True, False, 0.2),
     # no prologue and channel counts in multiples of 64: the LDS-direct kernel (zero fill at the borders, two
