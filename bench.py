@@ -245,6 +245,12 @@ def main():
     else:
         roofline = dict(bound="mfma", kernel=dom, achieved=dk["tflops"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=f_mfma,
                         traffic=traffic, algorithmic_flops_per_launch=dk["gflop_per_launch"] * 1e9)
+    # what this GPU itself reaches on a plain copy and on a register-resident MFMA loop (context for the published peaks)
+    scratch = torch.empty(2 << 30, dtype=torch.uint8, device=dev)      # 1 GiB each way: past the 256 MB last-level cache
+    copy_gbs, mfma_tf = fb.fise_calibrate_peaks(scratch)
+    del scratch
+    roofline["empirical"] = dict(copy_gbs=copy_gbs, mfma_bf16_tflops=mfma_tf, hbm_frac_of_copy=dk["gbs"] / copy_gbs,
+                                 mfma_frac_of_loop=dk["tflops"] / mfma_tf)
     roofline.update(avg_launch_us=dk["avg_us"], avg_launch_us_raw=dk["avg_us_raw"], empty_bracket_us=empty_us,
                     launches_per_step=dk["launches_per_step"], mfma_frac=f_mfma, hbm_frac=f_hbm)
 

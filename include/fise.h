@@ -367,6 +367,16 @@ int fise_profile_enable(int on);
 int fise_profile_calibrate(int n, void* stream);
 int fise_profile_read(int kind, double* total_ms, double* total_flops, double* total_bytes, int* launches);
 
+/* Empirical ceilings of the current device, for the benchmark's roofline: the rate
+ * of a plain streaming copy inside `scratch` (first half -> second half; bytes read +
+ * bytes written per second, GB/s) and the rate of a register-resident bf16 MFMA loop
+ * with no memory traffic (TFLOP/s).  Best of five timed passes each, after two
+ * untimed ones.  scratch: device, 16-byte aligned, >= 64 MiB, overwritten (give well
+ * over twice the 256 MB last-level cache to measure HBM and not that cache).  The two
+ * results are host doubles.  WAITS for its own launches on `stream` (HIP events);
+ * not to be called under graph capture. */
+int fise_calibrate_peaks(void* scratch, size_t scratch_bytes, double* copy_gbs, double* mfma_bf16_tflops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

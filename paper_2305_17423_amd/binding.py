@@ -105,6 +105,7 @@ _SIGS = {
     "fise_masked_unet_step": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), vp, sz, vp]),
     "fise_profile_enable": (i32, [i32]),
     "fise_profile_calibrate": (i32, [i32, vp]),
+    "fise_calibrate_peaks": (i32, [vp, sz, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]),
     "fise_profile_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]),
     "fise_unet_num_modules": (i32, [vp]),
     "fise_unet_module_name": (i32, [vp, i32, C.c_char_p]),
@@ -422,6 +423,14 @@ def fise_profile_enable(on):
 
 def fise_profile_calibrate(n, stream=None):
     _ck(lib().fise_profile_calibrate(int(n), _stream(stream)))
+
+
+def fise_calibrate_peaks(scratch, stream=None):
+    """(copy GB/s, bf16 MFMA TFLOP/s) measured on the current device; `scratch` is overwritten."""
+    gbs, tf = C.c_double(), C.c_double()
+    _ck(lib().fise_calibrate_peaks(_p(scratch), scratch.numel() * scratch.element_size(), C.byref(gbs), C.byref(tf),
+                                   _stream(stream)))
+    return gbs.value, tf.value
 
 
 def fise_profile_read(kind):
