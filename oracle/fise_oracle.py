@@ -90,14 +90,23 @@ def pixel_diff(cached: np.ndarray, fresh: np.ndarray) -> np.ndarray:
     return s / np.float32(B * C)
 
 
-def tiles_from_pixels(pix: np.ndarray, tile: int):
+def tile_hw(tile):
+    """A tile is a square edge (int) or a rectangular block (h, w), the shapes
+    the adaptive block-size selection chooses among."""
+    if isinstance(tile, (tuple, list)):
+        return int(tile[0]), int(tile[1])
+    return int(tile), int(tile)
+
+
+def tiles_from_pixels(pix: np.ndarray, tile):
     """Pixel mask -> (tile mask, ascending tile index list).  A tile is active
     iff any pixel inside it is."""
     H, W = pix.shape
-    if H % tile or W % tile:
+    bh, bw = tile_hw(tile)
+    if H % bh or W % bw:
         raise ValueError("H, W must be multiples of tile")
-    th, tw = H // tile, W // tile
-    tmask = pix.reshape(th, tile, tw, tile).astype(bool).any(axis=(1, 3))
+    th, tw = H // bh, W // bw
+    tmask = pix.reshape(th, bh, tw, bw).astype(bool).any(axis=(1, 3))
     idx = np.flatnonzero(tmask.reshape(-1)).astype(np.int32)
     return tmask.astype(np.uint8), idx
 
@@ -118,20 +127,22 @@ def mask_downsample(tmask: np.ndarray) -> np.ndarray:
     return tmask.reshape(H // 2, 2, W // 2, 2).astype(bool).any(axis=(1, 3)).astype(np.uint8)
 
 
-def active_pixels(idx, tile: int, W: int):
+def active_pixels(idx, tile, W: int):
     """Coordinates (ys, xs) of the active pixels of a W-wide map, tile by tile
     in list order, row-major inside each tile."""
     idx = np.asarray(idx, np.int64)
-    tw = W // tile
+    bh, bw = tile_hw(tile)
+    tw = W // bw
     ty, tx = idx // tw, idx % tw
-    oy, ox = np.divmod(np.arange(tile * tile), tile)
-    ys = (ty[:, None] * tile + oy[None, :]).reshape(-1)
-    xs = (tx[:, None] * tile + ox[None, :]).reshape(-1)
+    oy, ox = np.divmod(np.arange(bh * bw), bw)
+    ys = (ty[:, None] * bh + oy[None, :]).reshape(-1)
+    xs = (tx[:, None] * bw + ox[None, :]).reshape(-1)
     return ys, xs
 
 
-def full_index(H: int, W: int, tile: int) -> np.ndarray:
-    return np.arange((H // tile) * (W // tile), dtype=np.int32)
+def full_index(H: int, W: int, tile) -> np.ndarray:
+    bh, bw = tile_hw(tile)
+    return np.arange((H // bh) * (W // bw), dtype=np.int32)
 
 
 def normalize_minmax(a: np.ndarray) -> np.ndarray:

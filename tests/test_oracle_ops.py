@@ -438,3 +438,36 @@ def test_apsc_bruteforce():
     assert fo.apsc_block_size(p)[:2] == (2, 2)
     # as printed, blocks smaller than the kernel have non-positive cost and are skipped
     assert fo.apsc_block_size(p, as_written=True)[:2] == (4, 4)
+
+
+def test_rectangular_tiles_bruteforce_and_library():
+    """Blocks of h x w pixels (the shapes the adaptive block-size selection picks from): the tile list against loops
+    written here, the pixel enumeration against the same loops, and the convolution on such blocks against the
+    library convolution at exactly the covered pixels."""
+    rng = np.random.default_rng(23)
+    H, W = 8, 16
+    for bh, bw in ((2, 4), (4, 2), (8, 2), (2, 16), (1, 4)):
+        pix = (rng.random((H, W)) < 0.06).astype(np.uint8)
+        tmask, idx = fo.tiles_from_pixels(pix, (bh, bw))
+        want_ids, covered = [], np.zeros((H, W), bool)
+        for ty in range(H // bh):
+            for tx in range(W // bw):
+                if pix[ty * bh:(ty + 1) * bh, tx * bw:(tx + 1) * bw].any():
+                    want_ids.append(ty * (W // bw) + tx)
+                    covered[ty * bh:(ty + 1) * bh, tx * bw:(tx + 1) * bw] = True
+        assert idx.tolist() == want_ids and tmask.shape == (H // bh, W // bw) and int(tmask.sum()) == len(want_ids)
+        ys, xs = fo.active_pixels(idx, (bh, bw), W)
+        want_px = [(t // (W // bw) * bh + oy, t % (W // bw) * bw + ox) for t in want_ids for oy in range(bh) for ox in range(bw)]
+        assert list(zip(ys.tolist(), xs.tolist())) == want_px
+        assert fo.full_index(H, W, (bh, bw)).size == (H // bh) * (W // bw)
+        B, Ci, Co = 2, 3, 4
+        x = wl.normal(rng, (B, H, W, Ci)); w = wl.normal(rng, (Co, 3, 3, Ci), 0.3); bias = wl.normal(rng, (Co,))
+        cache = rng.standard_normal((B, H, W, Co))
+        y = cache.copy()
+        fo.masked_conv(x, w, bias, idx, (bh, bw), y, "f64")
+        want = nhwc(F.conv2d(nchw(x), oihw(w), torch.from_numpy(bias).double(), padding=1))
+        np.testing.assert_allclose(y[:, covered], want[:, covered], atol=1e-12)
+        np.testing.assert_array_equal(y[:, ~covered], cache[:, ~covered])
+    assert fo.tiles_from_pixels(np.zeros((H, W), np.uint8), (2, 4))[1].size == 0
+    with pytest.raises(ValueError):
+        fo.tiles_from_pixels(np.zeros((H, W), np.uint8), (3, 4))
