@@ -73,6 +73,9 @@ def main():
                     help="log per-module masked times by block kind, level and blob size, with the dense time (stderr)")
     ap.add_argument("--density-sweep", action="store_true",
                     help="log masked step time for blobs of 1/5/10/25/50 %% of the latent (stderr), then the normal run")
+    ap.add_argument("--apsc-sweep", action="store_true",
+                    help="log the time of one masked 3x3 convolution (C=320, level-0 map) for every candidate block size of the "
+                         "adaptive block-size selection, with the selection's own pick (stderr)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1")
@@ -193,6 +196,42 @@ def main():
         for label, mod in picks:
             ts = [time_module(names.index(mod), n_act, index) for _, n_act, index in lists]
             log(f"[bench] {label:26s}" + "".join(f"{t:11.1f}" for t in ts))
+    if args.apsc_sweep:
+        # The convolution the selection is defined for, on this step's own pixel mask: gathered pixels (its cost
+        # function) and measured time for each of the 25 block shapes.
+        Cc = d["base"]
+        xa = torch.randn((B, H, W, Cc), device=dev, generator=gen).to(torch.bfloat16)
+        wa = (0.02 * torch.randn((Cc, 3, 3, Cc), device=dev, generator=gen)).to(torch.bfloat16)
+        ya = torch.zeros((B, H, W, Cc), dtype=torch.bfloat16, device=dev)
+        pixd = torch.from_numpy(np.ascontiguousarray(pix.astype(np.uint8))).to(dev)
+        counts = torch.zeros(25, dtype=torch.int32, device=dev)
+        fb.fise_apsc_block_counts(pixd, counts)
+        ch = counts.cpu().tolist()
+        pick = fb.fise_apsc_select(ch)
+        log(f"[bench] block-size selection on the {int(pix.sum())}-pixel mask picks {pick[0]}x{pick[1]} (cost {pick[2]} gathered pixels)")
+        wsa = None
+        for i, bh in enumerate((2, 4, 8, 16, 32)):
+            for j, bw in enumerate((2, 4, 8, 16, 32)):
+                if ch[i * 5 + j] < 0:
+                    continue
+                nb = (H // bh) * (W // bw)
+                tmr = torch.zeros(nb, dtype=torch.uint8, device=dev); ixr = torch.zeros(nb, dtype=torch.int32, device=dev)
+                nr = torch.zeros(1, dtype=torch.int32, device=dev)
+                fb.fise_mask_from_pixels_rect(pixd, bh, bw, tmr, ixr, nr)
+                nblk = int(nr.item())
+                a = fb.conv_args(xa, wa, None, ixr, nblk, bh, ya, tile_w=bw)
+                if wsa is None:
+                    wsa = torch.zeros(fb.fise_masked_conv_workspace_bytes(a), dtype=torch.uint8, device=dev)
+                for _ in range(5):
+                    fb.fise_masked_conv(a, wsa)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(50):
+                    fb.fise_masked_conv(a, wsa)
+                e1.record(); torch.cuda.synchronize()
+                log(f"[bench]   {bh:2d}x{bw:<2d}: {nblk:4d} blocks, {nblk * bh * bw:5d} output pixels, cost {(bh + 2) * (bw + 2) * nblk:6d}, "
+                    f"conv {e0.elapsed_time(e1) / 50 * 1e3:6.1f} us")
     for i in range(args.warmup):
         step(i, na, idx)
     ms_masked = timed(args.steps, na, idx)

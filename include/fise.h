@@ -108,6 +108,20 @@ int fise_diff_accumulate(const void* cached, const void* fresh, int dtype, int B
  * map give -1.  The argmin of (h+2)(w+2)*count is a 25-element host loop. */
 int fise_apsc_block_counts(const uint8_t* pix_mask, int H, int W, int32_t* counts, void* stream);
 
+/* The argmin itself, on the host: counts is the HOST copy of the 25 counts above,
+ * (kh, kw) the kernel size.  cost(h,w) = (h+kh-1)(w+kw-1)*count, the gathered
+ * input pixels of all blocks (the printed (h-kh+1)(w-kw+1) is read with (h,w) as
+ * the output block, since it vanishes for h < kh).  Sizes with count -1 are
+ * skipped; ties go to the first size in (h, w) row-major order.  Returns
+ * FISE_ERR_SHAPE when no size divides the map.  All pointers host; cost may be NULL. */
+int fise_apsc_select(const int32_t* counts, int kh, int kw, int* h, int* w, int64_t* cost);
+
+/* fise_mask_from_pixels for rectangular blocks of tile_h x tile_w pixels: tile_mask
+ * [H/tile_h, W/tile_w], tile_idx ascending row-major block ids, same capacity and
+ * n_active rules. */
+int fise_mask_from_pixels_rect(const uint8_t* pix_mask, int H, int W, int tile_h, int tile_w, uint8_t* tile_mask,
+                               int32_t* tile_idx, int capacity, int32_t* n_active, void* stream);
+
 /* ------------------------------------------------------------------------
  * Normalisation (section "Approximate Normalization": mean and variance cached
  * from the previous generation are reused at masked positions).
@@ -156,6 +170,9 @@ typedef struct {
     const int32_t* tile_idx; int n_active; int tile;
     void* y_cache;               /* [B, Ho, Wo, Cout] */
     int dtype;
+    int tile_w;                  /* 0: square tiles of edge `tile`; else tiles of `tile` rows x `tile_w` columns,
+                                    the rectangular blocks of the adaptive block-size selection (tile_idx then
+                                    counts such blocks row-major, as fise_mask_from_pixels_rect writes them) */
 } fise_conv_args;
 size_t fise_masked_conv_workspace_bytes(const fise_conv_args* a);     /* `a` host */
 int fise_masked_conv(const fise_conv_args* a /* host */, void* workspace, size_t workspace_bytes, void* stream);

@@ -33,7 +33,7 @@ class fise_conv_args(C.Structure):
                 ("w", vp), ("bias", vp), ("Cout", i32), ("ksize", i32), ("stride", i32), ("upsample", i32),
                 ("gn_mean", vp), ("gn_rstd", vp), ("gn_gamma", vp), ("gn_beta", vp), ("G", i32), ("gn_silu", i32),
                 ("temb", vp), ("residual", vp), ("tile_idx", vp), ("n_active", i32), ("tile", i32),
-                ("y_cache", vp), ("dtype", i32)]
+                ("y_cache", vp), ("dtype", i32), ("tile_w", i32)]
 
 
 class fise_resnet_args(C.Structure):
@@ -72,6 +72,8 @@ _SIGS = {
     "fise_otsu_mask": (i32, [vp, i32, vp, vp, vp, vp]),
     "fise_diff_accumulate": (i32, [vp, vp, i32, i32, i32, i32, i32, vp, vp]),
     "fise_apsc_block_counts": (i32, [vp, i32, i32, vp, vp]),
+    "fise_apsc_select": (i32, [C.POINTER(C.c_int32), i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]),
+    "fise_mask_from_pixels_rect": (i32, [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp]),
     "fise_groupnorm_stats_workspace_bytes": (sz, [i32, i32, i32, i32]),
     "fise_groupnorm_stats": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]),
     "fise_masked_groupnorm_silu": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp]),
@@ -133,8 +135,8 @@ def _p(t):
     """Device (or host) address of a tensor, None -> NULL."""
     if t is None:
         return None
-    if isinstance(t, int):
-        return t
+    if not hasattr(t, "data_ptr"):          # a bare number here would reach a kernel as an address
+        raise TypeError(f"expected a tensor or None where a buffer is passed, got {type(t).__name__}")
     return t.data_ptr()
 
 
@@ -178,6 +180,12 @@ def fise_mask_from_pixels(pix_mask, tile, tile_mask, tile_idx, n_active, stream=
                                     _p(n_active), _stream(stream)))
 
 
+def fise_mask_from_pixels_rect(pix_mask, tile_h, tile_w, tile_mask, tile_idx, n_active, stream=None):
+    H, W = pix_mask.shape
+    _ck(lib().fise_mask_from_pixels_rect(_p(pix_mask), H, W, tile_h, tile_w, _p(tile_mask), _p(tile_idx), tile_idx.numel(),
+                                         _p(n_active), _stream(stream)))
+
+
 def fise_mask_downsample(mask, out, stream=None):
     H, W = mask.shape
     _ck(lib().fise_mask_downsample(_p(mask), H, W, _p(out), _stream(stream)))
@@ -201,6 +209,14 @@ def fise_apsc_block_counts(pix_mask, counts, stream=None):
     _ck(lib().fise_apsc_block_counts(_p(pix_mask), H, W, _p(counts), _stream(stream)))
 
 
+def fise_apsc_select(counts_host, kh=3, kw=3):
+    """(h, w, cost) from the 25 block counts (a host sequence of ints)."""
+    arr = (C.c_int32 * 25)(*[int(v) for v in counts_host])
+    h, w, cost = i32(), i32(), i64()
+    _ck(lib().fise_apsc_select(arr, kh, kw, C.byref(h), C.byref(w), C.byref(cost)))
+    return h.value, w.value, cost.value
+
+
 # --------------------------------------------------------------------------- normalisation
 def fise_groupnorm_stats_workspace_bytes(B, H, W, Cc):
     return lib().fise_groupnorm_stats_workspace_bytes(B, H, W, Cc)
@@ -221,7 +237,7 @@ def fise_masked_groupnorm_silu(x, mean, rstd, gamma, beta, G, tile_idx, n_active
 
 # --------------------------------------------------------------------------- convolution
 def conv_args(x0, w, bias, tile_idx, n_active, tile, y_cache, x1=None, ksize=3, stride=1, upsample=0, gn=None,
-              gn_silu=1, temb=None, residual=None):
+              gn_silu=1, temb=None, residual=None, tile_w=0):
     B, H, W, C0 = x0.shape
     a = fise_conv_args()
     a.x0, a.x1, a.C0, a.C1 = _p(x0), _p(x1), C0, (0 if x1 is None else x1.shape[-1])
@@ -231,7 +247,7 @@ def conv_args(x0, w, bias, tile_idx, n_active, tile, y_cache, x1=None, ksize=3, 
         a.gn_mean, a.gn_rstd, a.gn_gamma, a.gn_beta, a.G = _p(gn["mean"]), _p(gn["rstd"]), _p(gn["gamma"]), _p(gn["beta"]), gn["groups"]
     a.gn_silu = gn_silu
     a.temb, a.residual, a.tile_idx, a.n_active, a.tile = _p(temb), _p(residual), _p(tile_idx), n_active, tile
-    a.y_cache, a.dtype = _p(y_cache), _dt(x0)
+    a.y_cache, a.dtype, a.tile_w = _p(y_cache), _dt(x0), tile_w
     return a
 
 

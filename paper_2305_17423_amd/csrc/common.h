@@ -54,14 +54,20 @@ template <> struct Elem<bf16_t> {
 };
 
 // Active-pixel enumeration shared by all masked kernels: row m of the active set
-// -> (y, x) on a map that is `tiles_w` tiles wide with tile edge `tile`.
-__device__ __forceinline__ void active_pixel(const int* __restrict__ tile_idx, int m, int tile, int tiles_w,
+// -> (y, x) on a map that is `tiles_w` tiles wide, tiles of th x tw pixels, row-major
+// inside a tile.
+__device__ __forceinline__ void active_pixel(const int* __restrict__ tile_idx, int m, int th, int tw, int tiles_w,
                                              int& y, int& x) {
-    const int tt = tile * tile;
+    const int tt = th * tw;
     const int t = tile_idx[m / tt];
     const int p = m % tt;
-    y = (t / tiles_w) * tile + p / tile;
-    x = (t % tiles_w) * tile + p % tile;
+    y = (t / tiles_w) * th + p / tw;
+    x = (t % tiles_w) * tw + p % tw;
+}
+// square tiles of edge `tile`
+__device__ __forceinline__ void active_pixel(const int* __restrict__ tile_idx, int m, int tile, int tiles_w,
+                                             int& y, int& x) {
+    active_pixel(tile_idx, m, tile, tile, tiles_w, y, x);
 }
 
 }  // namespace fise

@@ -13,8 +13,8 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
                                                           const float* __restrict__ gn_mean, const float* __restrict__ gn_rstd,
                                                           const T* __restrict__ gn_gamma, const T* __restrict__ gn_beta, int G,
                                                           int gn_silu, const float* __restrict__ temb, const T* residual,
-                                                          const int* __restrict__ tile_idx, int Ma, int tile, int Ho, int Wo,
-                                                          T* y) {
+                                                          const int* __restrict__ tile_idx, int Ma, int tile, int tile_w, int Ho,
+                                                          int Wo, T* y) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long total = (long long)B * Ma * Cout;
     if (i >= total) return;
@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
     const int m = (int)((i / Cout) % Ma);
     const int b = (int)(i / ((long long)Cout * Ma));
     int oy, ox;
-    active_pixel(tile_idx, m, tile, Wo / tile, oy, ox);
+    active_pixel(tile_idx, m, tile, tile_w, Wo / tile_w, oy, ox);
     const int Cin = C0 + C1, pad = ksize >> 1;
     const int cpg = gn_mean ? Cin / G : 1;
     float acc = 0.f;
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
 __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __restrict__ x, int B, int H, int W,
                                                              const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
                                                              int Cout, const float* __restrict__ temb, const bf16_t* residual,
-                                                             const int* __restrict__ tile_idx, int Ma, int tile, bf16_t* y) {
+                                                             const int* __restrict__ tile_idx, int Ma, int tile, int tile_w, bf16_t* y) {
     const int q4 = Cout >> 2;
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (long long)B * Ma * q4) return;
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __res
     const int m = (int)((i / q4) % Ma);
     const int b = (int)(i / ((long long)q4 * Ma));
     int oy, ox;
-    active_pixel(tile_idx, m, tile, W / tile, oy, ox);
+    active_pixel(tile_idx, m, tile, tile_w, W / tile_w, oy, ox);
     float xin[36];
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
@@ -103,6 +103,8 @@ __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __res
     for (int j = 0; j < 4; ++j) Elem<bf16_t>::st(y + o + j, acc[j]);
 }
 
+static int tile_cols(const fise_conv_args* a) { return a->tile_w > 0 ? a->tile_w : a->tile; }
+
 static int validate(const fise_conv_args* a, int& Ho, int& Wo) {
     if (!a) return fail(FISE_ERR_NULL, "fise_masked_conv: null args");
     if (!a->x0 || !a->w || !a->y_cache) return fail(FISE_ERR_NULL, "fise_masked_conv: null x / w / y_cache");
@@ -115,10 +117,12 @@ static int validate(const fise_conv_args* a, int& Ho, int& Wo) {
     if (a->stride == 2 && ((a->H & 1) || (a->W & 1))) return fail(FISE_ERR_SHAPE, "fise_masked_conv: stride 2 needs even H, W");
     Ho = a->upsample ? 2 * a->H : a->H / a->stride;
     Wo = a->upsample ? 2 * a->W : a->W / a->stride;
-    if (a->tile < 1 || Ho % a->tile || Wo % a->tile)
-        return fail(FISE_ERR_SHAPE, "fise_masked_conv: output %dx%d not divisible by tile %d", Ho, Wo, a->tile);
-    if (a->n_active < 0 || a->n_active > (Ho / a->tile) * (Wo / a->tile))
-        return fail(FISE_ERR_CAPACITY, "fise_masked_conv: n_active %d beyond the %dx%d tile grid", a->n_active, Ho / a->tile, Wo / a->tile);
+    if (a->tile < 1 || a->tile_w < 0) return fail(FISE_ERR_SHAPE, "fise_masked_conv: tile %d, tile_w %d", a->tile, a->tile_w);
+    const int tw = tile_cols(a);
+    if (Ho % a->tile || Wo % tw)
+        return fail(FISE_ERR_SHAPE, "fise_masked_conv: output %dx%d not divisible by the %dx%d tile", Ho, Wo, a->tile, tw);
+    if (a->n_active < 0 || a->n_active > (Ho / a->tile) * (Wo / tw))
+        return fail(FISE_ERR_CAPACITY, "fise_masked_conv: n_active %d beyond the %dx%d tile grid", a->n_active, Ho / a->tile, Wo / tw);
     if (a->n_active > 0 && !a->tile_idx) return fail(FISE_ERR_NULL, "fise_masked_conv: null tile_idx");
     if (a->gn_mean) {
         if (!a->gn_rstd || !a->gn_gamma || !a->gn_beta) return fail(FISE_ERR_NULL, "fise_masked_conv: incomplete GroupNorm arguments");
@@ -137,12 +141,12 @@ static bool mfma_path(const fise_conv_args* a) {
 
 template <typename T>
 static void launch_scalar(const fise_conv_args* a, int Ho, int Wo, hipStream_t st) {
-    const int Ma = a->n_active * a->tile * a->tile;
+    const int Ma = a->n_active * a->tile * tile_cols(a);
     const long long total = (long long)a->B * Ma * a->Cout;
     hipLaunchKernelGGL(conv_scalar_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a->x0,
                        (const T*)a->x1, a->C0, a->C1, a->B, a->H, a->W, (const T*)a->w, (const T*)a->bias, a->Cout, a->ksize,
                        a->stride, a->upsample ? 1 : 0, a->gn_mean, a->gn_rstd, (const T*)a->gn_gamma, (const T*)a->gn_beta,
-                       a->G, a->gn_silu, a->temb, (const T*)a->residual, a->tile_idx, Ma, a->tile, Ho, Wo, (T*)a->y_cache);
+                       a->G, a->gn_silu, a->temb, (const T*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), Ho, Wo, (T*)a->y_cache);
 }
 
 int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st) {
@@ -152,11 +156,11 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     if (!mfma_path(a)) {
         if (a->dtype == FISE_BF16 && a->C0 == 4 && a->C1 == 0 && a->ksize == 3 && a->stride == 1 && !a->upsample &&
             !a->gn_mean && a->Cout % 4 == 0) {
-            const int Ma = a->n_active * a->tile * a->tile;
+            const int Ma = a->n_active * a->tile * tile_cols(a);
             const long long total = (long long)a->B * Ma * (a->Cout / 4);
             hipLaunchKernelGGL(conv_latent3x3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                                (const bf16_t*)a->x0, a->B, a->H, a->W, (const bf16_t*)a->w, (const bf16_t*)a->bias, a->Cout,
-                               a->temb, (const bf16_t*)a->residual, a->tile_idx, Ma, a->tile, (bf16_t*)a->y_cache);
+                               a->temb, (const bf16_t*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), (bf16_t*)a->y_cache);
             FISE_CHECK_LAUNCH("fise_masked_conv(latent 3x3)");
             return FISE_OK;
         }
@@ -168,8 +172,8 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     IgemmArgs g{};
     g.a0 = (const bf16_t*)a->x0; g.a1 = (const bf16_t*)a->x1; g.C0 = a->C0; g.C1 = a->C1; g.a_compact = 0;
     g.Hin = a->H; g.Win = a->W; g.ksize = a->ksize; g.stride = a->stride; g.ups = a->upsample ? 1 : 0;
-    g.tile_idx = a->tile_idx; g.tile = a->tile; g.tiles_w = Wo / a->tile; g.Ho = Ho; g.Wo = Wo; g.B = a->B;
-    g.Ma = a->n_active * a->tile * a->tile;
+    g.tile_idx = a->tile_idx; g.tile = a->tile; g.tile_w = tile_cols(a); g.tiles_w = Wo / g.tile_w; g.Ho = Ho; g.Wo = Wo; g.B = a->B;
+    g.Ma = a->n_active * a->tile * g.tile_w;
     g.pro = a->gn_mean ? (a->gn_silu ? PRO_GN_SILU : PRO_GN) : PRO_NONE;
     g.gn_mean = a->gn_mean; g.gn_rstd = a->gn_rstd; g.gn_gamma = (const bf16_t*)a->gn_gamma; g.gn_beta = (const bf16_t*)a->gn_beta; g.G = a->G;
     g.w = (const bf16_t*)a->w; g.N = a->Cout; g.K = a->ksize * a->ksize * (a->C0 + a->C1); g.geglu = 0;

@@ -15,7 +15,7 @@ struct IgemmArgs {
     int a_compact;                                      // 1: a0 is a compact bf16 [rows, C0] buffer (ksize must be 1)
     int Hin, Win, ksize, stride, ups;
     // ---- row geometry (output map)
-    const int* tile_idx; int tile, tiles_w, Ho, Wo, B, Ma;
+    const int* tile_idx; int tile, tile_w, tiles_w, Ho, Wo, B, Ma;   // tiles of tile x tile_w pixels (tile_w 0: square)
     // ---- prologue on A: GroupNorm (+SiLU) with given statistics
     int pro; const float* gn_mean; const float* gn_rstd; const bf16_t* gn_gamma; const bf16_t* gn_beta; int G;
     const float2* gn_table;                             // [B, Cin] (scale, shift), filled by the launcher when it has scratch

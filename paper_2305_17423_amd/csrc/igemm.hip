@@ -87,7 +87,7 @@ __device__ __forceinline__ void build_row_table(const IgemmArgs& a, int m0, int 
         const int gm = m0 + r;
         if (gm < rows) {
             ri.ok = 1; ri.b = gm / a.Ma;
-            if (a.tile_idx && (a.need_pix || !a.a_compact)) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, ri.y, ri.x);
+            if (a.tile_idx && (a.need_pix || !a.a_compact)) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tile_w, a.tiles_w, ri.y, ri.x);
             else ri.x = gm % a.Ma;                      // compact rows: token = position in the batch element
         }
         rinfo[r] = ri;
@@ -473,7 +473,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
     // Naming every field the set-up and the K loop need as an operand of an empty asm statement right
     // here makes their loads one batch with one wait.
     asm volatile("" ::"s"(a.a0), "s"(a.a1), "s"(a.C0), "s"(a.C1), "s"(a.a_compact), "s"(a.Hin), "s"(a.Win), "s"(a.ksize), "s"(a.stride),
-                 "s"(a.ups), "s"(a.tile_idx), "s"(a.tile), "s"(a.tiles_w), "s"(a.Ho), "s"(a.Wo));
+                 "s"(a.ups), "s"(a.tile_idx), "s"(a.tile), "s"(a.tile_w), "s"(a.tiles_w), "s"(a.Ho), "s"(a.Wo));
     asm volatile("" ::"s"(a.B), "s"(a.Ma), "s"(a.w), "s"(a.N), "s"(a.K), "s"(a.geglu), "s"(a.s0), "s"(a.s1), "s"(a.S0), "s"(a.S1),
                  "s"(a.w2), "s"(a.K2), "s"(a.splits), "s"(a.partial), "s"(a.gx), "s"(a.gy));
     constexpr int NW = WGM * WGN, NT = 64 * NW;
@@ -725,7 +725,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const float* P = a.partial + (size_t)gm * ncols + col;
     int y = 0, x = gm % a.Ma;
     const int b = gm / a.Ma;
-    if (a.tile_idx && a.need_pix) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tiles_w, y, x);
+    if (a.tile_idx && a.need_pix) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tile_w, a.tiles_w, y, x);
     float t[4], tg[4];                                   // terms added to the value / gate sums
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -892,6 +892,7 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     a.dbg = g_igemm_dbg;
 #endif
     a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
+    if (a.tile_w <= 0) a.tile_w = a.tile;
     a.need_pix = a.res && a.res_compact == 0;
     for (int sct = 0; sct < a.nsect; ++sct) a.need_pix |= a.out_mode[sct] == OUT_MAP || a.out_mode[sct] == OUT_TOKENS_T;
     dim3 grid((unsigned)(a.gx * a.gy * a.splits));

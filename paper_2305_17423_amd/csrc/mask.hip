@@ -55,20 +55,20 @@ __global__ __launch_bounds__(DET_PIX) void pixel_diff_kernel(const T* __restrict
 // tile OR + ordered compaction, one workgroup; tiles are taken 256 at a time,
 // the running base keeps ids ascending across chunks.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void tile_compact_kernel(const uint8_t* __restrict__ pix, int H, int W, int tile,
+__global__ __launch_bounds__(256) void tile_compact_kernel(const uint8_t* __restrict__ pix, int H, int W, int tile_h, int tile_w,
                                                            uint8_t* __restrict__ tile_mask, int* __restrict__ idx,
                                                            int capacity, int* __restrict__ n_active) {
     __shared__ int wave_cnt[4];
-    const int tw = W / tile, nt = tw * (H / tile);
+    const int tw = W / tile_w, nt = tw * (H / tile_h);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int base = 0;
     for (int c0 = 0; c0 < nt; c0 += 256) {
         const int t = c0 + threadIdx.x;
         bool act = false;
         if (t < nt) {
-            const int y0 = (t / tw) * tile, x0 = (t % tw) * tile;
-            for (int yy = 0; yy < tile; ++yy)
-                for (int xx = 0; xx < tile; ++xx) act |= pix[(y0 + yy) * W + x0 + xx] != 0;
+            const int y0 = (t / tw) * tile_h, x0 = (t % tw) * tile_w;
+            for (int yy = 0; yy < tile_h; ++yy)
+                for (int xx = 0; xx < tile_w; ++xx) act |= pix[(y0 + yy) * W + x0 + xx] != 0;
             tile_mask[t] = act ? 1 : 0;
         }
         const unsigned long long bal = __ballot(act);
@@ -198,9 +198,22 @@ extern "C" int fise_mask_from_pixels(const uint8_t* pix_mask, int H, int W, int 
     if (!pix_mask || !tile_mask || !tile_idx || !n_active) return fail(FISE_ERR_NULL, "fise_mask_from_pixels: null pointer");
     if (int e = check_tile("fise_mask_from_pixels", H, W, tile)) return e;
     if (capacity < 0) return fail(FISE_ERR_CAPACITY, "fise_mask_from_pixels: capacity %d", capacity);
-    hipLaunchKernelGGL(tile_compact_kernel, dim3(1), dim3(256), 0, as_stream(stream), pix_mask, H, W, tile, tile_mask,
+    hipLaunchKernelGGL(tile_compact_kernel, dim3(1), dim3(256), 0, as_stream(stream), pix_mask, H, W, tile, tile, tile_mask,
                        tile_idx, capacity, n_active);
     FISE_CHECK_LAUNCH("fise_mask_from_pixels");
+    return FISE_OK;
+}
+
+extern "C" int fise_mask_from_pixels_rect(const uint8_t* pix_mask, int H, int W, int tile_h, int tile_w, uint8_t* tile_mask,
+                                          int32_t* tile_idx, int capacity, int32_t* n_active, void* stream) {
+    if (!pix_mask || !tile_mask || !tile_idx || !n_active) return fail(FISE_ERR_NULL, "fise_mask_from_pixels_rect: null pointer");
+    if (tile_h < 1 || tile_w < 1 || H < 1 || W < 1 || H % tile_h || W % tile_w)
+        return fail(FISE_ERR_SHAPE, "fise_mask_from_pixels_rect: H=%d, W=%d must be positive multiples of the %dx%d block", H, W,
+                    tile_h, tile_w);
+    if (capacity < 0) return fail(FISE_ERR_CAPACITY, "fise_mask_from_pixels_rect: capacity %d", capacity);
+    hipLaunchKernelGGL(tile_compact_kernel, dim3(1), dim3(256), 0, as_stream(stream), pix_mask, H, W, tile_h, tile_w, tile_mask,
+                       tile_idx, capacity, n_active);
+    FISE_CHECK_LAUNCH("fise_mask_from_pixels_rect");
     return FISE_OK;
 }
 
@@ -263,5 +276,22 @@ extern "C" int fise_apsc_block_counts(const uint8_t* pix_mask, int H, int W, int
     if (H < 1 || W < 1) return fail(FISE_ERR_SHAPE, "fise_apsc_block_counts: H=%d W=%d", H, W);
     hipLaunchKernelGGL(apsc_count_kernel, dim3(25), dim3(256), 0, as_stream(stream), pix_mask, H, W, counts);
     FISE_CHECK_LAUNCH("fise_apsc_block_counts");
+    return FISE_OK;
+}
+
+extern "C" int fise_apsc_select(const int32_t* counts, int kh, int kw, int* h, int* w, int64_t* cost) {
+    if (!counts || !h || !w) return fail(FISE_ERR_NULL, "fise_apsc_select: null pointer");
+    if (kh < 1 || kw < 1) return fail(FISE_ERR_SHAPE, "fise_apsc_select: kernel %dx%d", kh, kw);
+    int64_t best = -1;
+    for (int i = 0; i < 5; ++i)
+        for (int j = 0; j < 5; ++j) {
+            const int32_t n = counts[i * 5 + j];
+            if (n < 0) continue;
+            const int bh = 2 << i, bw = 2 << j;
+            const int64_t c = (int64_t)(bh + kh - 1) * (bw + kw - 1) * n;
+            if (best < 0 || c < best) { best = c; *h = bh; *w = bw; }
+        }
+    if (best < 0) return fail(FISE_ERR_SHAPE, "fise_apsc_select: no candidate block size divides the map");
+    if (cost) *cost = best;
     return FISE_OK;
 }

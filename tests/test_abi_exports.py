@@ -75,3 +75,38 @@ def test_unet_plan_matches_oracle_tables():
     bad = uo.tiny_desc(base=48)
     with pytest.raises(fb.FiseError):
         fb.fise_unet_create(bad)
+
+
+def test_apsc_select_is_the_oracle_argmin():
+    """The host argmin over the 25 candidate block sizes against the oracle's selection, counts taken from the oracle."""
+    import numpy as np
+    from oracle import fise_oracle as fo
+    from paper_2305_17423_amd import workloads as wl
+    for seed, (H, W), frac in ((1, (32, 32), 0.1), (2, (64, 64), 0.03), (3, (64, 32), 0.3), (4, (48, 48), 0.1), (5, (32, 64), 0.6)):
+        pix = wl.ellipse_pixels(np.random.default_rng(seed), H, W, frac)
+        for kh, kw in ((3, 3), (1, 1)):
+            counts = []
+            for h in (2, 4, 8, 16, 32):
+                for w in (2, 4, 8, 16, 32):
+                    c = fo.apsc_cost(pix, h, w, kh, kw)
+                    counts.append(-1 if c is None else c // ((h + kh - 1) * (w + kw - 1)))
+            assert fb.fise_apsc_select(counts, kh, kw) == fo.apsc_block_size(pix, kh, kw)
+    with pytest.raises(fb.FiseError):
+        fb.fise_apsc_select([-1] * 25)
+    L = fb.lib()
+    a = 0x1000
+    assert L.fise_mask_from_pixels_rect(a, 8, 8, 3, 4, a, a, 4, a, None) == -2               # H % tile_h
+    assert L.fise_mask_from_pixels_rect(a, 8, 8, 2, 0, a, a, 4, a, None) == -2
+    args = fb.fise_conv_args()
+    args.x0 = args.w = a; args.y_cache = 0x2000; args.B = 1; args.H = args.W = 8; args.C0 = 32; args.Cout = 32
+    args.ksize = 3; args.stride = 1; args.tile = 4; args.tile_w = 3; args.dtype = fb.FISE_BF16
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -2                       # W % tile_w
+    args.tile_w = 2; args.n_active = 9
+    assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == -5                       # 2 x 4 = 8 blocks
+
+
+def test_binding_refuses_numbers_where_buffers_go():
+    """A Python number in a buffer position would reach a kernel as an address: the binding raises instead."""
+    with pytest.raises(TypeError):
+        fb._p(12)
+    assert fb._p(None) is None

@@ -81,6 +81,14 @@ CASES = [
     ("direct-deep", 2, 8, 8, 1280, 1280, 1280, 3, 1, 0, 1, False, 0, True, True, 0.2),
     ("direct-ds-concat", 2, 32, 32, 64, 64, 128, 3, 2, 0, 4, False, 0, False, False, 0.1),
     ("direct-us-256", 2, 8, 8, 256, 0, 256, 3, 1, 1, 4, False, 0, False, False, 0.1),
+    # rectangular h x w blocks (adaptive block-size selection): LDS-direct, GroupNorm-prologue, scalar and resampling paths
+    ("rect-2x8-direct", 2, 16, 16, 64, 64, 128, 3, 1, 0, (2, 8), False, 0, True, True, 0.15),
+    ("rect-8x2-gn", 2, 16, 32, 64, 0, 96, 3, 1, 0, (8, 2), True, 1, True, False, 0.15),
+    ("rect-4x16-c1", 1, 16, 32, 128, 0, 64, 1, 1, 0, (4, 16), False, 0, False, True, 0.2),
+    ("rect-2x4-ds", 2, 32, 32, 64, 0, 64, 3, 2, 0, (2, 4), False, 0, False, False, 0.1),
+    ("rect-4x2-us", 2, 8, 8, 64, 0, 64, 3, 1, 1, (4, 2), False, 0, False, False, 0.1),
+    ("rect-2x4-latent", 2, 16, 16, 4, 0, 32, 3, 1, 0, (2, 4), False, 0, True, False, 0.2),
+    ("rect-4x2-scalar-gn", 1, 8, 16, 8, 0, 12, 3, 1, 0, (4, 2), True, 1, False, True, 0.2),
 ]
 
 
@@ -124,10 +132,11 @@ def test_bf16_conv_variants(fb, case):
     x0d, x1d, wd, bd = dev(x0, dt), (dev(x1, dt) if C1 else None), dev(w, dt), dev(bias, dt)
     tembd = dev(temb) if use_temb else None
     resd = dev(res, dt) if use_res else None
+    th, tw = (t[0], t[1]) if isinstance(t, tuple) else (t, 0)
     for ix in (idx, full, np.zeros(0, np.int32)):
         y = dev(cache, dt)
-        a = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, t, y, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
-                         gn_silu=silu, temb=tembd, residual=resd)
+        a = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, th, y, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
+                         gn_silu=silu, temb=tembd, residual=resd, tile_w=tw)
         # with the split-K scratch (filled with garbage: the library zeroes what it needs) ...
         ws = torch.full((fb.fise_masked_conv_workspace_bytes(a),), 0xA5, dtype=torch.uint8, device=DEV)
         fb.fise_masked_conv(a, ws)
@@ -137,8 +146,8 @@ def test_bf16_conv_variants(fb, case):
         assert np.array_equal(host(y), got), "not idempotent"
         # ... and without it (no K split): same result up to the summation order
         y2 = dev(cache, dt)
-        a2 = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, t, y2, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
-                          gn_silu=silu, temb=tembd, residual=resd)
+        a2 = fb.conv_args(x0d, wd, bd, idx_dev(ix), ix.size, th, y2, x1=x1d, ksize=k, stride=stride, upsample=ups, gn=gnd,
+                          gn_silu=silu, temb=tembd, residual=resd, tile_w=tw)
         fb.fise_masked_conv(a2)
         check_map(host(y2), oracle(ix), cache.astype(np.float64), active_mask(ix, t, Ho, Wo), TOL[dt], f"{name} unsplit n={ix.size}")
 
@@ -155,3 +164,35 @@ def test_conv_residual_in_place(fb):
     y = dev(cache, "bf16")
     fb.fise_masked_conv3x3(dev(x, "bf16"), dev(w, "bf16"), dev(bias, "bf16"), 1, idx_dev(idx), idx.size, t, y, residual=y)
     check_map(host(y), want, cache.astype(np.float64), active_mask(idx, t, H, W), TOL["bf16"], "in-place residual")
+
+
+@pytest.mark.parametrize("seed,frac", [(31, 0.02), (32, 0.10), (33, 0.45)])
+def test_apsc_selected_blocks_end_to_end(fb, seed, frac):
+    """Adaptive block size: block counts on the device, argmin on the host, index list for the chosen h x w blocks,
+    convolution on them.  Every stage bit-exact (integers) or within tolerance (conv) of the oracle taking the same steps."""
+    rng = np.random.default_rng(seed)
+    B, H, W, C, Co, dt = 2, 32, 64, 64, 64, "bf16"
+    pix = wl.ellipse_pixels(rng, H, W, frac)
+    counts = torch.zeros(25, dtype=torch.int32, device=DEV)
+    pixd = torch.from_numpy(pix.astype(np.uint8)).to(DEV)
+    fb.fise_apsc_block_counts(pixd, counts)
+    h, w_, cost = fb.fise_apsc_select(counts.cpu().tolist())
+    assert (h, w_, cost) == fo.apsc_block_size(pix)
+    nblk = (H // h) * (W // w_)
+    tm = torch.zeros(nblk, dtype=torch.uint8, device=DEV); idx = torch.full((nblk,), -1, dtype=torch.int32, device=DEV)
+    n = torch.zeros(1, dtype=torch.int32, device=DEV)
+    fb.fise_mask_from_pixels_rect(pixd, h, w_, tm, idx, n)
+    tm_o, idx_o = fo.tiles_from_pixels(pix, (h, w_))
+    na = int(n.item())
+    assert na == idx_o.size and np.array_equal(idx.cpu().numpy()[:na], idx_o) and np.array_equal(tm.cpu().numpy(), tm_o.reshape(-1))
+    x = wl.normal(rng, (B, H, W, C), 1.0, dt); wt = wl.normal(rng, (Co, 3, 3, C), 1 / 24, dt); bias = wl.normal(rng, (Co,), 0.1, dt)
+    cache = wl.normal(rng, (B, H, W, Co), 1.0, dt)
+    want = cache.astype(np.float64).copy()
+    fo.masked_conv(x, wt, bias, idx_o, (h, w_), want, dt)
+    y = dev(cache, dt)
+    a = fb.conv_args(dev(x, dt), dev(wt, dt), dev(bias, dt), idx, na, h, y, tile_w=w_)
+    ws = torch.zeros(fb.fise_masked_conv_workspace_bytes(a), dtype=torch.uint8, device=DEV)
+    fb.fise_masked_conv(a, ws)
+    act = active_mask(idx_o, (h, w_), H, W)
+    assert act[pix.astype(bool)].all()                                   # the chosen blocks cover every masked pixel
+    check_map(host(y), want, cache.astype(np.float64), act, TOL[dt], f"apsc {h}x{w_}")
