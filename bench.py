@@ -73,6 +73,9 @@ def main():
                     help="log per-module masked times by block kind, level and blob size, with the dense time (stderr)")
     ap.add_argument("--density-sweep", action="store_true",
                     help="log masked step time for blobs of 1/5/10/25/50 %% of the latent (stderr), then the normal run")
+    ap.add_argument("--host-spill", action="store_true",
+                    help="also time the masked step with the per-step caches in pinned host memory, streamed through three "
+                         "device slots on two copy streams (reported beside the resident figure, never as `value`)")
     ap.add_argument("--apsc-sweep", action="store_true",
                     help="log the time of one masked 3x3 convolution (C=320, level-0 map) for every candidate block size of the "
                          "adaptive block-size selection, with the selection's own pick (stderr)")
@@ -241,6 +244,39 @@ def main():
             step(i, ntiles, full)
         ms_dense = timed(max(3, min(args.steps, 10)), ntiles, full)
 
+    # ---- the same step with the caches spilled to pinned host memory (PCIe in the loop; context, not `value`)
+    spill = None
+    if args.host_spill:
+        from paper_2305_17423_amd.cache_ring import CacheRing
+        nsp = min(max(ncache, 4), 16)
+        t0 = time.time()
+        ring = CacheRing(nsp, cbytes, dev, host_spill=True, slots=3)
+        for i in range(nsp):
+            ring.store(i, caches[i % ncache])
+        log(f"[bench] host spill: {nsp} caches of {cbytes / 1e6:.0f} MB in pinned memory, set up in {time.time() - t0:.1f} s")
+
+        def spill_steps(n, write_back):
+            for i in range(n):
+                c = ring.acquire(i)
+                fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)
+                fb.fise_masked_unet_step(u, Wd, c, lat_new, t_sin_all[i % T], kv_new, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
+                ring.release(i, write_back=write_back)
+
+        def spill_ms(write_back):
+            spill_steps(nsp, write_back)
+            torch.cuda.synchronize()
+            t1 = time.time()
+            spill_steps(args.steps, write_back)
+            torch.cuda.synchronize()
+            return (time.time() - t1) * 1e3 / args.steps
+        ms_spill, ms_in_only = spill_ms(True), spill_ms(False)
+        spill = {"ms_per_step": ms_spill, "ms_per_step_copy_in_only": ms_in_only, "caches": nsp, "slots": 3,
+                 "bytes_each_way_per_step": cbytes, "link_gbs_each_way": cbytes / ms_spill / 1e6,
+                 "link_gbs_copy_in_only": cbytes / ms_in_only / 1e6}
+        log(f"[bench] host spill: {ms_spill:.3f} ms per step with write-back ({cbytes / ms_spill / 1e6:.1f} GB/s in and out at once), "
+            f"{ms_in_only:.3f} ms copy-in only ({cbytes / ms_in_only / 1e6:.1f} GB/s), vs {ms_masked:.3f} ms resident")
+        del ring
+
     # ---- per-kernel accounting with HIP events on the launch stream (separate passes: the events
     # widen the gaps between kernels, so these passes are not the timed ones)
     def profile(n, n_active, index):
@@ -308,6 +344,8 @@ def main():
         "weight_stream_floor_ms": nW * 2 / (HBM_PEAK_GBS * 1e6),
         "kernels": kinds, "roofline": roofline,
     }
+    if spill:
+        res["host_spill"] = spill
 
     # ---- the oracle, as it stands, on the host cores: one masked step of the same workload
     if not args.no_cpu_baseline:
