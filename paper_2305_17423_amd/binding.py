@@ -319,14 +319,15 @@ def fise_masked_attention(x, ln_gamma, ln_beta, Wq, Wk, Wv, Wo, bo, heads, K_cac
 # --------------------------------------------------------------------------- modules
 def fill_args(struct_type, keep, **kw):
     """A ctypes argument struct from keyword values; tensors become addresses and are appended
-    to `keep` so they outlive the (asynchronous) call."""
+    to `keep` so they outlive the (asynchronous) call.  An int in a pointer field is taken as an
+    address read from another argument struct."""
     a = struct_type()
     types = dict(struct_type._fields_)
     for k, v in kw.items():
         if types[k] is vp:
             if hasattr(v, "data_ptr"):
                 keep.append(v)
-            setattr(a, k, _p(v))
+            setattr(a, k, v if isinstance(v, int) else _p(v))
         else:
             setattr(a, k, int(v))
     return a

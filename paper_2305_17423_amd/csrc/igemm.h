@@ -38,7 +38,6 @@ struct IgemmArgs {
     int splits; float* partial;
     int gx, gy;                                         // tile grid (row tiles, column tiles); set by the launcher
     int need_pix;                                       // set by the launcher: the epilogue addresses a map (else rows only)
-    long long* dbg;                                     // development aid: per-workgroup phase timestamps (null = off)
 };
 
 // Scratch of the launcher: GroupNorm (scale, shift) table and the parked partial sums of split-K launches.

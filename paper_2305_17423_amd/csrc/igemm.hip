@@ -20,16 +20,10 @@
 #include "igemm.h"
 #include "profile.h"
 
-#ifndef FISE_PF
-#define FISE_PF 2
-#endif
-#ifndef FISE_NST
-#define FISE_NST 3
-#endif
-
 namespace fise {
 
-constexpr int PF = FISE_PF;             // prefetch distance in K steps
+constexpr int PF = 2;                   // prefetch distance in K steps (register-staged kernel)
+constexpr int NST_RING = 3;             // LDS ring stages of the LDS-direct kernel (2 and 4 measured slower)
 
 struct RowInfo { int b, y, x, ok; };
 
@@ -224,13 +218,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
         bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
     }
-#ifdef FISE_DEBUG_STAMPS      // development aid: wall-clock stamps of the workgroup's phases
-    long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
-#define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
-#else
-#define FISE_STAMP(i) do { } while (0)
-#endif
-    FISE_STAMP(0);
     const int m0 = bx * BM;
     const int Cin = a.C0 + a.C1;
     const int pad = a.ksize >> 1;
@@ -269,7 +256,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         }
     }
     __syncthreads();
-    FISE_STAMP(1);
 
     // ---- per-thread load slots: TPR threads per tile row, RP rows per pass
     const int seg = tid % TPR;                         // which 8-element segment of the K step
@@ -411,7 +397,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
     // fill the FIFO
 #pragma unroll
     for (int s = 0; s < PF; ++s) issue(s);
-    FISE_STAMP(2);
 
     for (int kc0 = kc_begin; kc0 < kc_end; kc0 += PF) {
 #pragma unroll
@@ -420,7 +405,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
             if (kc >= kc_end) break;                   // uniform across the workgroup
             const int buf = s & 1;                     // PF is even: the parity of kc - kc_begin
             stash(s, buf);
-            if (kc == kc_begin) FISE_STAMP(3);
             issue(s);
             lds_barrier();
 #pragma unroll
@@ -440,11 +424,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
             }
         }
     }
-    FISE_STAMP(4);
 
     finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
-    FISE_STAMP(5);
-#undef FISE_STAMP
 }
 
 
@@ -495,18 +476,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
     {
         const int total = a.gx * a.gy * a.splits, chunk = total >> 3;
         int w = blockIdx.x;
-#ifndef FISE_NO_XCD_REMAP
         if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
-#endif
         bx = w % a.gx; const int t = w / a.gx; by = t % a.gy; bz = t / a.gy;
     }
-#ifdef FISE_DEBUG_STAMPS      // development aid: wall-clock stamps of the workgroup's phases
-    long long* dbg = a.dbg ? a.dbg + 8 * blockIdx.x : nullptr;
-#define FISE_STAMP(i) do { if (dbg && tid == 0) dbg[i] = wall_clock64(); } while (0)
-#else
-#define FISE_STAMP(i) do { } while (0)
-#endif
-    FISE_STAMP(0);
     const int m0 = bx * BM;
     const int Cin = a.C0 + a.C1;
     const int pad = a.ksize >> 1;
@@ -520,7 +492,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
         kc_begin = bz * per; kc_end = min(nsteps_total, kc_begin + per);
     }
     __syncthreads();
-    FISE_STAMP(1);
 
     // ---- descriptors of the operand arrays
     const unsigned npix_in = a.a_compact ? (unsigned)rows : (unsigned)(a.B * a.Hin * a.Win);
@@ -668,7 +639,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
 
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s);         // NST - 1 steps in flight
-    FISE_STAMP(2);
 
     for (int kc0 = kc_begin; kc0 < kc_end; kc0 += NST) {
 #pragma unroll
@@ -678,7 +648,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
             // the younger ones remain, then meet the other waves (their rows of the stage have landed too,
             // and everybody is done reading the stage that is refilled next)
             wait_loads<(NST - 2) * (AL + BL)>();
-            if (kc0 + s == kc_begin) FISE_STAMP(3);
             const unsigned char* stage = ring + s * STAGE;
             // all operand fragments of the step are requested before the first MFMA: the LDS round trips
             // overlap each other and the matrix pipe instead of alternating with it
@@ -703,10 +672,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
         }
     }
     wait_loads<0>();                                    // the trailing out-of-range loads still target the ring
-    FISE_STAMP(4);
     finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
-    FISE_STAMP(5);
-#undef FISE_STAMP
 #endif
 }
 
@@ -850,10 +816,6 @@ int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hip
     return FISE_OK;
 }
 
-#ifdef FISE_DEBUG_STAMPS
-long long* g_igemm_dbg = nullptr;      // set through fise_debug_timing_buffer
-#endif
-
 // How many workgroups share the K loop of one output tile.  A CU pulls operands at a few tens of
 // GB/s whatever runs on it, so what matters most is that every CU streams part of the operands: aim
 // at roughly two workgroups per CU, keep at least two K steps per workgroup, and keep the parked
@@ -865,13 +827,7 @@ static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) 
     const int rows = a.B * a.Ma;
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
-#ifndef FISE_SPLIT_TARGET
-#define FISE_SPLIT_TARGET 480
-#endif
-#ifndef FISE_SPLIT_MIN_STEPS
-#define FISE_SPLIT_MIN_STEPS 4
-#endif
-    constexpr int target = FISE_SPLIT_TARGET, min_steps = FISE_SPLIT_MIN_STEPS;   // measured optimum is flat between 384 and 480 workgroups
+    constexpr int target = 480, min_steps = 4;          // measured optimum is flat between 384 and 480 workgroups
     if (tiles * 2 > target || nsteps < min_steps) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
@@ -888,9 +844,6 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     const int ncols = a.geglu ? 2 * a.N : a.N;
     a.splits = (a.N % 4 == 0 && a.sect_n % 4 == 0) ? pick_splits<BM, BN, BK>(a, ws, ncols) : 1;
     if (a.splits > 1) a.partial = ws->partial;
-#ifdef FISE_DEBUG_STAMPS
-    a.dbg = g_igemm_dbg;
-#endif
     a.gx = ceil_div(rows, BM); a.gy = ceil_div(ncols, BN);
     if (a.tile_w <= 0) a.tile_w = a.tile;
     a.need_pix = a.res && a.res_compact == 0;
@@ -927,7 +880,7 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     const bool dma = BK == 64 && a.pro == PRO_NONE && npix_in * std::max(a.C0, a.C1) * 2 < kLim &&
                      npix_out * std::max(a.S0, a.S1) * 2 < kLim && (size_t)ncols * std::max(a.K, a.K2) * 2 < kLim;
     if (dma) {
-        constexpr int NST = FISE_NST;
+        constexpr int NST = NST_RING;
         constexpr int ring = NST * (BM + BN) * 128;
         static bool raised = false;                     // once per instantiation
         if (!raised && ring > 48 * 1024) {
@@ -1005,8 +958,3 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
 
 }  // namespace fise
 
-#ifdef FISE_DEBUG_STAMPS
-// Development aid, not part of the documented ABI: a device buffer of 8 x int64 per workgroup that
-// the gathered-GEMM kernels fill with wall-clock stamps of their phases (null switches it off).
-extern "C" void fise_debug_timing_buffer(void* dev) { fise::g_igemm_dbg = (long long*)dev; }
-#endif
