@@ -126,6 +126,48 @@ def test_tiny_unet_step_vs_oracle(fb, seed):
     fb.fise_unet_destroy(u)
 
 
+ARCHS = [
+    ("two-levels-nonsquare", dict(base=64, mults=(1, 2), attn=(True, False), layers=1, heads=2, ctx_dim=64, n_ctx=7, H=16, W=24, B=1), 2),
+    ("three-levels-batch3", dict(base=32, mults=(1, 1, 2), attn=(False, True, True), layers=2, heads=4, ctx_dim=64, n_ctx=20, H=24, W=16, B=3), 4),
+    ("four-levels-8ch-latent", dict(in_ch=8, out_ch=8, base=32, mults=(1, 2, 2, 4), attn=(True, False, True, True), layers=1, heads=4,
+                                    ctx_dim=96, n_ctx=77, H=32, W=32, B=2), 8),
+]
+
+
+@pytest.mark.parametrize("name,over,bt", ARCHS, ids=[a[0] for a in ARCHS])
+def test_other_architectures_vs_oracle(fb, name, over, bt):
+    """The plan is parametric: other depths, widths, attention placements, head counts, context sizes, batch sizes
+    and non-square latents, dense forward and masked step against the oracle's walk of the same description."""
+    d = uo.sd15_desc(**over)
+    rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, 5100 + bt, 0.05)
+    H, W = d["H"], d["W"]
+    shapes = uo.cache_shapes(d)
+    kv_old = uo.context_kv_all(P, d, ctx_old, "bf16"); kv_new = uo.context_kv_all(P, d, ctx_new, "bf16")
+    _, cache_old = uo.unet_dense(P, d, lat, t_sin, kv_old, "bf16")
+    u = fb.fise_unet_create(d)
+    assert fb.fise_unet_module_names(u) == [m["name"] for m in uo.unet_modules(d)]
+    Wd = pack_weights(fb, u, P)
+    kvd_old = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=DEV); kvd_new = torch.zeros_like(kvd_old)
+    fb.fise_unet_context_kv(u, Wd, dev(ctx_old, "bf16"), kvd_old); fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd_new)
+    ntiles = (H // bt) * (W // bt)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, ntiles, bt), dtype=torch.uint8, device=DEV)
+    tsd = dev(t_sin)
+    full = fo.full_index(H, W, bt)
+    cd = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_masked_unet_step(u, Wd, cd, dev(lat, "bf16"), tsd, kvd_old, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
+    zero = {k: np.zeros_like(v) for k, v in cache_old.items()}
+    compare_caches(d, unpack_cache(fb, u, cd, shapes), cache_old, zero, full, bt, TOL["bf16"])
+    lat_new = wl.perturb(rng, lat, wl.rect_pixels(rng, H, W, 5, 7), 1.0, "bf16")
+    _, _, idx = fo.mask_detect(lat, lat_new, 0.1, bt)
+    assert 0 < idx.size < ntiles
+    want = {k: v.copy() for k, v in cache_old.items()}
+    uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16")
+    cm = pack_cache(fb, u, cache_old)
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
+    compare_caches(d, unpack_cache(fb, u, cm, shapes), want, cache_old, idx, bt, TOL["bf16"])
+    fb.fise_unet_destroy(u)
+
+
 def test_tiny_unet_full_mask_fresh_equals_dense_of_new_inputs(fb):
     d = uo.tiny_desc()
     rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, 5003, 0.08)
