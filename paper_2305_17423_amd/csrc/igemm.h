@@ -18,7 +18,6 @@ struct IgemmArgs {
     const int* tile_idx; int tile, tile_w, tiles_w, Ho, Wo, B, Ma;   // tiles of tile x tile_w pixels (tile_w 0: square)
     // ---- prologue on A: GroupNorm (+SiLU) with given statistics
     int pro; const float* gn_mean; const float* gn_rstd; const bf16_t* gn_gamma; const bf16_t* gn_beta; int G;
-    const float2* gn_table;                             // [B, Cin] (scale, shift), filled by the launcher when it has scratch
     // ---- B operand: weights [rows_w, K], K innermost
     const bf16_t* w; int N; int K;                      // N = output columns (GEGLU: N = D, weights have 2D rows)
     int geglu;
@@ -42,8 +41,7 @@ struct IgemmArgs {
 
 // Scratch of the launcher: GroupNorm (scale, shift) table and the parked partial sums of split-K launches.
 constexpr size_t IGEMM_PARTIAL_BYTES = 32u << 20;
-constexpr size_t IGEMM_GN_TABLE_BYTES = 256u << 10;
-struct IgemmWorkspace { float* partial; size_t partial_bytes; float2* gn_table; size_t gn_table_bytes; };
+struct IgemmWorkspace { float* partial; size_t partial_bytes; };
 size_t igemm_workspace_bytes();
 // Carves the scratch out of `workspace`; with a null or too
 // small workspace `out` is left empty and every launch runs unsplit.

@@ -243,15 +243,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         for (int e = tid * 2; e < (b_last - b_first + 1) * clen; e += 2 * NT) {   // two entries (16 bytes) per thread
             const int bb = b_first + e / clen;
             int c = c_lo + e % clen; if (c >= Cin) c -= Cin;
-            if (a.gn_table) {
-                *reinterpret_cast<float4*>(&gn_ss[e]) = *reinterpret_cast<const float4*>(&a.gn_table[(size_t)bb * Cin + c]);
-            } else {
+            // (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given
+            // statistics.  Worked out here by every workgroup for its own channels: a separate launch that
+            // tabulated them once cost more than it saved.
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const float rs = a.gn_rstd[bb * a.G + (c + q) / cpg], mu = a.gn_mean[bb * a.G + (c + q) / cpg];
-                    const float sc = rs * bf2f(a.gn_gamma[c + q]);
-                    gn_ss[e + q] = make_float2(sc, bf2f(a.gn_beta[c + q]) - mu * sc);
-                }
+            for (int q = 0; q < 2; ++q) {
+                const float rs = a.gn_rstd[bb * a.G + (c + q) / cpg], mu = a.gn_mean[bb * a.G + (c + q) / cpg];
+                const float sc = rs * bf2f(a.gn_gamma[c + q]);
+                gn_ss[e + q] = make_float2(sc, bf2f(a.gn_beta[c + q]) - mu * sc);
             }
         }
     }
@@ -790,28 +789,17 @@ __global__ __launch_bounds__(256) void igemm_reduce_ln_kernel(const IgemmArgs a)
     }
 }
 
-// (scale, shift) per (batch element, channel): u = x * scale + shift is GroupNorm with the given statistics
-__global__ void gn_table_kernel(const float* __restrict__ mean, const float* __restrict__ rstd, const bf16_t* __restrict__ gamma,
-                                const bf16_t* __restrict__ beta, int B, int Cin, int G, float2* __restrict__ out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B * Cin) return;
-    const int b = i / Cin, c = i % Cin, g = c / (Cin / G);
-    const float sc = rstd[b * G + g] * bf2f(gamma[c]);
-    out[i] = make_float2(sc, bf2f(beta[c]) - mean[b * G + g] * sc);
-}
-
 
 // ---------------------------------------------------------------------------
 // host side: tile shape and K split per problem
 // ---------------------------------------------------------------------------
-size_t igemm_workspace_bytes() { return IGEMM_GN_TABLE_BYTES + IGEMM_PARTIAL_BYTES; }
+size_t igemm_workspace_bytes() { return IGEMM_PARTIAL_BYTES; }
 
 int igemm_workspace_init(void* workspace, size_t bytes, IgemmWorkspace* out, hipStream_t st) {
     (void)st;
-    out->partial = nullptr; out->partial_bytes = 0; out->gn_table = nullptr; out->gn_table_bytes = 0;
+    out->partial = nullptr; out->partial_bytes = 0;
     if (!workspace || bytes < igemm_workspace_bytes()) return FISE_OK;          // no split-K without it
-    out->gn_table = (float2*)workspace; out->gn_table_bytes = IGEMM_GN_TABLE_BYTES;
-    out->partial = (float*)((char*)workspace + IGEMM_GN_TABLE_BYTES);
+    out->partial = (float*)workspace;
     out->partial_bytes = IGEMM_PARTIAL_BYTES;
     return FISE_OK;
 }
@@ -855,12 +843,6 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         const int Cin = a.C0 + a.C1;
         const int per = ceil_div((a.K + a.K2) / BK, a.splits);
         shmem = (size_t)span * std::min(Cin, per * BK) * sizeof(float2);
-        if (ws && ws->gn_table && (size_t)a.B * Cin * sizeof(float2) <= ws->gn_table_bytes) {
-            hipLaunchKernelGGL(gn_table_kernel, dim3(ceil_div(a.B * Cin, 256)), dim3(256), 0, st, a.gn_mean, a.gn_rstd, a.gn_gamma,
-                               a.gn_beta, a.B, Cin, a.G, ws->gn_table);
-            FISE_CHECK_LAUNCH("igemm gn table");
-            a.gn_table = ws->gn_table;
-        }
         constexpr size_t kMaxDyn = 64 * 1024;
         if (shmem > kMaxDyn) return fail(FISE_ERR_SHAPE, "igemm: GroupNorm table of %zu bytes does not fit in LDS", shmem);
         static bool raised = false;                 // once per instantiation: static tiles + table may exceed 64 KB
