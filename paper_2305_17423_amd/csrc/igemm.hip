@@ -51,15 +51,48 @@ __device__ __forceinline__ float epilogue_terms(const IgemmArgs& a, int gm, int 
     return v;
 }
 
+// Position of an output row on its map, worked out once per row: pix = (b * Ho + y) * Wo + x, yx = y * Wo + x.
+// 24-bit multiplies are exact here (coordinates and map edges are far below 2^24) and run at full rate.
+struct OutPos { int b; unsigned pix, yx; };
+__device__ __forceinline__ OutPos out_pos(const IgemmArgs& a, int b, int y, int x) {
+    OutPos p;
+    p.b = b;
+    p.yx = __umul24((unsigned)y, (unsigned)a.Wo) + (unsigned)x;
+    p.pix = (unsigned)b * (unsigned)(a.Ho * a.Wo) + p.yx;
+    return p;
+}
+
+// Time projection and residual for columns col .. col + 3 of output row gm (col % 4 == 0, N % 4 == 0).
+__device__ __forceinline__ void epilogue_terms4(const IgemmArgs& a, int gm, const OutPos& p, int col, float (&t)[4]) {
+    t[0] = t[1] = t[2] = t[3] = 0.f;
+    if (a.temb) {
+        const float* e = a.temb + (size_t)p.b * a.temb_stride + col;
+        t[0] = e[0]; t[1] = e[1]; t[2] = e[2]; t[3] = e[3];
+    }
+    if (a.res) {
+        if (a.res_compact == 2) {
+            const float4 r = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col);
+            t[0] += r.x; t[1] += r.y; t[2] += r.z; t[3] += r.w;
+        } else {
+            const size_t row = a.res_compact ? (size_t)gm : (size_t)p.pix;
+            const uint2 r = *reinterpret_cast<const uint2*>(a.res + row * a.N + col);
+            t[0] += __uint_as_float(r.x << 16); t[1] += __uint_as_float(r.x & 0xffff0000u);
+            t[2] += __uint_as_float(r.y << 16); t[3] += __uint_as_float(r.y & 0xffff0000u);
+        }
+    }
+}
+
 // Four consecutive columns col .. col + 3 of one section (col % 4 == 0, section widths are multiples of 4).
-__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, int b, int y, int x, int col, const float (&v)[4]) {
-    const int sect = col / a.sect_n, scol = col % a.sect_n;
-    bf16_t* outp = a.out[sect];
-    const int omode = a.out_mode[sect];
+__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, const OutPos& p, int col, const float (&v)[4]) {
+    // at most three sections: two compares instead of a division
+    const int sect = (col >= a.sect_n) + (col >= 2 * a.sect_n), scol = col - sect * a.sect_n;
+    bf16_t* const outp = sect == 0 ? a.out[0] : (sect == 1 ? a.out[1] : a.out[2]);
+    const int omode = sect == 0 ? a.out_mode[0] : (sect == 1 ? a.out_mode[1] : a.out_mode[2]);
     if (omode == OUT_TOKENS_T) {
+        bf16_t* o = outp + ((size_t)p.b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + p.yx;
+        const size_t HW = (size_t)a.Ho * a.Wo;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            outp[((size_t)b * a.sect_n + scol + q) * ((size_t)a.Ho * a.Wo) + (size_t)y * a.Wo + x] = f2bf(v[q]);
+        for (int q = 0; q < 4; ++q) o[q * HW] = f2bf(v[q]);
         return;
     }
     const uint2 packed = make_uint2(f2bf2(v[0], v[1]), f2bf2(v[2], v[3]));
@@ -69,7 +102,7 @@ __device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, int b,
     } else if (omode == OUT_COMPACT) {
         *reinterpret_cast<uint2*>(outp + (size_t)gm * a.sect_n + scol) = packed;
     } else {
-        *reinterpret_cast<uint2*>(outp + (((size_t)b * a.Ho + y) * a.Wo + x) * a.sect_n + scol) = packed;
+        *reinterpret_cast<uint2*>(outp + (size_t)p.pix * a.sect_n + scol) = packed;
     }
 }
 
@@ -109,7 +142,7 @@ __device__ __forceinline__ int weight_row(const IgemmArgs& a, int by, int col) {
 // bias, GEGLU gate, time projection, residual, store.
 template <int BM, int BN, int WGM, int WGN>
 __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32], const RowInfo* rinfo,
-                                            int m0, int by, int bz, int rows, int lane, int wave) {
+                                            int m0, int by, int bz, int rows, int lane, int wave, float* stage = nullptr) {
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     if (a.splits > 1) {
@@ -130,6 +163,71 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         return;
     }
     constexpr int n_out_blocks = TN >= 2 ? TN / 2 : 1;    // GEGLU pairs block j (value) with block j + TN/2 (gate)
+    if (stage && (a.N & 3) == 0 && (a.sect_n & 3) == 0) {
+        // The finished tile goes through LDS (`stage`: free once every wave has left the K loop) so that the stores
+        // are row-contiguous: a thread then owns four consecutive columns of one row, works out that row's
+        // destination once and moves 8 or 16 bytes per access, where the accumulator layout would give it one
+        // element of sixteen different rows.
+        constexpr int NT = 64 * WGM * WGN;
+        const int tid = wave * 64 + lane;
+        const int OW = a.geglu ? BN / 2 : BN;             // output columns of the tile
+        const int pitch = OW + 4;
+        __syncthreads();                                   // all waves are done reading the operand ring
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (a.geglu && j >= n_out_blocks) break;
+            int col, c;                                    // global column, column within the tile
+            if (a.geglu) { c = (wave % WGN) * (WN / 2) + j * 32 + (lane & 31); col = by * (BN / 2) + c; }
+            else { c = wn0 + j * 32 + (lane & 31); col = by * BN + c; }
+            float bias_v = 0.f, bias_g = 0.f;
+            if (col < a.N) {
+                if (a.bias) bias_v = bf2f(a.bias[col]);
+                if (a.bias2) bias_v += bf2f(a.bias2[col]);
+                if (a.geglu && a.bias) bias_g = bf2f(a.bias[col + a.N]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int r = wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    float v = acc[i][j][e] + bias_v;
+                    if (a.geglu) {
+                        const float g = acc[i][(j + TN / 2) % TN][e] + bias_g;
+                        v = v * (0.5f * g * (1.0f + erff(g * 0.70710678118654752f)));
+                    }
+                    stage[r * pitch + c] = v;
+                }
+        }
+        __syncthreads();
+        const int cshift = a.geglu ? __builtin_ctz(BN / 8) : __builtin_ctz(BN / 4);   // log2 of the four-column chunks per row
+        constexpr int MAXI = (BM * BN / 4 + NT - 1) / NT;
+        float t[MAXI][4];
+        // first every load (time projection, residual: the output may alias the residual), then every store
+#pragma unroll
+        for (int it = 0; it < MAXI; ++it) {
+            const int item = tid + it * NT;
+            const int r = item >> cshift, c = (item - (r << cshift)) * 4;
+            const int col = by * OW + c;
+            t[it][0] = t[it][1] = t[it][2] = t[it][3] = 0.f;
+            if (r < BM && col < a.N) {
+                const RowInfo ri = rinfo[r];
+                if (ri.ok) epilogue_terms4(a, m0 + r, out_pos(a, ri.b, ri.y, ri.x), col, t[it]);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < MAXI; ++it) {
+            const int item = tid + it * NT;
+            const int r = item >> cshift, c = (item - (r << cshift)) * 4;
+            const int col = by * OW + c;
+            if (r >= BM || col >= a.N) continue;
+            const RowInfo ri = rinfo[r];
+            if (!ri.ok) continue;
+            const float4 sv = *reinterpret_cast<const float4*>(&stage[r * pitch + c]);
+            const float v[4] = {sv.x + t[it][0], sv.y + t[it][1], sv.z + t[it][2], sv.w + t[it][3]};
+            epilogue_put4(a, m0 + r, out_pos(a, ri.b, ri.y, ri.x), col, v);
+        }
+        return;
+    }
     const size_t HW = (size_t)a.Ho * a.Wo;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -424,7 +522,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
         }
     }
 
-    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
+    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave, nullptr);
 }
 
 
@@ -456,6 +554,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
                  "s"(a.ups), "s"(a.tile_idx), "s"(a.tile), "s"(a.tile_w), "s"(a.tiles_w), "s"(a.Ho), "s"(a.Wo));
     asm volatile("" ::"s"(a.B), "s"(a.Ma), "s"(a.w), "s"(a.N), "s"(a.K), "s"(a.geglu), "s"(a.s0), "s"(a.s1), "s"(a.S0), "s"(a.S1),
                  "s"(a.w2), "s"(a.K2), "s"(a.splits), "s"(a.partial), "s"(a.gx), "s"(a.gy));
+    // ... and what the epilogue needs: fetched there, each group of fields was another exposed round trip
+    asm volatile("" ::"s"(a.bias), "s"(a.bias2), "s"(a.temb), "s"(a.temb_stride), "s"(a.res), "s"(a.res_compact), "s"(a.sect_n),
+                 "s"(a.out[0]), "s"(a.out[1]), "s"(a.out[2]), "s"(a.out_mode[0]), "s"(a.out_mode[1]), "s"(a.out_mode[2]),
+                 "s"(a.mirror), "s"(a.need_pix));
     constexpr int NW = WGM * WGN, NT = 64 * NW;
     constexpr int RB = 8 * NW;                          // tile rows filled by one load slot of the workgroup
     static_assert(BM % RB == 0 && BN % RB == 0, "tile rows must split evenly over the waves");
@@ -671,7 +773,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
         }
     }
     wait_loads<0>();                                    // the trailing out-of-range loads still target the ring
-    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave);
+    finish_tile<BM, BN, WGM, WGN>(a, acc, rinfo, m0, by, bz, rows, lane, wave, reinterpret_cast<float*>(ring));
 #endif
 }
 
@@ -697,9 +799,9 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
         t[q] = (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
         tg[q] = (GEGLU && a.bias) ? bf2f(a.bias[col + q + a.N]) : 0.f;
     }
+    const OutPos pos = out_pos(a, b, y, x);
     float post[4];                                       // added after the gate
-#pragma unroll
-    for (int q = 0; q < 4; ++q) post[q] = epilogue_terms(a, gm, b, y, x, col + q);
+    epilogue_terms4(a, gm, pos, col, post);
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
 #pragma unroll 4
     for (int z = 0; z < a.splits; ++z) {                  // split order: deterministic; four splits in flight
@@ -715,7 +817,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) r[q] += post[q];
-    epilogue_put4(a, gm, b, y, x, col, r);
+    epilogue_put4(a, gm, pos, col, r);
 }
 
 // Split-K reduce fused with the LayerNorm that follows a residual-stream GEMM: LPR lanes share a row of
