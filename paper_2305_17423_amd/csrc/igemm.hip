@@ -82,27 +82,51 @@ __device__ __forceinline__ void epilogue_terms4(const IgemmArgs& a, int gm, cons
     }
 }
 
+// The destinations of the (up to three) column sections.  Indexing a.out[] / a.out_mode[] with a per-lane section
+// number makes the compiler build a table: either it selects the ADDRESS inside the kernel-argument block and fetches
+// pointer and mode with a vector load (an exposed round trip in front of every store), or it parks the table in LDS,
+// which drags in a read of the dispatch packet in host memory for the workgroup size.  So the choice is made with
+// arithmetic on the values: base + (col >= n ? d1 : 0) + (col >= 2n ? d2 : 0).
+template <typename T>
+__device__ __forceinline__ __attribute__((address_space(1))) T* as_global(T* p) {   // a pointer rebuilt from integers has
+    return (__attribute__((address_space(1))) T*)p;                                  // to be told it is global again
+}
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));       // plain vectors: the HIP vector classes cannot be
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));         // assigned through an address-space pointer
+struct OutSel { unsigned long long base, d1, d2; int mode0, m1, m2; int sect_n; };
+__device__ __forceinline__ OutSel out_sel(const IgemmArgs& a) {
+    OutSel o;
+    const unsigned long long p0 = reinterpret_cast<unsigned long long>(a.out[0]), p1 = reinterpret_cast<unsigned long long>(a.out[1]),
+                             p2 = reinterpret_cast<unsigned long long>(a.out[2]);
+    o.base = p0; o.d1 = p1 - p0; o.d2 = p2 - p1;
+    o.mode0 = a.out_mode[0]; o.m1 = a.out_mode[1] - a.out_mode[0]; o.m2 = a.out_mode[2] - a.out_mode[1];
+    o.sect_n = a.sect_n;
+    return o;
+}
+
 // Four consecutive columns col .. col + 3 of one section (col % 4 == 0, section widths are multiples of 4).
-__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, int gm, const OutPos& p, int col, const float (&v)[4]) {
+__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& o, int gm, const OutPos& p, int col, const float (&v)[4]) {
     // at most three sections: two compares instead of a division
-    const int sect = (col >= a.sect_n) + (col >= 2 * a.sect_n), scol = col - sect * a.sect_n;
-    bf16_t* const outp = sect == 0 ? a.out[0] : (sect == 1 ? a.out[1] : a.out[2]);
-    const int omode = sect == 0 ? a.out_mode[0] : (sect == 1 ? a.out_mode[1] : a.out_mode[2]);
+    const bool s1 = col >= o.sect_n, s2 = col >= 2 * o.sect_n;
+    const int scol = col - ((int)s1 + (int)s2) * o.sect_n;
+    bf16_t* const outp = reinterpret_cast<bf16_t*>(o.base + (s1 ? o.d1 : 0ull) + (s2 ? o.d2 : 0ull));
+    const int omode = o.mode0 + (s1 ? o.m1 : 0) + (s2 ? o.m2 : 0);
     if (omode == OUT_TOKENS_T) {
-        bf16_t* o = outp + ((size_t)p.b * a.sect_n + scol) * ((size_t)a.Ho * a.Wo) + p.yx;
         const size_t HW = (size_t)a.Ho * a.Wo;
+        auto q0 = as_global(outp + ((size_t)p.b * o.sect_n + scol) * HW + p.yx);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) o[q * HW] = f2bf(v[q]);
+        for (int q = 0; q < 4; ++q) q0[q * HW] = f2bf(v[q]);
         return;
     }
-    const uint2 packed = make_uint2(f2bf2(v[0], v[1]), f2bf2(v[2], v[3]));
+    const u32x2_t packed = {f2bf2(v[0], v[1]), f2bf2(v[2], v[3])};
     if (omode == OUT_COMPACT_F32) {
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(outp) + (size_t)gm * a.sect_n + scol) = make_float4(v[0], v[1], v[2], v[3]);
-        if (a.mirror) *reinterpret_cast<uint2*>(a.mirror + (size_t)gm * a.sect_n + scol) = packed;
+        const f32x4v_t full = {v[0], v[1], v[2], v[3]};
+        *as_global(reinterpret_cast<f32x4v_t*>(reinterpret_cast<float*>(outp) + (size_t)gm * o.sect_n + scol)) = full;
+        if (a.mirror) *reinterpret_cast<u32x2_t*>(a.mirror + (size_t)gm * o.sect_n + scol) = packed;
     } else if (omode == OUT_COMPACT) {
-        *reinterpret_cast<uint2*>(outp + (size_t)gm * a.sect_n + scol) = packed;
+        *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)gm * o.sect_n + scol)) = packed;
     } else {
-        *reinterpret_cast<uint2*>(outp + (size_t)p.pix * a.sect_n + scol) = packed;
+        *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)p.pix * o.sect_n + scol)) = packed;
     }
 }
 
@@ -201,30 +225,39 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         __syncthreads();
         const int cshift = a.geglu ? __builtin_ctz(BN / 8) : __builtin_ctz(BN / 4);   // log2 of the four-column chunks per row
         constexpr int MAXI = (BM * BN / 4 + NT - 1) / NT;
-        float t[MAXI][4];
-        // first every load (time projection, residual: the output may alias the residual), then every store
+        // Every LDS read of the pass is issued before anything branches on its result (rows and columns past the
+        // tile are clamped for the read and masked at the store): the round trips overlap instead of queueing
+        // behind one another.  Then every global load (the output may alias the residual), then every store.
+        const OutSel osel = out_sel(a);
+        RowInfo ri[MAXI]; float4 sv[MAXI]; int colv[MAXI], rowv[MAXI];
 #pragma unroll
         for (int it = 0; it < MAXI; ++it) {
             const int item = tid + it * NT;
             const int r = item >> cshift, c = (item - (r << cshift)) * 4;
-            const int col = by * OW + c;
-            t[it][0] = t[it][1] = t[it][2] = t[it][3] = 0.f;
-            if (r < BM && col < a.N) {
-                const RowInfo ri = rinfo[r];
-                if (ri.ok) epilogue_terms4(a, m0 + r, out_pos(a, ri.b, ri.y, ri.x), col, t[it]);
-            }
+            rowv[it] = r; colv[it] = by * OW + c;
+            const int rc = min(r, BM - 1);
+            ri[it] = rinfo[rc];
+            sv[it] = *reinterpret_cast<const float4*>(&stage[rc * pitch + c]);
+        }
+        OutPos pos[MAXI]; bool ok[MAXI];
+#pragma unroll
+        for (int it = 0; it < MAXI; ++it) {
+            ok[it] = rowv[it] < BM && colv[it] < a.N && ri[it].ok;
+            pos[it] = out_pos(a, ri[it].b, ri[it].y, ri[it].x);
+        }
+        float t[MAXI][4];
+#pragma unroll
+        for (int it = 0; it < MAXI; ++it) t[it][0] = t[it][1] = t[it][2] = t[it][3] = 0.f;
+        if (a.temb || a.res) {
+#pragma unroll
+            for (int it = 0; it < MAXI; ++it)
+                if (ok[it]) epilogue_terms4(a, m0 + rowv[it], pos[it], colv[it], t[it]);
         }
 #pragma unroll
         for (int it = 0; it < MAXI; ++it) {
-            const int item = tid + it * NT;
-            const int r = item >> cshift, c = (item - (r << cshift)) * 4;
-            const int col = by * OW + c;
-            if (r >= BM || col >= a.N) continue;
-            const RowInfo ri = rinfo[r];
-            if (!ri.ok) continue;
-            const float4 sv = *reinterpret_cast<const float4*>(&stage[r * pitch + c]);
-            const float v[4] = {sv.x + t[it][0], sv.y + t[it][1], sv.z + t[it][2], sv.w + t[it][3]};
-            epilogue_put4(a, m0 + r, out_pos(a, ri.b, ri.y, ri.x), col, v);
+            if (!ok[it]) continue;
+            const float v[4] = {sv[it].x + t[it][0], sv[it].y + t[it][1], sv[it].z + t[it][2], sv[it].w + t[it][3]};
+            epilogue_put4(a, osel, m0 + rowv[it], pos[it], colv[it], v);
         }
         return;
     }
@@ -783,6 +816,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmAr
 // residual, then the partials (16 bytes per split, twice that with the GEGLU gate, four splits in flight).
 template <bool GEGLU>
 __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
+    // one batch of kernel-argument loads instead of a dependent round trip per group of fields (see igemm_dma_kernel)
+    asm volatile("" ::"s"(a.B), "s"(a.Ma), "s"(a.N), "s"(a.partial), "s"(a.splits), "s"(a.bias), "s"(a.bias2), "s"(a.temb),
+                 "s"(a.temb_stride), "s"(a.tile_idx), "s"(a.need_pix), "s"(a.tile), "s"(a.tile_w), "s"(a.tiles_w), "s"(a.res),
+                 "s"(a.res_compact));
+    asm volatile("" ::"s"(a.Ho), "s"(a.Wo), "s"(a.out[0]), "s"(a.out[1]), "s"(a.out[2]), "s"(a.out_mode[0]), "s"(a.out_mode[1]),
+                 "s"(a.out_mode[2]), "s"(a.sect_n), "s"(a.mirror));
     const int rows = a.B * a.Ma;
     const int gm = blockIdx.y * 4 + (threadIdx.x >> 6);  // 4 rows per workgroup; 64 threads x 4 columns per row and block
     const int col = (blockIdx.x * 64 + (threadIdx.x & 63)) * 4;
@@ -790,18 +829,26 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     const int ncols = GEGLU ? 2 * a.N : a.N;
     const size_t stride = (size_t)rows * ncols;
     const float* P = a.partial + (size_t)gm * ncols + col;
-    int y = 0, x = gm % a.Ma;
-    const int b = gm / a.Ma;
-    if (a.tile_idx && a.need_pix) active_pixel(a.tile_idx, gm % a.Ma, a.tile, a.tile_w, a.tiles_w, y, x);
-    float t[4], tg[4];                                   // terms added to the value / gate sums
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        t[q] = (a.bias ? bf2f(a.bias[col + q]) : 0.f) + (a.bias2 ? bf2f(a.bias2[col + q]) : 0.f);
-        tg[q] = (GEGLU && a.bias) ? bf2f(a.bias[col + q + a.N]) : 0.f;
+    const int b = gm / a.Ma, m = gm - b * a.Ma;
+    const OutSel osel = out_sel(a);
+    // Every load that does not depend on another is requested before anything is used: biases, the time
+    // projection, the tile id of this row and a compact residual go out together with the first partials.
+    // (Used where they are loaded, each would be a round trip of its own in front of the sum.)
+    uint2 bias_raw = make_uint2(0u, 0u), bias2_raw = bias_raw, gate_raw = bias_raw, res_raw = bias_raw;
+    float4 temb_v = make_float4(0.f, 0.f, 0.f, 0.f), res_v = temb_v;
+    if (a.bias) bias_raw = *reinterpret_cast<const uint2*>(a.bias + col);
+    if (a.bias2) bias2_raw = *reinterpret_cast<const uint2*>(a.bias2 + col);
+    if (GEGLU && a.bias) gate_raw = *reinterpret_cast<const uint2*>(a.bias + col + a.N);
+    if (a.temb) {
+        const float* e = a.temb + (size_t)b * a.temb_stride + col;
+        temb_v = make_float4(e[0], e[1], e[2], e[3]);
     }
-    const OutPos pos = out_pos(a, b, y, x);
-    float post[4];                                       // added after the gate
-    epilogue_terms4(a, gm, pos, col, post);
+    const bool pix = a.tile_idx && a.need_pix;
+    const int tt = a.tile * a.tile_w;
+    int tile_id = 0;
+    if (pix) tile_id = a.tile_idx[m / tt];
+    if (a.res && a.res_compact == 2) res_v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col);
+    else if (a.res && a.res_compact) res_raw = *reinterpret_cast<const uint2*>(a.res + (size_t)gm * a.N + col);
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
 #pragma unroll 4
     for (int z = 0; z < a.splits; ++z) {                  // split order: deterministic; four splits in flight
@@ -809,15 +856,30 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
         v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
         if (GEGLU) { const float4 q = *reinterpret_cast<const float4*>(P + z * stride + a.N); g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w; }
     }
-    float r[4] = {v.x + t[0], v.y + t[1], v.z + t[2], v.w + t[3]};
+    // position of the row on the map (needs the tile id), then the one load that depends on it
+    int y = 0, x = m;
+    if (pix) {
+        const int p = m % tt;
+        y = (tile_id / a.tiles_w) * a.tile + p / a.tile_w;
+        x = (tile_id % a.tiles_w) * a.tile_w + p % a.tile_w;
+    }
+    const OutPos pos = out_pos(a, b, y, x);
+    if (a.res && a.res_compact == 0) res_raw = *reinterpret_cast<const uint2*>(a.res + (size_t)pos.pix * a.N + col);
+    auto lo = [](unsigned w) { return __uint_as_float(w << 16); };
+    auto hi = [](unsigned w) { return __uint_as_float(w & 0xffff0000u); };
+    // same order of additions as the unsplit epilogue: sum, biases, (gate), time projection, residual
+    float r[4] = {v.x + (lo(bias_raw.x) + lo(bias2_raw.x)), v.y + (hi(bias_raw.x) + hi(bias2_raw.x)),
+                  v.z + (lo(bias_raw.y) + lo(bias2_raw.y)), v.w + (hi(bias_raw.y) + hi(bias2_raw.y))};
     if (GEGLU) {
-        const float gg[4] = {g.x + tg[0], g.y + tg[1], g.z + tg[2], g.w + tg[3]};
+        const float gg[4] = {g.x + lo(gate_raw.x), g.y + hi(gate_raw.x), g.z + lo(gate_raw.y), g.w + hi(gate_raw.y)};
 #pragma unroll
         for (int q = 0; q < 4; ++q) r[q] = r[q] * (0.5f * gg[q] * (1.0f + erff(gg[q] * 0.70710678118654752f)));
     }
+    const float post[4] = {temb_v.x + (res_v.x + lo(res_raw.x)), temb_v.y + (res_v.y + hi(res_raw.x)),
+                           temb_v.z + (res_v.z + lo(res_raw.y)), temb_v.w + (res_v.w + hi(res_raw.y))};
 #pragma unroll
     for (int q = 0; q < 4; ++q) r[q] += post[q];
-    epilogue_put4(a, gm, pos, col, r);
+    epilogue_put4(a, osel, gm, pos, col, r);
 }
 
 // Split-K reduce fused with the LayerNorm that follows a residual-stream GEMM: LPR lanes share a row of
@@ -826,6 +888,8 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
 // residual stream), then normalise it in registers (two passes, fp32) and store the bf16 LayerNorm row.
 template <int LPR>
 __global__ __launch_bounds__(256) void igemm_reduce_ln_kernel(const IgemmArgs a) {
+    asm volatile("" ::"s"(a.B), "s"(a.Ma), "s"(a.partial), "s"(a.splits), "s"(a.bias), "s"(a.res), "s"(a.out[0]), "s"(a.mirror),
+                 "s"(a.ln_gamma), "s"(a.ln_beta), "s"(a.ln_eps), "s"(a.ln_out));    // one batch of argument loads
     constexpr int C = 20 * LPR, RPB = 256 / LPR;
     const int rows = a.B * a.Ma;
     const int row = blockIdx.x * RPB + threadIdx.x / LPR;
@@ -917,7 +981,10 @@ static int pick_splits(const IgemmArgs& a, const IgemmWorkspace* ws, int ncols) 
     const int rows = a.B * a.Ma;
     const int tiles = ceil_div(rows, BM) * ceil_div(ncols, BN);
     const int nsteps = (a.K + a.K2) / BK;
-    constexpr int target = 480, min_steps = 4;          // measured optimum is flat between 384 and 480 workgroups
+    constexpr int target = 480;                         // measured optimum is flat between 384 and 480 workgroups
+    // Below a dozen K steps the LDS-direct kernel finishes a tile faster alone (6 us + 0.33 us per step) than a
+    // split launch and its reduce launch do together; the register-staged kernel has a slower step and splits earlier.
+    const int min_steps = a.pro != PRO_NONE ? 4 : 12;
     if (tiles * 2 > target || nsteps < min_steps) return 1;
     const size_t out_bytes = (size_t)rows * ncols * sizeof(float);
     int s = (target + tiles - 1) / tiles;
