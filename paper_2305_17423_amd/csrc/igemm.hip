@@ -38,15 +38,24 @@ __device__ __forceinline__ void wait_loads() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// A pointer that went through an integer or an opaque register copy has lost the fact that it points to global
+// memory; accesses through it would become FLAT instructions (aperture check, both wait counters).  Every access of
+// the epilogues says so again.
+template <typename T>
+__device__ __forceinline__ __attribute__((address_space(1))) T* as_global(T* p) {   // a pointer rebuilt from integers has
+    return (__attribute__((address_space(1))) T*)p;                                  // to be told it is global again
+}
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));       // plain vectors: the HIP vector classes cannot be
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));         // assigned through an address-space pointer
 // Epilogue terms that depend on the output position: time projection and residual for output element
 // (row gm = (b, y, x), column col).
 __device__ __forceinline__ float epilogue_terms(const IgemmArgs& a, int gm, int b, int y, int x, int col) {
     float v = 0.f;
-    if (a.temb) v += a.temb[b * a.temb_stride + col];
+    if (a.temb) v += as_global(a.temb)[b * a.temb_stride + col];
     if (a.res) {
-        if (a.res_compact == 2) v += reinterpret_cast<const float*>(a.res)[(size_t)gm * a.N + col];
-        else if (a.res_compact) v += bf2f(a.res[(size_t)gm * a.N + col]);
-        else v += bf2f(a.res[(((size_t)b * a.Ho + y) * a.Wo + x) * a.N + col]);
+        if (a.res_compact == 2) v += as_global(reinterpret_cast<const float*>(a.res))[(size_t)gm * a.N + col];
+        else if (a.res_compact) v += bf2f(as_global(a.res)[(size_t)gm * a.N + col]);
+        else v += bf2f(as_global(a.res)[(((size_t)b * a.Ho + y) * a.Wo + x) * a.N + col]);
     }
     return v;
 }
@@ -66,18 +75,18 @@ __device__ __forceinline__ OutPos out_pos(const IgemmArgs& a, int b, int y, int 
 __device__ __forceinline__ void epilogue_terms4(const IgemmArgs& a, int gm, const OutPos& p, int col, float (&t)[4]) {
     t[0] = t[1] = t[2] = t[3] = 0.f;
     if (a.temb) {
-        const float* e = a.temb + (size_t)p.b * a.temb_stride + col;
+        auto e = as_global(a.temb + (size_t)p.b * a.temb_stride + col);
         t[0] = e[0]; t[1] = e[1]; t[2] = e[2]; t[3] = e[3];
     }
     if (a.res) {
         if (a.res_compact == 2) {
-            const float4 r = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col);
-            t[0] += r.x; t[1] += r.y; t[2] += r.z; t[3] += r.w;
+            const f32x4v_t r = *as_global(reinterpret_cast<const f32x4v_t*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col));
+            t[0] += r[0]; t[1] += r[1]; t[2] += r[2]; t[3] += r[3];
         } else {
             const size_t row = a.res_compact ? (size_t)gm : (size_t)p.pix;
-            const uint2 r = *reinterpret_cast<const uint2*>(a.res + row * a.N + col);
-            t[0] += __uint_as_float(r.x << 16); t[1] += __uint_as_float(r.x & 0xffff0000u);
-            t[2] += __uint_as_float(r.y << 16); t[3] += __uint_as_float(r.y & 0xffff0000u);
+            const u32x2_t r = *as_global(reinterpret_cast<const u32x2_t*>(a.res + row * a.N + col));
+            t[0] += __uint_as_float(r[0] << 16); t[1] += __uint_as_float(r[0] & 0xffff0000u);
+            t[2] += __uint_as_float(r[1] << 16); t[3] += __uint_as_float(r[1] & 0xffff0000u);
         }
     }
 }
@@ -87,12 +96,6 @@ __device__ __forceinline__ void epilogue_terms4(const IgemmArgs& a, int gm, cons
 // pointer and mode with a vector load (an exposed round trip in front of every store), or it parks the table in LDS,
 // which drags in a read of the dispatch packet in host memory for the workgroup size.  So the choice is made with
 // arithmetic on the values: base + (col >= n ? d1 : 0) + (col >= 2n ? d2 : 0).
-template <typename T>
-__device__ __forceinline__ __attribute__((address_space(1))) T* as_global(T* p) {   // a pointer rebuilt from integers has
-    return (__attribute__((address_space(1))) T*)p;                                  // to be told it is global again
-}
-typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));       // plain vectors: the HIP vector classes cannot be
-typedef float f32x4v_t __attribute__((ext_vector_type(4)));         // assigned through an address-space pointer
 struct OutSel { unsigned long long base, d1, d2; int mode0, m1, m2; int sect_n; };
 __device__ __forceinline__ OutSel out_sel(const IgemmArgs& a) {
     OutSel o;
@@ -122,7 +125,7 @@ __device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& 
     if (omode == OUT_COMPACT_F32) {
         const f32x4v_t full = {v[0], v[1], v[2], v[3]};
         *as_global(reinterpret_cast<f32x4v_t*>(reinterpret_cast<float*>(outp) + (size_t)gm * o.sect_n + scol)) = full;
-        if (a.mirror) *reinterpret_cast<u32x2_t*>(a.mirror + (size_t)gm * o.sect_n + scol) = packed;
+        if (a.mirror) *as_global(reinterpret_cast<u32x2_t*>(a.mirror + (size_t)gm * o.sect_n + scol)) = packed;
     } else if (omode == OUT_COMPACT) {
         *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)gm * o.sect_n + scol)) = packed;
     } else {
@@ -171,7 +174,7 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     if (a.splits > 1) {
         const int ncols = a.geglu ? 2 * a.N : a.N;
-        float* P = a.partial + (size_t)bz * rows * ncols;
+        auto P = as_global(a.partial + (size_t)bz * rows * ncols);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int wr = weight_row<BN, WN>(a, by, wn0 + j * 32 + (lane & 31));
@@ -195,7 +198,7 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         constexpr int NT = 64 * WGM * WGN;
         const int tid = wave * 64 + lane;
         const int OW = a.geglu ? BN / 2 : BN;             // output columns of the tile
-        const int pitch = OW + 4;
+        constexpr int pitch = BN + 4;                      // floats per staged row (GEGLU tiles use the first half)
         __syncthreads();                                   // all waves are done reading the operand ring
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -205,9 +208,9 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
             else { c = wn0 + j * 32 + (lane & 31); col = by * BN + c; }
             float bias_v = 0.f, bias_g = 0.f;
             if (col < a.N) {
-                if (a.bias) bias_v = bf2f(a.bias[col]);
-                if (a.bias2) bias_v += bf2f(a.bias2[col]);
-                if (a.geglu && a.bias) bias_g = bf2f(a.bias[col + a.N]);
+                if (a.bias) bias_v = bf2f(as_global(a.bias)[col]);
+                if (a.bias2) bias_v += bf2f(as_global(a.bias2)[col]);
+                if (a.geglu && a.bias) bias_g = bf2f(as_global(a.bias)[col + a.N]);
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -245,6 +248,19 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
             ok[it] = rowv[it] < BM && colv[it] < a.N && ri[it].ok;
             pos[it] = out_pos(a, ri[it].b, ri[it].y, ri[it].x);
         }
+        if (!a.temb && !a.res && osel.sect_n >= a.N && (osel.mode0 == OUT_MAP || osel.mode0 == OUT_COMPACT)) {
+            // the common plain case (one bf16 destination, nothing to add): one multiply-add, two packs, one store per item
+            const bool to_map = osel.mode0 == OUT_MAP;
+            auto dst = as_global(reinterpret_cast<u32x2_t*>(osel.base));
+#pragma unroll
+            for (int it = 0; it < MAXI; ++it) {
+                if (!ok[it]) continue;
+                const size_t row = to_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it]);
+                const u32x2_t packed = {f2bf2(sv[it].x, sv[it].y), f2bf2(sv[it].z, sv[it].w)};
+                dst[(row * a.N + colv[it]) >> 2] = packed;
+            }
+            return;
+        }
         float t[MAXI][4];
 #pragma unroll
         for (int it = 0; it < MAXI; ++it) t[it][0] = t[it][1] = t[it][2] = t[it][3] = 0.f;
@@ -270,12 +286,13 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
         else col = by * BN + wn0 + j * 32 + (lane & 31);
         if (col >= a.N) continue;
         // everything that depends on the column alone, once: biases, section, destination, residual / projection bases
-        float bias_v = a.bias ? bf2f(a.bias[col]) : 0.f;
-        if (a.bias2) bias_v += bf2f(a.bias2[col]);
-        const float bias_g = (a.geglu && a.bias) ? bf2f(a.bias[col + a.N]) : 0.f;
+        float bias_v = a.bias ? bf2f(as_global(a.bias)[col]) : 0.f;
+        if (a.bias2) bias_v += bf2f(as_global(a.bias2)[col]);
+        const float bias_g = (a.geglu && a.bias) ? bf2f(as_global(a.bias)[col + a.N]) : 0.f;
         const int sect = col / a.sect_n, scol = col - sect * a.sect_n;
-        bf16_t* const outp = a.out[sect];
-        const int omode = a.out_mode[sect];
+        const OutSel osel = out_sel(a);                   // (never index a.out[] by a run-time value: see out_sel)
+        bf16_t* const outp = reinterpret_cast<bf16_t*>(osel.base + (sect >= 1 ? osel.d1 : 0ull) + (sect >= 2 ? osel.d2 : 0ull));
+        const int omode = osel.mode0 + (sect >= 1 ? osel.m1 : 0) + (sect >= 2 ? osel.m2 : 0);
         // Two passes per 32-row block: first every load (time projection, residual), then every store.  The
         // output may alias the residual (the residual stream is updated in place), so in a single pass the
         // compiler has to keep each load behind the previous store and the 16 round trips add up.
@@ -301,14 +318,14 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                 v += t[e];
                 const size_t gm = (size_t)(m0 + r);
                 if (omode == OUT_COMPACT_F32) {
-                    reinterpret_cast<float*>(outp)[gm * a.sect_n + scol] = v;
-                    if (a.mirror) a.mirror[gm * a.sect_n + scol] = f2bf(v);
+                    as_global(reinterpret_cast<float*>(outp))[gm * a.sect_n + scol] = v;
+                    if (a.mirror) as_global(a.mirror)[gm * a.sect_n + scol] = f2bf(v);
                 } else if (omode == OUT_COMPACT) {
-                    outp[gm * a.sect_n + scol] = f2bf(v);
+                    as_global(outp)[gm * a.sect_n + scol] = f2bf(v);
                 } else if (omode == OUT_MAP) {
-                    outp[(((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x) * a.sect_n + scol] = f2bf(v);
+                    as_global(outp)[(((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x) * a.sect_n + scol] = f2bf(v);
                 } else {
-                    outp[((size_t)ri.b * a.sect_n + scol) * HW + (size_t)ri.y * a.Wo + ri.x] = f2bf(v);
+                    as_global(outp)[((size_t)ri.b * a.sect_n + scol) * HW + (size_t)ri.y * a.Wo + ri.x] = f2bf(v);
                 }
             }
         }
