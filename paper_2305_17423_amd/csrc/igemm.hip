@@ -248,16 +248,47 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
             ok[it] = rowv[it] < BM && colv[it] < a.N && ri[it].ok;
             pos[it] = out_pos(a, ri[it].b, ri[it].y, ri[it].x);
         }
-        if (!a.temb && !a.res && osel.sect_n >= a.N && (osel.mode0 == OUT_MAP || osel.mode0 == OUT_COMPACT)) {
-            // the common plain case (one bf16 destination, nothing to add): one multiply-add, two packs, one store per item
-            const bool to_map = osel.mode0 == OUT_MAP;
-            auto dst = as_global(reinterpret_cast<u32x2_t*>(osel.base));
+        if (!a.temb && osel.sect_n >= a.N && osel.mode0 != OUT_TOKENS_T) {
+            // The common cases: one destination (bf16 map / bf16 rows / float rows with a bf16 mirror), optional residual
+            // (bf16 map or rows, float rows), no time projection.  Everything uniform is decided out here; an item is
+            // then one multiply-add for its address, one residual load, the packs and one or two stores.
+            const bool out_map = osel.mode0 == OUT_MAP, out_f32 = osel.mode0 == OUT_COMPACT_F32;
+            const int resk = !a.res ? 0 : (a.res_compact == 2 ? 2 : 1);
+            const bool res_map = a.res_compact == 0;
+            u32x2_t rh[MAXI]; f32x4v_t rf[MAXI];
+#pragma unroll
+            for (int it = 0; it < MAXI; ++it) { rh[it] = u32x2_t{0u, 0u}; rf[it] = f32x4v_t{0.f, 0.f, 0.f, 0.f}; }
+            // residual loads without a branch each (a masked-off item reads element 0 instead: valid memory, value
+            // unused), so that they all go out back to back
+            if (resk == 1) {
+                auto src = as_global(reinterpret_cast<const u32x2_t*>(a.res));
+#pragma unroll
+                for (int it = 0; it < MAXI; ++it) {
+                    const size_t e4 = ((res_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it])) * a.N + colv[it]) >> 2;
+                    rh[it] = src[ok[it] ? e4 : 0];
+                }
+            } else if (resk == 2) {
+                auto src = as_global(reinterpret_cast<const f32x4v_t*>(a.res));
+#pragma unroll
+                for (int it = 0; it < MAXI; ++it) {
+                    const size_t e4 = ((size_t)(m0 + rowv[it]) * a.N + colv[it]) >> 2;
+                    rf[it] = src[ok[it] ? e4 : 0];
+                }
+            }
+            auto dst16 = as_global(reinterpret_cast<u32x2_t*>(out_f32 ? reinterpret_cast<unsigned long long>(a.mirror) : osel.base));
+            auto dst32 = as_global(reinterpret_cast<f32x4v_t*>(osel.base));
+            const bool put16 = !out_f32 || a.mirror != nullptr;
 #pragma unroll
             for (int it = 0; it < MAXI; ++it) {
                 if (!ok[it]) continue;
-                const size_t row = to_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it]);
-                const u32x2_t packed = {f2bf2(sv[it].x, sv[it].y), f2bf2(sv[it].z, sv[it].w)};
-                dst[(row * a.N + colv[it]) >> 2] = packed;
+                // the residual is added as one term, as everywhere else: value + (0 + residual)
+                const float v0 = sv[it].x + (rf[it][0] + __uint_as_float(rh[it][0] << 16));
+                const float v1 = sv[it].y + (rf[it][1] + __uint_as_float(rh[it][0] & 0xffff0000u));
+                const float v2 = sv[it].z + (rf[it][2] + __uint_as_float(rh[it][1] << 16));
+                const float v3 = sv[it].w + (rf[it][3] + __uint_as_float(rh[it][1] & 0xffff0000u));
+                const size_t e4 = ((out_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it])) * a.N + colv[it]) >> 2;
+                if (out_f32) dst32[e4] = f32x4v_t{v0, v1, v2, v3};
+                if (put16) dst16[e4] = u32x2_t{f2bf2(v0, v1), f2bf2(v2, v3)};
             }
             return;
         }
@@ -594,7 +625,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmArgs a
 // ---------------------------------------------------------------------------
 // LINEAR: compact A rows, one source, no side product (the per-token linears): the cursor is a single K offset.
 template <int BM, int BN, int WGM, int WGN, int NST, bool LINEAR>
-__global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmArgs a) {
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN >= 8 ? 4 : 1)) void igemm_dma_kernel(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)    // the buffer-descriptor type and builtins exist in the device pass only
     // Kernel arguments arrive through scalar loads that the compiler places where a field is first used:
     // left alone, the set-up below turns into dozens of dependent round trips to the scalar cache.
