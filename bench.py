@@ -34,7 +34,7 @@ KIND_NAMES = {0: "igemm_dma_kernel<64,64,2,2,3,*>", 1: "igemm_dma_kernel<64,128,
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this bench on the
 # headline workload, scaled by what the same counters read for a plain copy of known size; see profiles/.
 PMC_TRAFFIC_BYTES_PER_LAUNCH = {       # (FETCH_SIZE KiB x 2.0 copy factor + WRITE_SIZE KiB x 1.0) x 1024
-    "igemm_dma_kernel<64,64,2,2,3,*>": (5023.3 * 2.0 + 5653.1) * 1024,
+    "igemm_dma_kernel<64,64,2,2,3,*>": (5599.7 * 2.0 + 4347.5) * 1024,
 }
 
 SD15 = dict(in_ch=4, out_ch=4, base=320, mults=(1, 2, 4, 4), layers=2, attn=(True, True, True, False),
