@@ -225,17 +225,18 @@ int fise_masked_attention(const void* x, const void* ln_gamma, const void* ln_be
                           void* y_cache, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Masked ResNet and transformer modules (section "Sparse Computation": "the
- * U-Net architecture is composed of several attention and ResNet modules";
- * each is recomputed on the masked region only).  bf16 only.  The UNet step
- * below is a sequence of these two calls plus resampling convolutions.
+ * Masked ResNet and transformer modules (section "Sparse Computation": the
+ * U-Net is a stack of these two module kinds, each recomputed on the masked
+ * region only).  bf16 only.  The UNet step below is a sequence of these two
+ * calls plus resampling convolutions.
  * ------------------------------------------------------------------------ */
 
 /* out = shortcut(x) + conv2(SiLU(GN2(h1))),  h1 = conv1(SiLU(GN1(x))) + temb,
  * at active pixels; x = channel concatenation of x0 [B,H,W,C0] and x1
  * [B,H,W,C1] (skip link; NULL / 0 for none).  h1_cache and out_cache
  * [B,H,W,Cout] are updated in place (conv2's halo reads cached h1).
- * shortcut = identity (C0+C1 == Cout, sc_w NULL) or the 1x1 conv sc_w/sc_b.
+ * shortcut = identity (one source: C1 == 0, C0 == Cout, sc_w NULL) or the 1x1
+ * conv sc_w/sc_b (required whenever C0+C1 != Cout or a skip source is given).
  * gn*_mean/rstd [B,G] float: with stats_fresh == 0 they are inputs (statistics
  * cached from the previous generation); with stats_fresh != 0 they are
  * recomputed from the current x / updated h1 and written back (eps 1e-5).
@@ -351,9 +352,9 @@ int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cach
                              int first_module, int n_modules,
                              void* workspace, size_t workspace_bytes, void* stream);
 
-/* The keys-restricted reading of the same sub-layer (Approximate Attention:
- * "only calculate the results using non-zero regions" read as restricting the
- * keys too): each active query attends to the keys and values of the ACTIVE
+/* The keys-restricted reading of the same sub-layer (section "Approximate
+ * Attention": computing with the non-zero regions only, read as restricting
+ * the keys too): each active query attends to the keys and values of the ACTIVE
  * tokens of its batch element only.  No K/V cache is read or written; cost is
  * O(M_a^2) instead of O(M_a * H*W).  y = x + Attn(LayerNorm(x)) Wo^T + bo at
  * active tokens, scattered into y_cache; everything else as fise_masked_attention

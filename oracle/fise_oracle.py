@@ -4,13 +4,22 @@ TEST INFRASTRUCTURE ONLY.  Only tests/, __graft_entry__.smoke() and bench.py's
 cpu_baseline leg may import this module.  It shares no code with the HIP path
 and never imports it.  Everything is plain numpy in float64; tensors that the
 method stores (cached feature maps, K/V caches) are rounded to the storage
-dtype exactly where they are stored and nowhere else.
+dtype exactly where they are stored and, by default, nowhere else.  (An
+optional mode, `scratch` / `act_dtype` / `p_dtype` = 'bf16', also rounds the
+operands that pass from one product to the next without being stored: the
+model of any implementation whose matrix units take bf16 operands.)
 
 What each function follows (FISEdit, arxiv 2305.17423):
   * mask_detect ............. section "Fine-Grained Mask Generation", the
                               |X - Y| difference and the {diff >= eps} set of
                               its equation block (single pair, threshold given)
-  * otsu_threshold .......... same equation block, the OTSU(eps) objective
+  * otsu_threshold_exact .... same equation block: argmax of the OTSU(eps)
+                              objective over eps in [0, 1] (every distinct
+                              partition of the values is tried)
+  * otsu_threshold .......... the same objective on the grid eps = k/256
+  * accumulate_diff,
+    normalize_minmax ........ same equation block: the sum over steps of
+                              |X_t - Y_t| and Normalize(.)
   * tiles_from_pixels ....... section "Adaptive Pixel-Wise Sparse Convolution":
                               the set of blocks gathered under a mask m
   * apsc_block_size ......... same section, the argmin over {2,4,8,16,32}^2
@@ -188,6 +197,40 @@ def otsu_threshold(diff: np.ndarray, bins: int = 256):
     return best_eps, (np.asarray(diff, F64) >= best_eps).astype(np.uint8)
 
 
+def otsu_threshold_exact(diff: np.ndarray):
+    """argmax over eps in [0, 1] of OTSU(eps) (the paper's definition, no grid).
+
+    The objective only changes when eps crosses a value of `diff`: with the
+    distinct values v_0 < v_1 < ... every eps in (v_i, v_{i+1}] gives the same
+    classes A = {diff <= v_i}, B = {diff >= v_{i+1}}, so trying one eps per
+    interval tries every partition the definition can produce.  The first
+    maximising interval wins (as the grid search takes its first maximiser).
+    Returns (lo, hi, mask): any eps in (lo, hi] is an exact maximiser, and
+    mask = diff >= hi is the unique mask they all give.  A constant map has no
+    two classes: (0, 0, all ones), the value every eps <= min gives."""
+    a = np.asarray(diff, F64)
+    v = np.unique(a.reshape(-1))
+    if v.size < 2:
+        return 0.0, 0.0, np.ones(a.shape, np.uint8)
+    best, lo, hi = -1.0, 0.0, 0.0
+    for i in range(v.size - 1):
+        o = otsu_objective(a, v[i + 1])         # eps = v_{i+1}: A = {diff <= v_i}
+        if o > best:
+            best, lo, hi = o, float(v[i]), float(v[i + 1])
+    return lo, hi, (a >= hi).astype(np.uint8)
+
+
+def otsu_grid_is_exact(diff: np.ndarray, bins: int = 256) -> bool:
+    """True when the grid search must return the exact mask: some grid point k/bins
+    lies in the exact maximiser's interval (lo, hi] and no grid point before it does
+    better (the grid's objective values are a subset of the exact search's, so the
+    first grid point inside the winning interval is the grid's first maximiser
+    unless an earlier interval ties)."""
+    lo, hi, _ = otsu_threshold_exact(diff)
+    k = math.floor(lo * bins) + 1               # first grid point strictly above lo
+    return k / bins <= hi
+
+
 def apsc_cost(pix: np.ndarray, h: int, w: int, hk: int = 3, wk: int = 3, as_written: bool = False):
     """Cost of splitting into (h, w) blocks under pixel mask `pix`.
 
@@ -290,7 +333,7 @@ def geglu(g):
 # masked convolution
 # ----------------------------------------------------------------------------
 def masked_conv(xs, w, bias, idx, tile, y_cache, dtype, stride: int = 1, upsample: bool = False,
-                gn=None, temb=None, residual=None):
+                gn=None, temb=None, residual=None, act_dtype: str = "f64"):
     """Convolution (k x k, zero padding k//2) evaluated only at the active
     pixels of the *output* map; results are written into y_cache in place,
     all other positions keep their cached value.
@@ -305,7 +348,10 @@ def masked_conv(xs, w, bias, idx, tile, y_cache, dtype, stride: int = 1, upsampl
     their channel concatenation.  stride 2: q = 2p + (ky,kx) - pad.  upsample:
     the input is first enlarged 2x by nearest neighbour (q = (p + (ky,kx) -
     pad) >> 1, zero outside the enlarged image).  `tile` is the tile edge on
-    the output map.
+    the output map.  act_dtype: precision in which the normalised + activated
+    input is held before it is multiplied ('f64' = not rounded; 'bf16' models an
+    implementation that materialises it as a bf16 operand, see `scratch` in the
+    composite oracle).
     """
     x = np.asarray(_cat_sources(xs), F64)
     w = np.asarray(w, F64)
@@ -333,8 +379,8 @@ def masked_conv(xs, w, bias, idx, tile, y_cache, dtype, stride: int = 1, upsampl
                     ok = (iy >= 0) & (iy < Hi) & (ix >= 0) & (ix < Wi)
                 v = x[b, np.clip(iy, 0, Hi - 1), np.clip(ix, 0, Wi - 1), :]
                 if gn is not None:
-                    v = _gn_silu(v, b, gn["mean"], gn["rstd"], np.asarray(gn["gamma"], F64),
-                                 np.asarray(gn["beta"], F64), gn["groups"])
+                    v = round_store(_gn_silu(v, b, gn["mean"], gn["rstd"], np.asarray(gn["gamma"], F64),
+                                             np.asarray(gn["beta"], F64), gn["groups"]), act_dtype)
                 v = v * ok[:, None]
                 acc += v @ w[:, ky, kx, :].T
         if bias is not None:
@@ -358,9 +404,11 @@ def linear(a, w, bias=None):
 # ----------------------------------------------------------------------------
 # attention
 # ----------------------------------------------------------------------------
-def attention_active(q, K, V, heads: int):
+def attention_active(q, K, V, heads: int, p_dtype: str = "f64"):
     """O[b,m,:] = softmax_k(q[b,m,h] . K[b,k,h] / sqrt(d)) V[b,k,h] for each
-    head h (channels [h*d, (h+1)*d)), over *all* keys k."""
+    head h (channels [h*d, (h+1)*d)), over *all* keys k.  p_dtype 'bf16' rounds
+    the unnormalised weights exp(s - max) before they multiply V (the
+    normalising sum stays unrounded): a bf16 P.V product."""
     q, K, V = (np.asarray(t, F64) for t in (q, K, V))
     B, M, C = q.shape
     d = C // heads
@@ -371,8 +419,7 @@ def attention_active(q, K, V, heads: int):
             s = (q[b, :, sl] @ K[b, :, sl].T) / math.sqrt(d)
             s = s - s.max(axis=1, keepdims=True)
             p = np.exp(s)
-            p = p / p.sum(axis=1, keepdims=True)
-            out[b, :, sl] = p @ V[b, :, sl]
+            out[b, :, sl] = (round_store(p, p_dtype) @ V[b, :, sl]) / p.sum(axis=1, keepdims=True)
     return out
 
 
@@ -381,15 +428,15 @@ def token_ids(idx, tile, W):
     return ys * W + xs
 
 
-def masked_self_attention(n_act, wq, wk, wv, heads, K_cache, V_cache, tok, dtype):
+def masked_self_attention(n_act, wq, wk, wv, heads, K_cache, V_cache, tok, dtype, scratch: str = "f64"):
     """Self-attention for active tokens: their K, V rows are refreshed in the
     caches (stored, hence rounded), then each active query attends to every
     key of the updated caches.  n_act[B, M, C] are the (already normalised)
     active tokens; tok their token ids.  Returns O[B, M, C] (heads merged)."""
-    q = linear(n_act, wq)
+    q = round_store(linear(n_act, wq), scratch)
     K_cache[:, tok, :] = round_store(linear(n_act, wk), dtype)
     V_cache[:, tok, :] = round_store(linear(n_act, wv), dtype)
-    return attention_active(q, K_cache, V_cache, heads)
+    return attention_active(q, K_cache, V_cache, heads, scratch)
 
 
 def masked_attention_block(x_map, ln_g, ln_b, wq, wk, wv, wo, bo, heads, K_cache, V_cache,

@@ -153,11 +153,12 @@ def _silu(a):
     return a / (1.0 + np.exp(-a))
 
 
-def resnet_block(P, name, xs, emb, cache, idx, tile, dtype, groups=32, stats="cached"):
+def resnet_block(P, name, xs, emb, cache, idx, tile, dtype, groups=32, stats="cached", scratch="f64"):
     """GN+SiLU -> conv3x3 (+ time projection) -> GN+SiLU -> conv3x3 -> + shortcut,
     at active pixels; `xs` is the input map or [map, skip map] (channel concat).
     Stores h1 and the block output in the cache; the shortcut (identity, or a
-    1x1 conv when the channel count changes) is not stored, hence not rounded."""
+    1x1 conv when the channel count changes) is not stored, hence not rounded.
+    scratch: see unet_step."""
     xs = list(xs) if isinstance(xs, (list, tuple)) else [xs]
     ci = sum(x.shape[-1] for x in xs)
     co = P[f"{name}.conv1.w"].shape[0]
@@ -165,7 +166,7 @@ def resnet_block(P, name, xs, emb, cache, idx, tile, dtype, groups=32, stats="ca
     tproj = fo.linear(_silu(np.asarray(emb, F64)), P[f"{name}.temb.w"], P[f"{name}.temb.b"])
     fo.masked_conv(xs, P[f"{name}.conv1.w"], P[f"{name}.conv1.b"], idx, tile, cache[f"{name}.h1"], dtype,
                    gn=dict(mean=m1, rstd=r1, gamma=P[f"{name}.gn1.g"], beta=P[f"{name}.gn1.b"], groups=groups),
-                   temb=tproj)
+                   temb=tproj, act_dtype=scratch)
     h1 = cache[f"{name}.h1"]
     m2, r2 = _stats(cache, f"{name}.gn2", h1, groups, 1e-5, stats)
     if ci != co:
@@ -176,16 +177,17 @@ def resnet_block(P, name, xs, emb, cache, idx, tile, dtype, groups=32, stats="ca
         short = fo._cat_sources(xs)
     fo.masked_conv(h1, P[f"{name}.conv2.w"], P[f"{name}.conv2.b"], idx, tile, cache[f"{name}.out"], dtype,
                    gn=dict(mean=m2, rstd=r2, gamma=P[f"{name}.gn2.g"], beta=P[f"{name}.gn2.b"], groups=groups),
-                   residual=short)
+                   residual=short, act_dtype=scratch)
     return cache[f"{name}.out"]
 
 
-def transformer_block(P, name, x, Kc, Vc, cache, idx, tile, dtype, heads, groups=32, stats="cached"):
+def transformer_block(P, name, x, Kc, Vc, cache, idx, tile, dtype, heads, groups=32, stats="cached", scratch="f64"):
     """GN -> 1x1 in -> [LN, self-attn] -> [LN, cross-attn] -> [LN, GEGLU FF]
     -> 1x1 out -> + block input, on active tokens only.  Self-attention K/V
     rows of the active tokens are refreshed in the cache (stored => rounded);
     active queries attend to all keys.  Kc, Vc: context K/V of this block
-    (computed once per conditioning).  Stores the block output."""
+    (computed once per conditioning).  Stores the block output.  scratch: see
+    unet_step (the residual stream h itself is never rounded)."""
     x = np.asarray(x, F64)
     B, H, W, C = x.shape
     m, r = _stats(cache, f"{name}.gn", x, groups, 1e-6, stats)
@@ -194,22 +196,23 @@ def transformer_block(P, name, x, Kc, Vc, cache, idx, tile, dtype, heads, groups
         return cache[f"{name}.out"]
     gi = np.arange(C) // (C // groups)
     xa = x[:, ys, xs, :]                                              # [B, M, C]
-    g = (xa - m[:, None, gi]) * r[:, None, gi] * np.asarray(P[f"{name}.gn.g"], F64) + np.asarray(P[f"{name}.gn.b"], F64)
+    rs = lambda a: fo.round_store(a, scratch)                          # an operand parked in scratch memory
+    g = rs((xa - m[:, None, gi]) * r[:, None, gi] * np.asarray(P[f"{name}.gn.g"], F64) + np.asarray(P[f"{name}.gn.b"], F64))
     h = fo.linear(g, np.asarray(P[f"{name}.pin.w"]).reshape(C, C), P[f"{name}.pin.b"])
     # self-attention
-    n = fo.layernorm(h, P[f"{name}.ln1.g"], P[f"{name}.ln1.b"])
-    o = fo.masked_self_attention(n, P[f"{name}.a1.q.w"], P[f"{name}.a1.k.w"], P[f"{name}.a1.v.w"], heads,
-                                 cache[f"{name}.k"], cache[f"{name}.v"], ys * W + xs, dtype)
+    n = rs(fo.layernorm(h, P[f"{name}.ln1.g"], P[f"{name}.ln1.b"]))
+    o = rs(fo.masked_self_attention(n, P[f"{name}.a1.q.w"], P[f"{name}.a1.k.w"], P[f"{name}.a1.v.w"], heads,
+                                    cache[f"{name}.k"], cache[f"{name}.v"], ys * W + xs, dtype, scratch))
     h = h + fo.linear(o, P[f"{name}.a1.o.w"], P[f"{name}.a1.o.b"])
     # cross-attention
-    n = fo.layernorm(h, P[f"{name}.ln2.g"], P[f"{name}.ln2.b"])
-    o = fo.attention_active(fo.linear(n, P[f"{name}.a2.q.w"]), Kc, Vc, heads)
+    n = rs(fo.layernorm(h, P[f"{name}.ln2.g"], P[f"{name}.ln2.b"]))
+    o = rs(fo.attention_active(rs(fo.linear(n, P[f"{name}.a2.q.w"])), Kc, Vc, heads, scratch))
     h = h + fo.linear(o, P[f"{name}.a2.o.w"], P[f"{name}.a2.o.b"])
     # feed-forward
-    n = fo.layernorm(h, P[f"{name}.ln3.g"], P[f"{name}.ln3.b"])
-    f = fo.geglu(fo.linear(n, P[f"{name}.ff1.w"], P[f"{name}.ff1.b"]))
+    n = rs(fo.layernorm(h, P[f"{name}.ln3.g"], P[f"{name}.ln3.b"]))
+    f = rs(fo.geglu(fo.linear(n, P[f"{name}.ff1.w"], P[f"{name}.ff1.b"])))
     h = h + fo.linear(f, P[f"{name}.ff2.w"], P[f"{name}.ff2.b"])
-    y = fo.linear(h, np.asarray(P[f"{name}.pout.w"]).reshape(C, C), P[f"{name}.pout.b"]) + xa
+    y = fo.linear(rs(h), np.asarray(P[f"{name}.pout.w"]).reshape(C, C), P[f"{name}.pout.b"]) + xa
     cache[f"{name}.out"][:, ys, xs, :] = fo.round_store(y, dtype)
     return cache[f"{name}.out"]
 
@@ -257,7 +260,8 @@ def module_output_name(m):
     return "eps" if m["kind"] == "out" else f"{m['name']}.out"
 
 
-def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stats="cached", level_dense=None, only=None):
+def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stats="cached", level_dense=None, only=None,
+              scratch="f64"):
     """One masked UNet evaluation.  `latent` [B,H,W,in_ch] is the (updated)
     input; `t_sin` [B, base] the sinusoidal time embedding; `ctx_kv` the dict
     from context_kv_all for the *new* conditioning; `idx` the active-tile list
@@ -267,7 +271,16 @@ def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stat
     divisible by 2**(levels-1).  The cache is updated in place; returns the
     predicted noise map cache['eps'].  level_dense[l] = True runs level l with
     the full index list.  only = a set of module positions in the walk: the
-    others are skipped and their cached output stands in for them."""
+    others are skipped and their cached output stands in for them.
+
+    scratch: precision of the operands a module hands from one product to the
+    next WITHOUT storing them in the cache (normalised / activated conv inputs,
+    LayerNorm outputs, queries, softmax weights, attention outputs, the gated
+    feed-forward activations, the residual stream entering the 1x1 out).  'f64'
+    (default) keeps them exact: only stored tensors are rounded.  'bf16' rounds
+    each of them once, which is what any implementation whose matrix units take
+    bf16 operands must do; the float accumulations and the residual stream stay
+    unrounded in both modes."""
     G, heads = desc["groups"], desc["heads"]
     H, W = desc["H"], desc["W"]
     nl = len(desc["mults"])
@@ -290,10 +303,10 @@ def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stat
             cur = fo.masked_conv(np.asarray(latent, F64), P[f"{n}.w"], P[f"{n}.b"], li, lt, cache[f"{n}.out"], dtype)
         elif k == "res":
             src = [cur] if m["skip"] is None else [cur, cache[m["skip"]]]
-            cur = resnet_block(P, n, src, emb, cache, li, lt, dtype, G, stats)
+            cur = resnet_block(P, n, src, emb, cache, li, lt, dtype, G, stats, scratch)
         elif k == "tr":
             Kc, Vc = ctx_kv[n]
-            cur = transformer_block(P, n, cur, Kc, Vc, cache, li, lt, dtype, heads, G, stats)
+            cur = transformer_block(P, n, cur, Kc, Vc, cache, li, lt, dtype, heads, G, stats, scratch)
         elif k == "ds":
             cur = fo.masked_conv(cur, P[f"{n}.w"], P[f"{n}.b"], li, lt, cache[f"{n}.out"], dtype, stride=2)
         elif k == "us":
@@ -301,16 +314,17 @@ def unet_step(P, desc, cache, latent, t_sin, ctx_kv, idx, base_tile, dtype, stat
         elif k == "out":
             mo, ro = _stats(cache, f"{n}.gn", cur, G, 1e-5, stats)
             cur = fo.masked_conv(cur, P[f"{n}.conv.w"], P[f"{n}.conv.b"], li, lt, cache["eps"], dtype,
-                                 gn=dict(mean=mo, rstd=ro, gamma=P[f"{n}.gn.g"], beta=P[f"{n}.gn.b"], groups=G))
+                                 gn=dict(mean=mo, rstd=ro, gamma=P[f"{n}.gn.g"], beta=P[f"{n}.gn.b"], groups=G),
+                                 act_dtype=scratch)
     return cache["eps"]
 
 
-def unet_dense(P, desc, latent, t_sin, ctx_kv, dtype):
+def unet_dense(P, desc, latent, t_sin, ctx_kv, dtype, scratch="f64"):
     """Dense forward = the same walk, full index list, fresh statistics, on an
     all-zero cache.  Returns (eps, cache)."""
     cache = empty_cache(desc)
     nl = len(desc["mults"])
     tile = 1 << (nl - 1)
     eps = unet_step(P, desc, cache, latent, t_sin, ctx_kv, fo.full_index(desc["H"], desc["W"], tile), tile,
-                    dtype, stats="fresh")
+                    dtype, stats="fresh", scratch=scratch)
     return eps, cache

@@ -72,10 +72,13 @@ class CacheRing:
         self._prefetch(t)
         s = self._slot(t)
         torch.cuda.current_stream().wait_event(self.h2d_done[s])
-        if prefetch_next and self.slots >= 3:
-            # with three slots or more the next step's slot is neither this one nor one still waiting for its
-            # write-back to start; with two, the next copy-in is issued by release() instead
-            self._prefetch((t + 1) % self.n_steps)
+        nxt = (t + 1) % self.n_steps
+        if prefetch_next and self.slots >= 3 and self._slot(nxt) != s:
+            # with three slots or more the next step's slot is normally neither this one nor one still waiting for
+            # its write-back to start.  With two slots, and when the step count wraps onto this very slot
+            # (n_steps % slots == 1 at the last step), the next copy-in is issued by release() instead, after the
+            # work on this slot and its write-back have been ordered in front of it.
+            self._prefetch(nxt)
         return self.dev[s]
 
     def release(self, t: int, write_back: bool = True):
@@ -96,8 +99,9 @@ class CacheRing:
                 done = torch.cuda.Event()
                 done.record(self.d2h)
             self.d2h_done[s] = done
-        if self.slots == 2:
-            self._prefetch((t + 1) % self.n_steps)
+        nxt = (t + 1) % self.n_steps
+        if self.slots == 2 or self._slot(nxt) == s:
+            self._prefetch(nxt)
 
     def store(self, t: int, src: torch.Tensor):
         """Set step t's cache from a device tensor (cache building).  Synchronous for host spill."""

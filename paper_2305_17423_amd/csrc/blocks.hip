@@ -181,6 +181,8 @@ extern "C" int fise_masked_resnet_block(const fise_resnet_args* a, void* workspa
     if (a->B < 1 || a->C0 < 1 || a->Cout < 1 || a->G < 1 || Ci % a->G || a->Cout % a->G) return fail(FISE_ERR_SHAPE, "%s: channels %d->%d, groups %d", fn, Ci, a->Cout, a->G);
     if (a->C0 % 32 || a->C1 % 32 || a->Cout % 32) return fail(FISE_ERR_ALIGN, "%s: channel counts must be multiples of 32", fn);
     if (Ci != a->Cout && !a->sc_w) return fail(FISE_ERR_NULL, "%s: %d -> %d channels needs the 1x1 shortcut", fn, Ci, a->Cout);
+    // the identity shortcut reads x0 with row pitch Cout: a concatenated input has no such map
+    if (a->C1 > 0 && !a->sc_w) return fail(FISE_ERR_SHAPE, "%s: two sources (%d + %d channels) need the 1x1 shortcut", fn, a->C0, a->C1);
     if (int e = check_region(fn, a->H, a->W, a->tile, a->n_active, a->tile_idx)) return e;
     if (a->out_cache == a->x0 || a->h1_cache == a->x0 || a->out_cache == a->h1_cache) return fail(FISE_ERR_SHAPE, "%s: maps alias", fn);
     if (a->n_active == 0) return FISE_OK;

@@ -53,6 +53,25 @@ def test_host_side_validation_without_gpu():
     assert L.fise_masked_conv(ctypes.byref(args), None, 0, None) == 0                        # empty mask: no-op
 
 
+def test_resnet_block_rejects_identity_shortcut_for_two_sources():
+    """The identity shortcut reads one map of Cout channels per pixel: a concatenated input (skip link) must come
+    with the 1x1 shortcut, even when C0 + C1 == Cout."""
+    L = fb.lib()
+    a = 0x1000
+    r = fb.fise_resnet_args()
+    for f in ("x0", "x1", "gn1_mean", "gn1_rstd", "gn1_gamma", "gn1_beta", "conv1_w", "gn2_mean", "gn2_rstd", "gn2_gamma",
+              "gn2_beta", "conv2_w"):
+        setattr(r, f, a)
+    r.h1_cache, r.out_cache = 0x2000, 0x3000
+    r.C0 = r.C1 = 32; r.Cout = 64; r.B = 1; r.H = r.W = 8; r.G = 32; r.tile = 4; r.n_active = 0
+    assert L.fise_masked_resnet_block(ctypes.byref(r), None, 0, None) == -2
+    assert "shortcut" in fb.fise_last_error()
+    r.sc_w = a
+    assert L.fise_masked_resnet_block(ctypes.byref(r), None, 0, None) == 0                  # empty mask: accepted, no-op
+    r.sc_w = None; r.x1 = None; r.C1 = 0; r.C0 = 64
+    assert L.fise_masked_resnet_block(ctypes.byref(r), None, 0, None) == 0                  # one source: identity is fine
+
+
 def test_unet_plan_matches_oracle_tables():
     import numpy as np
     from oracle import fise_unet_oracle as uo

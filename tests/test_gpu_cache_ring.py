@@ -18,7 +18,7 @@ def fb():
     return binding
 
 
-@pytest.mark.parametrize("slots,n_steps", [(3, 5), (2, 5), (3, 2)])
+@pytest.mark.parametrize("slots,n_steps", [(3, 5), (2, 5), (3, 2), (3, 4), (3, 7)])
 def test_host_spill_session_equals_resident_session(fb, slots, n_steps):
     from paper_2305_17423_amd.cache_ring import CacheRing
     d = uo.tiny_desc(H=32, W=32, base=64)

@@ -417,6 +417,164 @@ def test_otsu_objective_is_between_class_variance_and_two_cluster_case():
     assert fo.otsu_objective(d, 0.0) == 0 and fo.otsu_objective(d, 1.5) == 0
 
 
+def _otsu_scalar(vals, eps):
+    """OTSU(eps) of the paper's equation block with scalar loops: N1 N2 / (N1 + N2)^2 (mean_A - mean_B)^2."""
+    n1 = n2 = 0
+    s1 = s2 = 0.0
+    for v in vals:
+        if v < eps:
+            n1 += 1; s1 += v
+        else:
+            n2 += 1; s2 += v
+    if n1 == 0 or n2 == 0:
+        return 0.0
+    return n1 * n2 / float(n1 + n2) ** 2 * (s1 / n1 - s2 / n2) ** 2
+
+
+def test_accumulate_diff_vs_scalar_loops():
+    """sum_t mean_{b,c} |X_t - Y_t| per pixel, spelled out index by index (a wrong axis, a sum for the mean, a dropped
+    absolute value or a dropped step all fail)."""
+    rng = np.random.default_rng(31)
+    T, B, H, W, C = 3, 2, 3, 4, 5
+    X = [rng.standard_normal((B, H, W, C)) for _ in range(T)]
+    Y = [rng.standard_normal((B, H, W, C)) for _ in range(T)]
+    got = fo.accumulate_diff(X, Y)
+    assert got.shape == (H, W)
+    for y in range(H):
+        for x in range(W):
+            acc = 0.0
+            for t in range(T):
+                s = 0.0
+                for b in range(B):
+                    for c in range(C):
+                        s += abs(X[t][b, y, x, c] - Y[t][b, y, x, c])
+                acc += s / (B * C)
+            assert abs(got[y, x] - acc) < 1e-12
+    # one step, identical maps -> zero; swapping the roles of the maps changes nothing
+    assert np.all(fo.accumulate_diff(X[:1], X[:1]) == 0)
+    np.testing.assert_allclose(fo.accumulate_diff(Y, X), got, rtol=0, atol=1e-15)
+    # a single-step accumulation is the per-pixel difference of mask_detect (float32 there)
+    np.testing.assert_allclose(fo.accumulate_diff(X[:1], Y[:1]), fo.pixel_diff(X[0], Y[0]), rtol=1e-5)
+
+
+def test_normalize_minmax_closed_forms():
+    rng = np.random.default_rng(32)
+    a = rng.uniform(-3, 5, (6, 7))
+    n = fo.normalize_minmax(a)
+    lo, hi = min(a.reshape(-1).tolist()), max(a.reshape(-1).tolist())
+    for y in range(6):
+        for x in range(7):
+            assert abs(n[y, x] - (a[y, x] - lo) / (hi - lo)) < 1e-15
+    assert n.min() == 0.0 and n.max() == 1.0
+    # invariant under positive affine maps of the input, order preserving, and flat maps give zeros
+    np.testing.assert_allclose(fo.normalize_minmax(3.5 * a - 11.0), n, atol=1e-13)
+    assert np.array_equal(np.argsort(n.reshape(-1)), np.argsort(a.reshape(-1)))
+    assert np.all(fo.normalize_minmax(np.full((3, 3), 2.5)) == 0)
+    np.testing.assert_array_equal(fo.normalize_minmax(np.array([[0.0, 0.25], [1.0, 0.5]])), [[0.0, 0.25], [1.0, 0.5]])
+
+
+def test_otsu_exact_bruteforce_tiny_maps():
+    """Exact argmax over eps in [0, 1] on maps of <= 16 pixels: no eps from a dense sweep of [0, 1] (plus every value
+    and midpoint of the map) reaches a higher objective than the returned interval, every eps inside the interval
+    attains the maximum, the mask is {diff >= eps} for those eps, and the maximum equals the one found by trying all
+    2^n two-class partitions that a threshold can make (upper sets of the sorted values)."""
+    rng = np.random.default_rng(33)
+    for trial in range(40):
+        n = int(rng.integers(2, 17))
+        vals = rng.uniform(0, 1, n)
+        if trial % 3 == 0:
+            vals = np.round(vals * 6) / 6                 # repeated values
+        if trial % 5 == 0:
+            vals[: n // 2] = vals[0]                      # a heavy tie
+        d = fo.normalize_minmax(vals.reshape(1, n))
+        flat = d.reshape(-1).tolist()
+        lo, hi, mask = fo.otsu_threshold_exact(d)
+        if len(set(flat)) < 2:
+            assert mask.all()
+            continue
+        sweep = [k / 4096 for k in range(4097)] + flat + [(a + b) / 2 for a in flat for b in flat]
+        best = max(_otsu_scalar(flat, e) for e in sweep)
+        inside = [lo + (hi - lo) * f for f in (1e-9, 0.25, 0.5, 1.0)]
+        for e in inside:
+            assert lo < e <= hi
+            assert abs(_otsu_scalar(flat, e) - best) < 1e-12, (trial, e)
+            assert np.array_equal(mask.reshape(-1), np.array([v >= e for v in flat], np.uint8))
+        # first maximiser: nothing at or below `lo` reaches the maximum
+        assert all(_otsu_scalar(flat, e) < best - 1e-13 for e in sweep if e <= lo)
+        # the objective is the between-class variance, so the maximiser also minimises the within-class variance
+        srt = sorted(set(flat))
+        within = []
+        for i in range(len(srt) - 1):
+            A = [v for v in flat if v <= srt[i]]; Bc = [v for v in flat if v > srt[i]]
+            within.append((len(A) * np.var(A) + len(Bc) * np.var(Bc)) / n)
+        A = [v for v in flat if v < hi]; Bc = [v for v in flat if v >= hi]
+        assert abs((len(A) * np.var(A) + len(Bc) * np.var(Bc)) / n - min(within)) < 1e-12
+
+
+def test_otsu_grid_vs_exact():
+    """The 257-point grid search returns the exact mask whenever a grid point falls inside the exact maximiser's
+    interval (lo, hi] (otsu_grid_is_exact); otherwise it may not, and then its objective is strictly smaller."""
+    rng = np.random.default_rng(34)
+    agree = differ = 0
+    for trial in range(60):
+        n = int(rng.integers(4, 400))
+        if trial % 2:
+            vals = np.concatenate([rng.uniform(0, 0.3, n), rng.uniform(0.6, 1.0, n // 3 + 1)])     # two clusters: a wide gap
+        else:
+            vals = rng.uniform(0, 1, n) ** 3                                                       # dense values, narrow gaps
+        d = fo.normalize_minmax(vals.reshape(1, -1))
+        lo, hi, exact = fo.otsu_threshold_exact(d)
+        eps, grid = fo.otsu_threshold(d)
+        if fo.otsu_grid_is_exact(d):
+            assert lo < eps <= hi and np.array_equal(grid, exact), trial
+            agree += 1
+        else:
+            assert not (lo < eps <= hi)
+            assert fo.otsu_objective(d, eps) < fo.otsu_objective(d, hi)
+            assert not np.array_equal(grid, exact)
+            differ += 1
+    assert agree >= 20, (agree, differ)
+    # A case where they must differ: two heavy clusters 0.9/256 apart inside one grid cell (76/256, 77/256), far from
+    # the two lone values that fix the range.  The best split separates the clusters; no grid point can.
+    n = 100000
+    v = np.concatenate([[0.0], np.full(n, 76.05 / 256), np.full(n, 76.95 / 256), [1.0]]).reshape(1, -1)
+    lo, hi, exact = fo.otsu_threshold_exact(v)
+    assert (lo, hi) == (76.05 / 256, 76.95 / 256) and exact.sum() == n + 1
+    assert not fo.otsu_grid_is_exact(v)
+    eps, grid = fo.otsu_threshold(v)
+    assert not np.array_equal(grid, exact) and fo.otsu_objective(v, eps) < fo.otsu_objective(v, hi)
+
+
+def test_scratch_rounding_mode_rounds_only_the_named_operands():
+    """masked_conv(act_dtype='bf16') equals the convolution of the explicitly rounded activation map; attention with
+    p_dtype='bf16' equals the product with explicitly rounded weights divided by the unrounded sum; the default mode
+    is untouched."""
+    rng = np.random.default_rng(35)
+    B, H, W, C, Co, G = 1, 6, 6, 8, 4, 2
+    x = rng.standard_normal((B, H, W, C)); w = rng.standard_normal((Co, 3, 3, C)) * 0.2
+    gamma, beta = 1 + 0.1 * rng.standard_normal(C), 0.1 * rng.standard_normal(C)
+    mean, rstd = fo.gn_stats(x, G, 1e-5)
+    full = fo.full_index(H, W, 2)
+    gn = dict(mean=mean, rstd=rstd, gamma=gamma, beta=beta, groups=G)
+    got = fo.masked_conv(x, w, None, full, 2, np.zeros((B, H, W, Co)), "f64", gn=gn, act_dtype="bf16")
+    act = np.zeros((B, H, W, C))
+    fo.masked_gn_silu(x, mean, rstd, gamma, beta, G, full, 2, act, "bf16")          # the activation map, stored as bf16
+    want = fo.masked_conv(act, w, None, full, 2, np.zeros((B, H, W, Co)), "f64")
+    np.testing.assert_allclose(got, want, atol=1e-12)
+    exact = fo.masked_conv(x, w, None, full, 2, np.zeros((B, H, W, Co)), "f64", gn=gn)
+    assert 0 < np.abs(got - exact).max() < 0.05
+    q, K, V = rng.standard_normal((1, 3, 8)), rng.standard_normal((1, 5, 8)), rng.standard_normal((1, 5, 8))
+    o = fo.attention_active(q, K, V, 2, "bf16")
+    for h in range(2):
+        sl = slice(4 * h, 4 * h + 4)
+        for m in range(3):
+            s = [float(q[0, m, sl] @ K[0, k, sl]) / 2.0 for k in range(5)]
+            p = [math.exp(v - max(s)) for v in s]
+            pr = [float(fo.round_store(v, "bf16")) for v in p]
+            want = sum(pr[k] * V[0, k, sl] for k in range(5)) / sum(p)
+            np.testing.assert_allclose(o[0, m, sl], want, atol=1e-12)
+
+
 def test_apsc_bruteforce():
     rng = np.random.default_rng(17)
     pix = wl.ellipse_pixels(rng, 32, 32, 0.1)
