@@ -73,3 +73,14 @@ def params_from_shapes(rng, shapes, std=0.02, dtype="bf16"):
         else:
             P[name] = normal(rng, shp, std, dtype)
     return P
+
+
+def ddim_coeffs(t: int, t_prev: int, T: int = 1000, beta0: float = 0.00085, beta1: float = 0.012):
+    """(a, b) of the deterministic sampler update x_prev = a * x + b * eps between timesteps t > t_prev of a
+    scaled-linear noise schedule (harness arithmetic between two UNet evaluations; not part of the masked path)."""
+    betas = np.linspace(math.sqrt(beta0), math.sqrt(beta1), T) ** 2
+    ab = np.cumprod(1.0 - betas)
+    at, ap = float(ab[t]), (float(ab[t_prev]) if t_prev >= 0 else 1.0)
+    a = math.sqrt(ap / at)
+    b = math.sqrt(1.0 - ap) - math.sqrt(ap * (1.0 - at) / at)
+    return a, b

@@ -48,6 +48,54 @@ def rel_l2(got, want):
     return float(np.sqrt(np.sum((got - want) ** 2)) / max(np.sqrt(np.sum(want ** 2)), 1e-30))
 
 
+# Whole-chain drift.  The device feeds every product bf16 operands; the float64 oracle in its default mode rounds
+# only what the method stores.  One operand rounding is a relative error uniform in +-2^-9 (rms 1.13e-3) on every
+# term of a sum, i.e. about 1.13e-3 of the output's rms.  Noise enters relative to the BRANCH it is made in, so what
+# counts is the number of normalised branches upstream of a tensor (a convolution behind its GroupNorm, the 1x1 in /
+# out pair, each LayerNorm-ed sub-block that adds into the residual stream): branch_depths() below.  The branches of
+# a chain add in quadrature and the normalisation in front of each one re-amplifies what is already there (measured
+# gain 1.4..2.4), so a tensor behind n branches carries a relative L2 error of at most
+# DRIFT_L2_PER_SQRT_STAGE * sqrt(n): measured 1.6e-3..2.7e-3 per sqrt(branch) at every depth of the small
+# instance (n = 2 .. 116; the largest in dense passes, whose statistics are recomputed) and 1.0e-3..2.2e-3 at SD-1.5 size.  The error field is noise of that size, not isolated
+# wrong elements: its elementwise maximum over the 1e5..1e6 elements of a tensor stays within DRIFT_MAX_OVER_L2
+# times its own L2 (measured 4.1..7.7).  The oracle's scratch='bf16' mode removes the first-order part (the two
+# sides then round the same operands), but only until the first rounding decisions differ: every later rounding is
+# taken on values that already differ and the two sides decorrelate.  Measured on both instances, that mode is
+# within the plain tolerance up to SCRATCH_FLAT_STAGES branches and follows the same sqrt(n) law after that.
+DRIFT_L2_PER_SQRT_STAGE = 3.0e-3
+DRIFT_MAX_OVER_L2 = 10.0
+SCRATCH_FLAT_STAGES = 7
+
+
+def chain_l2_bound(n_stages, tol, cap=True):
+    law = DRIFT_L2_PER_SQRT_STAGE * float(np.sqrt(n_stages))
+    return min(tol, law) if cap else law
+
+
+def branch_depths(mods, start=0):
+    """name of every stored tensor -> number of normalised branches between the step's input and that tensor,
+    following the module walk: a convolution counts 1 (ResNet: h1 after one, out after two), a transformer block 4
+    (1x1 in / out, self-attention, cross-attention, feed-forward; its K and V sit behind the 1x1 in and the QKV
+    projection: 2)."""
+    n, out = start, {}
+    for m in mods:
+        k, nm = m["kind"], m["name"]
+        if k == "res":
+            out[f"{nm}.h1"], out[f"{nm}.out"] = n + 1, n + 2
+            n += 2
+        elif k == "tr":
+            out[f"{nm}.k"] = out[f"{nm}.v"] = n + 2
+            out[f"{nm}.out"] = n + 4
+            n += 4
+        elif k == "out":
+            out["eps"] = n + 1
+            n += 1
+        else:
+            out[f"{nm}.out"] = n + 1
+            n += 1
+    return out
+
+
 def active_mask(idx, tile, H, W):
     ys, xs = fo.active_pixels(idx, tile, W)
     m = np.zeros((H, W), bool)

@@ -127,6 +127,12 @@ def test_otsu_and_accumulate_and_apsc(fb):
     fb.fise_otsu_mask(acc, eps, pm, wsb)
     np.testing.assert_array_equal(pm.cpu().numpy(), mask_o)
     assert abs(float(eps.item()) - eps_o) < 1e-7
+    # ... and against the exact argmax over [0, 1]: on this map a grid point lies inside the exact maximiser's interval,
+    # so the grid search (oracle and device) must give the exact mask
+    nd = fo.normalize_minmax(diff)
+    lo, hi, mask_x = fo.otsu_threshold_exact(nd)
+    assert fo.otsu_grid_is_exact(nd) and lo < float(eps.item()) <= hi
+    np.testing.assert_array_equal(pm.cpu().numpy(), mask_x)
     assert abs(mask_o.mean() - pixm.mean()) < 0.02                        # it found the blob
     # constant map: everything lands in class B
     fb.fise_otsu_mask(torch.ones(64, device=DEV), eps, pm.reshape(-1)[:64], wsb)

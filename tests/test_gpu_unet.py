@@ -7,7 +7,8 @@ import torch
 from oracle import fise_oracle as fo
 from oracle import fise_unet_oracle as uo
 from paper_2305_17423_amd import workloads as wl
-from helpers import (DEV, TOL, dev, host, rel_err, rel_l2, idx_dev, active_mask, pack_weights, pack_cache, unpack_cache)
+from helpers import (DEV, TOL, dev, host, rel_err, rel_l2, idx_dev, active_mask, pack_weights, pack_cache, unpack_cache,
+                     chain_l2_bound, branch_depths, DRIFT_MAX_OVER_L2, SCRATCH_FLAT_STAGES)
 
 pytestmark = pytest.mark.gpu
 
@@ -38,15 +39,18 @@ def stored_maps(d):
     yield uo.unet_modules(d)[-1], "eps"
 
 
-# The whole step chains ~100 bf16 stages (every GEMM input is rounded to bf16 on the device, the
-# oracle rounds only what the method stores), so the two drift apart with depth.  Module-level
-# parity (test_gpu_blocks.py) holds the elementwise 2e-2 bar; over the whole chain every stored
-# tensor must stay within 2e-2 in relative L2 norm and within CHAIN_MAX elementwise.
-CHAIN_MAX = 0.25
-
-
-def compare_caches(d, got, want, before, idx, bt, tol):
-    worst = ("", 0.0, 0.0)
+# One call of the whole step chains ~200 products (116 normalised branches) whose operands the device rounds to bf16, so
+# the device and the float64 oracle drift apart with depth (helpers.py states the law and where it comes from).  Every
+# stored tensor is held
+#   * in relative L2 to min(tol, 3.0e-3 * sqrt(branches upstream)) (cap=False: to the law alone),
+#   * elementwise to max(tol, 10 x its own relative L2): the difference is noise of the drift's size everywhere, never
+#     an isolated wrong element (a bad halo or tile edge is wrong by O(1)),
+#   * bitwise at every position the step may not write.
+# scratch=True: `want` comes from the oracle's bf16-operand mode, which follows the device's own roundings for the
+# first modules: tensors up to SCRATCH_FLAT_STAGES branches deep are then held to the plain elementwise tolerance.
+def compare_caches(d, got, want, before, idx, bt, tol, scratch=False, start=0, say=None, cap=True):
+    depth = branch_depths(uo.unet_modules(d), start)
+    worst_e, worst_l = ("", 0.0, 1.0), ("", 0.0, 1.0)          # name, value, bound
     for m, name in stored_maps(d):
         H, W = d["H"] >> m["lvl"], d["W"] >> m["lvl"]
         act = active_mask(idx, bt >> m["lvl"], H, W)
@@ -54,13 +58,19 @@ def compare_caches(d, got, want, before, idx, bt, tol):
         if g.ndim == 3:                                   # K / V caches [B, N, C]
             act = act.reshape(-1)
         err, l2 = rel_err(g[:, act], w_[:, act]), rel_l2(g[:, act], w_[:, act])
-        if l2 > worst[2]:
-            worst = (name, err, l2)
-        assert l2 <= tol, f"{name}: relative L2 error {l2:.3e}"
-        assert err <= CHAIN_MAX, f"{name}: elementwise rel err {err:.3e}"
+        n = depth[name]
+        l2_bound = chain_l2_bound(n, tol, cap)
+        e_bound = tol if (scratch and n <= SCRATCH_FLAT_STAGES) else max(tol, DRIFT_MAX_OVER_L2 * l2)
+        if err / e_bound > worst_e[1] / worst_e[2]:
+            worst_e = (name, err, e_bound)
+        if l2 / l2_bound > worst_l[1] / worst_l[2]:
+            worst_l = (name, l2, l2_bound)
+        assert l2 <= l2_bound, f"{name}: relative L2 error {l2:.3e} > {l2_bound:.3e} ({n} branches upstream)"
+        assert err <= e_bound, f"{name}: elementwise rel err {err:.3e} > {e_bound:.3e} ({n} branches upstream, L2 {l2:.3e})"
         assert np.array_equal(g[:, ~act], b_[:, ~act]), f"{name}: inactive positions changed"
-    print("worst:", worst)
-    return worst
+    (say or print)(f"closest to its bound: elementwise {worst_e[0]} {worst_e[1]:.3e} (bound {worst_e[2]:.3e}); "
+                   f"relative L2 {worst_l[0]} {worst_l[1]:.3e} (bound {worst_l[2]:.3e})")
+    return worst_e, worst_l
 
 
 @pytest.mark.parametrize("seed", [5001, 5002])
@@ -217,7 +227,7 @@ def download_tensor(layout, buf, name, shape):
     return raw.reshape(shape).to(torch.float64).numpy()
 
 
-def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"]):
+def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"], scratch="f64"):
     rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, seed, std)
     H, W = d["H"], d["W"]
     shapes = uo.cache_shapes(d)
@@ -249,7 +259,7 @@ def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"]):
     want = {k: v.copy() for k, v in cache_old.items()}
     worst = ("", 0.0)
     for mi, m in enumerate(mods):
-        uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16", only={mi})
+        uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16", only={mi}, scratch=scratch)
         fb.fise_masked_unet_modules(u, Wd, cm, latd, tsd, kvd, idxd, idx.size, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
         names = [f"{m['name']}.{s}" for s in module_tensors(m)] or ["eps"]
         act = active_mask(idx, bt >> m["lvl"], H >> m["lvl"], W >> m["lvl"])
@@ -265,12 +275,16 @@ def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"]):
         if mi % 8 == 7:
             say(f"  masked module {mi + 1}/{len(mods)} ok, worst so far {worst}")
     say(f"module-by-module worst elementwise rel err: {worst}")
-    # the whole chain in one call, from the same starting cache
+    # the whole chain in one call, from the same starting cache: against the oracle's default mode and against its
+    # bf16-operand mode (compare_caches states what each is held to)
     fb.fise_masked_unet_step(u, Wd, chain, latd, tsd, kvd, idxd, idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
     got = unpack_cache(fb, u, chain, shapes)
-    w = compare_caches(d, got, want, cache_old, idx, bt, TOL["bf16"])
-    say(f"whole chain: worst tensor {w[0]} elementwise {w[1]:.3e} relative L2 {w[2]:.3e}; "
-        f"eps L2 {rel_l2(got['eps'], want['eps']):.3e}")
+    for mode in ("f64", "bf16"):
+        ref = {k: v.copy() for k, v in cache_old.items()}
+        for mi in range(len(mods)):
+            uo.unet_step(P, d, ref, lat_new, t_sin, kv_new, idx, bt, "bf16", only={mi}, scratch=mode)
+        say(f"whole chain vs oracle with scratch={mode}: eps L2 {rel_l2(got['eps'], ref['eps']):.3e}")
+        compare_caches(d, got, ref, cache_old, idx, bt, TOL["bf16"], scratch=(mode == "bf16"), say=say)
     fb.fise_unet_destroy(u)
 
 
@@ -278,11 +292,12 @@ def test_tiny_unet_module_by_module(fb, capsys):
     def say(msg):
         with capsys.disabled():
             print(msg, flush=True)
-    # 64..256 channels: sums of a few hundred terms.  Rounding the GEMM inputs to bf16 (which any bf16
-    # MFMA path must do and the float64 oracle does not) already moves single outputs of this instance
-    # by 2.05e-2 of the metric (tests/test_oracle_unet.py::test_bf16_operand_rounding_alone shows it on
-    # the CPU), so the small instance is held to 2.5e-2; the SD-1.5 instance below to the stated 2e-2.
-    run_module_by_module(fb, uo.tiny_desc(H=32, W=32, base=64), 5010, 0.04, 8, 0.1, say, tol=2.5e-2)
+    # 64..256 channels: sums of a few hundred terms.  Rounding the GEMM inputs to bf16 (which any bf16 MFMA path must do
+    # and the float64 oracle's default mode does not) already moves single outputs of this instance by 2.05e-2 of the
+    # metric (tests/test_oracle_unet.py::test_bf16_operand_rounding_alone shows it on the CPU), so the small instance
+    # is teacher-forced against the oracle's bf16-operand mode, at the stated 2e-2; the SD-1.5 instance below is
+    # teacher-forced against the default mode at the same 2e-2.
+    run_module_by_module(fb, uo.tiny_desc(H=32, W=32, base=64), 5010, 0.04, 8, 0.1, say, scratch="bf16")
 
 
 def test_sd15_unet_module_by_module(fb, capsys):
