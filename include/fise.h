@@ -135,6 +135,20 @@ size_t fise_groupnorm_stats_workspace_bytes(int B, int H, int W, int C);
 int fise_groupnorm_stats(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1,
                          int G, float eps, float* mean, float* rstd, void* workspace, void* stream);
 
+/* fise_groupnorm_stats for callers that cannot allocate or pass a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments without `workspace`, same kernels, same results bit for bit.  The
+ * per-chunk partial sums go to a fixed array in device memory owned by the library
+ * (fise_groupnorm_stats_static_capacity_bytes() = 1 MiB per GPU, held until the
+ * process ends); its device address is looked up once per GPU on the first call
+ * there.  Calls need B * ceil(H*W / 64) * G * 16 bytes of it and return
+ * FISE_ERR_CAPACITY beyond that (nothing is launched).  The entry point allocates
+ * and frees nothing.  All calls on one GPU share the array: calls that may overlap
+ * in time on one GPU (different streams) race and must be ordered by the caller. */
+size_t fise_groupnorm_stats_static_capacity_bytes(void);
+int fise_groupnorm_stats_static(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1,
+                                int G, float eps, float* mean, float* rstd, void* stream);
+
 /* y = SiLU((x - mean[b,g]) * rstd[b,g] * gamma[c] + beta[c]) at active pixels,
  * with the GIVEN statistics; other positions of y_cache keep their value. */
 int fise_masked_groupnorm_silu(const void* x, const float* mean, const float* rstd, const void* gamma,

@@ -76,6 +76,8 @@ _SIGS = {
     "fise_mask_from_pixels_rect": (i32, [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp]),
     "fise_groupnorm_stats_workspace_bytes": (sz, [i32, i32, i32, i32]),
     "fise_groupnorm_stats": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]),
+    "fise_groupnorm_stats_static_capacity_bytes": (sz, []),
+    "fise_groupnorm_stats_static": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp]),
     "fise_masked_groupnorm_silu": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp]),
     "fise_masked_conv_workspace_bytes": (sz, [C.POINTER(fise_conv_args)]),
     "fise_masked_conv": (i32, [C.POINTER(fise_conv_args), vp, sz, vp]),
@@ -227,6 +229,16 @@ def fise_groupnorm_stats(x, x1, G, eps, mean, rstd, workspace, stream=None):
     C1 = 0 if x1 is None else x1.shape[-1]
     _ck(lib().fise_groupnorm_stats(_p(x), _p(x1), _dt(x), B, H, W, C0, C1, G, eps, _p(mean), _p(rstd), _p(workspace),
                                    _stream(stream)))
+
+
+def fise_groupnorm_stats_static_capacity_bytes():
+    return lib().fise_groupnorm_stats_static_capacity_bytes()
+
+
+def fise_groupnorm_stats_static(x, x1, G, eps, mean, rstd, stream=None):
+    B, H, W, C0 = x.shape
+    C1 = 0 if x1 is None else x1.shape[-1]
+    _ck(lib().fise_groupnorm_stats_static(_p(x), _p(x1), _dt(x), B, H, W, C0, C1, G, eps, _p(mean), _p(rstd), _stream(stream)))
 
 
 def fise_masked_groupnorm_silu(x, mean, rstd, gamma, beta, G, tile_idx, n_active, tile, y_cache, stream=None):

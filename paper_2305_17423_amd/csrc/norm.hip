@@ -2,6 +2,7 @@
 // masked GroupNorm+SiLU with given statistics, per-row LayerNorm of compact
 // token buffers.
 #include <algorithm>
+#include <mutex>
 #include "igemm.h"
 
 namespace fise {
@@ -321,18 +322,13 @@ extern "C" size_t fise_groupnorm_stats_workspace_bytes(int B, int H, int W, int 
     return align256((size_t)B * ceil_div(H * W, GS_PIX) * (size_t)(C > 0 ? C : 1) * sizeof(double2));
 }
 
-extern "C" int fise_groupnorm_stats(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
-                                    float eps, float* mean, float* rstd, void* workspace, void* stream) {
-    if (!x || !mean || !rstd || !workspace) return fail(FISE_ERR_NULL, "fise_groupnorm_stats: null pointer");
-    if (dtype != FISE_F32 && dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_groupnorm_stats: dtype %d", dtype);
-    if (C1 < 0 || (C1 > 0 && !x1)) return fail(FISE_ERR_NULL, "fise_groupnorm_stats: second source missing");
+// Both entry points below: argument checks, then the two launches with the partial sums in `partial`.
+static int gn_stats_run(const char* fn, const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
+                        float eps, float* mean, float* rstd, double2* partial, hipStream_t st) {
     const int C = C0 + C1;
-    if (B < 1 || H < 1 || W < 1 || C0 < 1 || G < 1 || C % G) return fail(FISE_ERR_SHAPE, "fise_groupnorm_stats: B%d H%d W%d C%d G%d", B, H, W, C, G);
     const int HW = H * W, nchunk = ceil_div(HW, GS_PIX);
     const size_t shmem = (size_t)C * sizeof(double2);
-    if (shmem > 64 * 1024) return fail(FISE_ERR_SHAPE, "fise_groupnorm_stats: C=%d too large", C);
-    double2* partial = (double2*)workspace;
-    hipStream_t st = as_stream(stream);
+    if (shmem > 64 * 1024) return fail(FISE_ERR_SHAPE, "%s: C=%d too large", fn, C);
     if (dtype == FISE_F32)
         hipLaunchKernelGGL(gn_partial_kernel<float>, dim3(nchunk, B), dim3(256), shmem, st, (const float*)x, (const float*)x1, HW, C0, C1, G, partial);
     else
@@ -342,6 +338,66 @@ extern "C" int fise_groupnorm_stats(const void* x, const void* x1, int dtype, in
                        (double)HW * (C / G), eps, mean, rstd);
     FISE_CHECK_LAUNCH("fise_groupnorm_stats(finish)");
     return FISE_OK;
+}
+
+static int gn_stats_check(const char* fn, const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
+                          const float* mean, const float* rstd) {
+    if (!x || !mean || !rstd) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    if (dtype != FISE_F32 && dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "%s: dtype %d", fn, dtype);
+    if (C1 < 0 || (C1 > 0 && !x1)) return fail(FISE_ERR_NULL, "%s: second source missing", fn);
+    if (B < 1 || H < 1 || W < 1 || C0 < 1 || G < 1 || (C0 + C1) % G) return fail(FISE_ERR_SHAPE, "%s: B%d H%d W%d C%d G%d", fn, B, H, W, C0 + C1, G);
+    return FISE_OK;
+}
+
+extern "C" int fise_groupnorm_stats(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
+                                    float eps, float* mean, float* rstd, void* workspace, void* stream) {
+    const char* fn = "fise_groupnorm_stats";
+    if (!workspace) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    if (int e = gn_stats_check(fn, x, x1, dtype, B, H, W, C0, C1, G, mean, rstd)) return e;
+    return gn_stats_run(fn, x, x1, dtype, B, H, W, C0, C1, G, eps, mean, rstd, (double2*)workspace, as_stream(stream));
+}
+
+// ---- the same statistics for callers that can pass no workspace: the per-chunk partial sums live in a fixed array
+// in device memory that belongs to the library (one copy per GPU, held until the process ends).
+constexpr size_t GN_STATIC_BYTES = 1u << 20;                      // 65536 (batch element, chunk, group) partial sums
+static __device__ __align__(256) unsigned char scratch[GN_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];                                 // device address of `scratch` on each GPU (null: not asked yet)
+
+// Device address of this GPU's copy of `scratch`.  In host code the array's name is only a handle: the address a
+// kernel can use comes from hipGetSymbolAddress, asked once per device with that device current.
+int static_scratch(const char* fn, void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(FISE_ERR_HIP, "%s: no current device", fn);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(FISE_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FISE_OK;
+}
+}  // namespace
+
+extern "C" size_t fise_groupnorm_stats_static_capacity_bytes(void) { return GN_STATIC_BYTES; }
+
+extern "C" int fise_groupnorm_stats_static(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
+                                           float eps, float* mean, float* rstd, void* stream) {
+    const char* fn = "fise_groupnorm_stats_static";
+    if (int e = gn_stats_check(fn, x, x1, dtype, B, H, W, C0, C1, G, mean, rstd)) return e;
+    const size_t need = (size_t)B * ceil_div(H * W, GS_PIX) * (size_t)G * sizeof(double2);
+    if (need > GN_STATIC_BYTES)
+        return fail(FISE_ERR_CAPACITY, "%s: B=%d x %d chunks of %d pixels x G=%d partial sums need %zu bytes, the fixed scratch holds %zu",
+                    fn, B, ceil_div(H * W, GS_PIX), GS_PIX, G, need, (size_t)GN_STATIC_BYTES);
+    void* partial = nullptr;
+    if (int e = static_scratch(fn, &partial)) return e;
+    // every partial sum the second launch reads is written by the first: nothing has to start at zero
+    return gn_stats_run(fn, x, x1, dtype, B, H, W, C0, C1, G, eps, mean, rstd, (double2*)partial, as_stream(stream));
 }
 
 extern "C" int fise_masked_groupnorm_silu(const void* x, const float* mean, const float* rstd, const void* gamma,
