@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 KIND_NAMES = {0: "igemm_dma_kernel<64,64,2,2,3,*>", 1: "igemm_dma_kernel<64,128,2,2,3,*> / <32,256,1,4,3,*> (GEGLU)",
               2: "attention_kernel", 3: "igemm_dma_kernel<64,128,2,4,3,*>", 4: "igemm_reduce_kernel / igemm_reduce_ln_kernel",
               5: "igemm_dma_kernel<32,128,1,4,3,*>", 6: "igemm_kernel<...> (GroupNorm prologue)", 7: "attention_merge_kernel",
-              8: "(empty bracket)"}
+              8: "(empty bracket)", 9: "igemm_wsk_kernel<32|64,NW,3>"}
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this bench on the
 # headline workload, scaled by what the same counters read for a plain copy of known size; see profiles/.
 PMC_TRAFFIC_BYTES_PER_LAUNCH = {       # (FETCH_SIZE KiB x 2.0 copy factor + WRITE_SIZE KiB x 1.0) x 1024

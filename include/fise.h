@@ -391,6 +391,7 @@ int fise_masked_attention_restricted(const void* x, const void* ln_gamma, const 
  *   4 split-K reduce launches           5 gathered GEMM, 32x128 tiles (<= 32 rows)
  *   6 gathered GEMM with the GroupNorm prologue / 32-wide K steps
  *   7 attention merge launches          8 empty brackets (fise_profile_calibrate)
+ *   9 wave-split GEMM (per-token products, K split inside the workgroup)
  * kind = -1 clears the log.  fise_profile_calibrate records n brackets with no
  * launch inside on `stream`: their average is what a bracket itself adds to every
  * figure above.  All pointers host.  Not thread safe.

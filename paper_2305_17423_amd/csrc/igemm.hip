@@ -858,6 +858,210 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN >= 8 ? 4 : 1)) void igem
 #endif
 }
 
+// ---------------------------------------------------------------------------
+// Wave-split form for the per-token products (1x1 convolutions and linears: one source, no taps).
+// One workgroup owns a 32 x BN output tile.  Its NW waves split the K range between them, and each wave runs
+// the LDS-direct K loop of igemm_dma_kernel on its own share with a ring of its own: a wave waits only for its
+// own loads, there is no barrier in the loop.  The NW partial tiles are then summed through LDS in wave order
+// (fixed, so the result is deterministic) and the epilogue runs on the sum.  The K split that keeps many memory
+// requests in flight for a few-row problem thus ends inside the launch: no parked partials in HBM, no second launch.
+// ---------------------------------------------------------------------------
+template <int BN, int NW, int NST>
+__global__ __launch_bounds__(64 * NW) void igemm_wsk_kernel(const IgemmArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" ::"s"(a.a0), "s"(a.C0), "s"(a.a_compact), "s"(a.Hin), "s"(a.Win), "s"(a.tile_idx), "s"(a.tile), "s"(a.tile_w),
+                 "s"(a.tiles_w), "s"(a.Ho), "s"(a.Wo), "s"(a.B), "s"(a.Ma), "s"(a.w), "s"(a.N), "s"(a.K), "s"(a.geglu), "s"(a.gx), "s"(a.gy));
+    asm volatile("" ::"s"(a.bias), "s"(a.bias2), "s"(a.temb), "s"(a.temb_stride), "s"(a.res), "s"(a.res_compact), "s"(a.sect_n),
+                 "s"(a.out[0]), "s"(a.out[1]), "s"(a.out[2]), "s"(a.out_mode[0]), "s"(a.out_mode[1]), "s"(a.out_mode[2]),
+                 "s"(a.mirror), "s"(a.need_pix));
+    constexpr int BM = 32, NT = 64 * NW, TN = BN / 32;
+    constexpr int AL = BM / 8, BL = BN / 8;             // 16-byte load slots per lane and K step (a load fills 8 tile rows)
+    constexpr int STAGE = (BM + BN) * 128;              // bytes
+    constexpr int PITCH = BN + 4;                       // floats per row of a parked partial tile
+    constexpr unsigned OOB = 0x80000000u;
+    constexpr int SRD_FLAGS = 0x00020000;
+    static_assert(NW * NST * STAGE >= NW * BM * PITCH * 4, "the partial tiles reuse the operand rings");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char ring[];      // [NW][NST][STAGE]
+    __shared__ RowInfo rinfo[BM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rows = a.B * a.Ma;
+    int bx, by;                                         // XCD-aware order, row tiles fastest: see igemm_kernel
+    {
+        const int total = a.gx * a.gy, chunk = total >> 3;
+        int w = blockIdx.x;
+        if (w < (chunk << 3)) w = (w & 7) * chunk + (w >> 3);
+        bx = w % a.gx; by = w / a.gx;
+    }
+    const int m0 = bx * BM;
+    // pixel coordinates are needed only to gather rows from a map or to scatter into one; compact rows in, compact
+    // rows out (most per-token products) skip the table
+    const bool use_table = a.need_pix || !a.a_compact;
+    if (use_table) build_row_table<BM, NT>(a, m0, rows, rinfo, tid);
+    const int nsteps = a.K / 64;
+    const int per = (nsteps + NW - 1) / NW;
+    const int kc_begin = wave * per, kc_end = min(nsteps, kc_begin + per);
+    if (use_table) __syncthreads();
+
+    const unsigned npix_in = a.a_compact ? (unsigned)rows : (unsigned)(a.B * a.Hin * a.Win);
+    const __amdgpu_buffer_rsrc_t srd_a = __builtin_amdgcn_make_buffer_rsrc((void*)a.a0, 0, (int)(npix_in * (unsigned)a.C0 * 2u), SRD_FLAGS);
+    const unsigned wrows = (unsigned)(a.geglu ? 2 * a.N : a.N);
+    const __amdgpu_buffer_rsrc_t srd_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(wrows * (unsigned)a.K * 2u), SRD_FLAGS);
+
+    const int lr = lane >> 3;
+    unsigned va[AL], vb[BL];
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+        const int r = j * 8 + lr;
+        unsigned row = (unsigned)(m0 + r);
+        if (!a.a_compact) { const RowInfo ri = rinfo[r]; row = (unsigned)((ri.b * a.Hin + ri.y) * a.Win + ri.x); }
+        va[j] = m0 + r < rows ? row * (unsigned)a.C0 * 2u + (unsigned)(((lane & 7) ^ ((r >> 1) & 7)) * 16) : OOB;
+    }
+#pragma unroll
+    for (int j = 0; j < BL; ++j) {
+        const int r = j * 8 + lr;
+        const int wr = weight_row<BN, BN>(a, by, r);
+        vb[j] = wr >= 0 ? (unsigned)wr * (unsigned)a.K * 2u + (unsigned)(((lane & 7) ^ ((r >> 1) & 7)) * 16) : OOB;
+    }
+    // ---- this thread's share of the epilogue (four consecutive columns of one row per item): everything it has to
+    // fetch (biases, time projection, residual) is requested here, before the K loop, and has long arrived when the
+    // sums are ready.  (The residual may be the output itself, updated in place: each element is read and written
+    // by this thread only.)
+    const bool geglu = a.geglu != 0;
+    const int OW = geglu ? BN / 2 : BN;                 // output columns of the tile
+    const int cshift = geglu ? __builtin_ctz(BN / 8) : __builtin_ctz(BN / 4);   // log2 of the four-column chunks per row
+    constexpr int ITEMS = (BM * BN / 4 + NT - 1) / NT;
+    int e_r[ITEMS], e_c[ITEMS]; bool e_ok[ITEMS]; OutPos e_pos[ITEMS];
+    u32x2_t e_bias[ITEMS], e_bias2[ITEMS], e_gate[ITEMS], e_res16[ITEMS]; f32x4v_t e_res32[ITEMS], e_temb[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int item = tid + it * NT;
+        const int r = item >> cshift, c = (item - (r << cshift)) * 4;
+        const int gm = m0 + r, col = by * OW + c;
+        e_r[it] = r; e_c[it] = c;
+        e_ok[it] = r < BM && gm < rows && col < a.N;
+        e_bias[it] = e_bias2[it] = e_gate[it] = e_res16[it] = u32x2_t{0u, 0u};
+        e_res32[it] = e_temb[it] = f32x4v_t{0.f, 0.f, 0.f, 0.f};
+        e_pos[it] = OutPos{0, 0u, 0u};
+        if (!e_ok[it]) continue;
+        if (use_table) { const RowInfo ri = rinfo[r]; e_pos[it] = out_pos(a, ri.b, ri.y, ri.x); }
+        else e_pos[it].b = gm / a.Ma;
+        if (a.bias) e_bias[it] = *as_global(reinterpret_cast<const u32x2_t*>(a.bias + col));
+        if (a.bias2) e_bias2[it] = *as_global(reinterpret_cast<const u32x2_t*>(a.bias2 + col));
+        if (geglu && a.bias) e_gate[it] = *as_global(reinterpret_cast<const u32x2_t*>(a.bias + col + a.N));
+        if (a.temb) e_temb[it] = *as_global(reinterpret_cast<const f32x4v_t*>(a.temb + (size_t)e_pos[it].b * a.temb_stride + col));
+        if (a.res) {
+            if (a.res_compact == 2) e_res32[it] = *as_global(reinterpret_cast<const f32x4v_t*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col));
+            else e_res16[it] = *as_global(reinterpret_cast<const u32x2_t*>(a.res + (a.res_compact ? (size_t)gm : (size_t)e_pos[it].pix) * a.N + col));
+        }
+    }
+
+    unsigned soff = (unsigned)kc_begin * 128u;
+    int kc_next = kc_begin;
+    unsigned char* const my_ring = ring + wave * (NST * STAGE);
+    auto issue = [&](int st) {
+        const bool live = kc_next < kc_end;
+        unsigned char* base = my_ring + st * STAGE;
+#pragma unroll
+        for (int j = 0; j < AL; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(srd_a, (__attribute__((address_space(3))) void*)(base + j * 1024), 16,
+                                                     live ? va[j] : OOB, soff, 0, 0);
+#pragma unroll
+        for (int j = 0; j < BL; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(srd_w, (__attribute__((address_space(3))) void*)(base + (BM + j * 8) * 128), 16,
+                                                     live ? vb[j] : OOB, soff, 0, 0);
+        if (live) { ++kc_next; soff += 128u; }
+    };
+
+    unsigned rda[4], rdb[TN][4];
+    {
+        const int r = lane & 31, t = (lane >> 5) ^ ((r >> 1) & 7);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) rda[ks] = (unsigned)(r * 128 + (((ks * 2) ^ t) * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int r = j * 32 + (lane & 31), t = (lane >> 5) ^ ((r >> 1) & 7);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) rdb[j][ks] = (unsigned)((BM + r) * 128 + (((ks * 2) ^ t) * 16));
+    }
+    f32x16_t acc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s);
+    for (int kc0 = kc_begin; kc0 < kc_end; kc0 += NST) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            if (kc0 + s >= kc_end) break;               // uniform across the wave
+            // this wave's own loads of the step have landed (a wave reads only what it fetched itself)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * (AL + BL)) : "memory");
+            const unsigned char* stage = my_ring + s * STAGE;
+            bf16x8_t fa[4], fb[4][TN];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                fa[ks] = *reinterpret_cast<const bf16x8_t*>(stage + rda[ks]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8_t*>(stage + rdb[j][ks]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue((s + NST - 1) % NST);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fb[ks][j], acc[j], 0, 0, 0);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the trailing out-of-range loads still target the ring
+    __syncthreads();                                    // every wave has left its ring
+    float* const part = reinterpret_cast<float*>(ring);       // [NW][BM][PITCH]
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            part[(wave * BM + r) * PITCH + j * 32 + (lane & 31)] = acc[j][e];
+        }
+    __syncthreads();
+    // ---- sum of the partial tiles in wave order, then the epilogue on the operands fetched before the K loop
+    const OutSel osel = out_sel(a);
+    auto lo = [](unsigned w) { return __uint_as_float(w << 16); };
+    auto hi = [](unsigned w) { return __uint_as_float(w & 0xffff0000u); };
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        if (!e_ok[it]) continue;
+        const int r = e_r[it], c = e_c[it];
+        float v[4] = {0.f, 0.f, 0.f, 0.f}, g[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float4 p = *reinterpret_cast<const float4*>(&part[(w * BM + r) * PITCH + c]);
+            v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
+            if (geglu) {
+                const float4 q = *reinterpret_cast<const float4*>(&part[(w * BM + r) * PITCH + c + BN / 2]);
+                g[0] += q.x; g[1] += q.y; g[2] += q.z; g[3] += q.w;
+            }
+        }
+        // same order of additions as the other epilogues: sum, biases, (gate), then time projection + residual as one term
+        v[0] += lo(e_bias[it][0]) + lo(e_bias2[it][0]); v[1] += hi(e_bias[it][0]) + hi(e_bias2[it][0]);
+        v[2] += lo(e_bias[it][1]) + lo(e_bias2[it][1]); v[3] += hi(e_bias[it][1]) + hi(e_bias2[it][1]);
+        if (geglu) {
+            g[0] += lo(e_gate[it][0]); g[1] += hi(e_gate[it][0]); g[2] += lo(e_gate[it][1]); g[3] += hi(e_gate[it][1]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = v[q] * (0.5f * g[q] * (1.0f + erff(g[q] * 0.70710678118654752f)));
+        }
+        v[0] += e_temb[it][0] + (e_res32[it][0] + lo(e_res16[it][0])); v[1] += e_temb[it][1] + (e_res32[it][1] + hi(e_res16[it][0]));
+        v[2] += e_temb[it][2] + (e_res32[it][2] + lo(e_res16[it][1])); v[3] += e_temb[it][3] + (e_res32[it][3] + hi(e_res16[it][1]));
+        epilogue_put4(a, osel, m0 + r, e_pos[it], by * OW + c, v);
+    }
+#endif
+}
+
 // Second half of a split-K launch: one thread per four output columns sums the parked partials in
 // split order (deterministic) and applies the epilogue.  A kernel this small lives on memory round
 // trips, so everything is requested up front: the pixel of the row, then biases, time projection and
@@ -1134,6 +1338,78 @@ static int launch_cfg(const IgemmArgs& a, const IgemmWorkspace* ws, int prof_kin
     return launch_bk<BM, BN, WGM, WGN, 32>(a, ws, prof_kind, st);
 }
 
+// ---- launcher of the wave-split form
+constexpr int WSK_MAX_ROWS = 256;       // measured: beyond this the 32-row tiles re-read the operands too often and the shared-tile kernels win
+static bool wsk_enabled() {
+    static const bool on = std::getenv("FISE_NO_WSK") == nullptr;       // switch for A/B measurements
+    return on;
+}
+
+template <int BN, int NW, int NST>
+static int launch_wsk(IgemmArgs a, hipStream_t st) {
+    constexpr int lds = NW * NST * (32 + BN) * 128;
+    const int rows = a.B * a.Ma;
+    const int ncols = a.geglu ? 2 * a.N : a.N;
+    a.splits = 1; a.partial = nullptr;
+    a.gx = ceil_div(rows, 32); a.gy = ceil_div(ncols, BN);
+    if (a.tile_w <= 0) a.tile_w = a.tile;
+    a.need_pix = a.res && a.res_compact == 0;
+    for (int sct = 0; sct < a.nsect; ++sct) a.need_pix |= a.out_mode[sct] == OUT_MAP || a.out_mode[sct] == OUT_TOKENS_T;
+    // raised once per instantiation (initialisation of a function-local static is thread safe)
+    static const hipError_t attr = lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_wsk_kernel<BN, NW, NST>),
+                                                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds) : hipSuccess;
+    if (attr != hipSuccess) return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
+    const double flops = 2.0 * rows * (double)ncols * (double)a.K;
+    const double bytes = 2.0 * ((double)ncols * (double)a.K + (double)rows * a.C0 + (double)rows * a.N);
+    {
+        ProfileScope prof(PROF_IGEMM_WSK, flops, bytes, st);
+        hipLaunchKernelGGL((igemm_wsk_kernel<BN, NW, NST>), dim3((unsigned)(a.gx * a.gy)), dim3(64 * NW), lds, st, a);
+    }
+    FISE_CHECK_LAUNCH("igemm (wave-split)");
+    if (a.ln_out) {
+        if (a.nsect != 1 || a.out_mode[0] != OUT_COMPACT_F32 || a.geglu || !a.ln_gamma || !a.ln_beta)
+            return fail(FISE_ERR_SHAPE, "igemm: LayerNorm output needs one float compact section");
+        return launch_ln_rows(a.out[0], 1, rows, a.N, a.ln_gamma, a.ln_beta, a.ln_eps, a.ln_out, nullptr, 1, 1, 1, 1, 1, st);
+    }
+    return FISE_OK;
+}
+
+static bool wsk_fits(const IgemmArgs& a) {
+    if (!wsk_enabled()) return false;
+    const int rows = a.B * a.Ma;
+    if (a.pro != PRO_NONE || a.K2 != 0 || a.ksize != 1 || a.C1 != 0 || a.stride != 1 || a.ups || a.C0 % 64) return false;
+    if (rows > WSK_MAX_ROWS || a.N % 4 || a.sect_n % 4) return false;
+    constexpr size_t kLim = (size_t)1 << 31;            // 32-bit buffer offsets, top bit reserved for "no such row"
+    const size_t npix_in = a.a_compact ? (size_t)rows : (size_t)a.B * a.Hin * a.Win;
+    const size_t ncols = a.geglu ? 2 * (size_t)a.N : (size_t)a.N;
+    return npix_in * a.C0 * 2 < kLim && ncols * a.K * 2 < kLim;
+}
+
+// Waves per tile (= K shares: about four K steps per wave at least) and ring depth.  Every workgroup of the launch
+// should be resident at once (a second round of workgroups doubles the time of these short kernels), so the LDS a
+// workgroup may take is the CU's 160 KB divided by the workgroups each of the 256 CUs has to hold.
+template <int BN>
+static int launch_wsk_bn(const IgemmArgs& a, hipStream_t st) {
+    const int nsteps = a.K / 64;
+    const int rows = a.B * a.Ma, ncols = a.geglu ? 2 * a.N : a.N;
+    const int wgs = ceil_div(rows, 32) * ceil_div(ncols, BN);
+    const int budget = 160 * 1024 / std::max(1, ceil_div(wgs, 256)) - 1024;
+    int nw = nsteps <= 6 ? 1 : nsteps <= 12 ? 2 : 4;
+    auto lds = [](int w, int n) { return w * n * (32 + BN) * 128; };
+    while (nw > 1 && lds(nw, 2) > budget) nw >>= 1;
+    const int nst = lds(nw, 4) <= std::min(budget, 128 * 1024) ? 4 : lds(nw, 3) <= budget ? 3 : 2;
+#define FISE_WSK(W, S) if (nw == W && nst == S) return launch_wsk<BN, W, S>(a, st)
+    FISE_WSK(1, 4); FISE_WSK(1, 3); FISE_WSK(1, 2);
+    FISE_WSK(2, 4); FISE_WSK(2, 3); FISE_WSK(2, 2);
+    FISE_WSK(4, 4); FISE_WSK(4, 3); FISE_WSK(4, 2);
+#undef FISE_WSK
+    return fail(FISE_ERR_SHAPE, "igemm: no wave-split configuration for %d waves, %d stages", nw, nst);
+}
+
+static int launch_wsk_any(const IgemmArgs& a, hipStream_t st) {
+    return a.geglu ? launch_wsk_bn<64>(a, st) : launch_wsk_bn<32>(a, st);
+}
+
 int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     const int rows = a.B * a.Ma;
     if (rows <= 0) return FISE_OK;
@@ -1145,6 +1421,7 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     if (a.nsect < 1 || a.nsect > 3 || a.nsect * a.sect_n != a.N) return fail(FISE_ERR_SHAPE, "igemm: sections");
     if (a.K2 != a.S0 + a.S1 || a.S0 % 32 || a.S1 % 32 || (a.K2 > 0 && (!a.w2 || !a.s0 || a.a_compact || a.stride != 1 || a.ups)))
         return fail(FISE_ERR_SHAPE, "igemm: side product");
+    if (wsk_fits(a)) return launch_wsk_any(a, st);
     const bool wide = rows >= 4096 && a.N >= 128;          // dense-sized problems: 64x128 tiles, 8 waves
     if (a.geglu) {
         if (rows <= 32) return launch_cfg<32, 256, 1, 4>(a, ws, PROF_IGEMM_GEGLU, st);

@@ -15,7 +15,8 @@ enum { PROF_IGEMM = 0,          // LDS-direct gathered GEMM, 64x64 tiles
        PROF_IGEMM_STAGED = 6,   // register-staged gathered GEMM (GroupNorm prologue, 32-wide K steps)
        PROF_ATTENTION_MERGE = 7,
        PROF_EMPTY = 8,          // nothing between the two events: the bracket's own cost
-       PROF_KINDS = 9 };
+       PROF_IGEMM_WSK = 9,      // wave-split gathered GEMM (per-token products, 32-row tiles, K split inside the workgroup)
+       PROF_KINDS = 10 };
 
 extern bool g_profile_on;
 void profile_begin(int kind, double flops, double bytes, hipStream_t st);
