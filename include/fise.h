@@ -320,8 +320,12 @@ int fise_unet_create(const fise_unet_desc* desc /* host */, fise_unet** out /* h
 void fise_unet_destroy(fise_unet* u);
 
 /* Flat buffers.  `kind` 0 = weights (bf16 elements; offset/numel in elements),
- * 1 = per-step cache (offset/numel in BYTES; maps bf16, statistics float),
- * 2 = context K/V buffer (bytes).  Tensor names follow the module walk
+ * 1 = per-step cache, the tensors the method stores (offset/numel in BYTES; maps
+ * bf16, statistics float), 2 = context K/V buffer (bytes), 3 = per-step cache, the
+ * DERIVED tensors kept behind the stored ones in the same buffer (bytes): for every
+ * GroupNorm its scale / shift table under the cached statistics ('<gn>.ss', float
+ * pairs [B, C]) and the normalised (ResNet: + SiLU) input map of the product that
+ * follows it ('<res>.a1', '<res>.a2', '<tr>.gx').  Tensor names follow the module walk
  * ("down.0.res.1.conv1.w", "up.2.tr.0.k", "mid.res.0.gn1.mean", "eps", ...);
  * '<tr>.v' entries hold V TRANSPOSED [B, C, H*W]. */
 int fise_unet_num_tensors(const fise_unet* u, int kind);
@@ -331,6 +335,14 @@ int64_t fise_unet_weight_elems(const fise_unet* u);
 size_t fise_unet_cache_bytes(const fise_unet* u);
 size_t fise_unet_ctxkv_bytes(const fise_unet* u);
 size_t fise_unet_workspace_bytes(const fise_unet* u, int max_active_tiles, int base_tile);
+
+/* Recomputes every derived tensor of `cache` (kind 3 above) from its stored maps and
+ * statistics: needed after stored tensors were written into the buffer by anything
+ * other than this library's own steps (a FRESH pass and every masked step keep them
+ * up to date by themselves).  workspace: fise_unet_refresh_derived_workspace_bytes(u). */
+size_t fise_unet_refresh_derived_workspace_bytes(const fise_unet* u);
+int fise_unet_refresh_derived(const fise_unet* u, const void* weights, void* cache, void* workspace,
+                              size_t workspace_bytes, void* stream);
 
 /* Context K/V of every transformer block for one conditioning ctx[B,n_ctx,ctx_dim]. */
 int fise_unet_context_kv(const fise_unet* u, const void* weights, const void* ctx, void* ctxkv,
@@ -346,7 +358,11 @@ typedef enum { FISE_STATS_CACHED = 0, FISE_STATS_FRESH = 1 } fise_stats_mode;
  *   conditioning), tile_idx/n_active on the finest level with tile edge
  *   base_tile (divisible by 2^(n_levels-1); level l uses base_tile >> l on the
  *   same tile grid).  stats_mode CACHED uses the statistics stored in `cache`;
- *   FRESH recomputes them from the updated maps and stores them.
+ *   FRESH recomputes them from the updated maps and stores them.  CACHED relies on
+ *   the derived tensors of `cache` being consistent with its stored ones (see
+ *   fise_unet_refresh_derived): each launch that rewrites a map at the active pixels
+ *   also rewrites, there, the normalised copies its consumers read, so no launch of
+ *   the step is spent on normalisation alone.
  *   level_dense (host int[n_levels], may be NULL): non-zero runs that level
  *   with the full tile list.  A dense forward is n_active = all tiles + FRESH. */
 int fise_masked_unet_step(const fise_unet* u, const void* weights, void* cache, const void* latent,

@@ -105,6 +105,8 @@ _SIGS = {
     "fise_unet_cache_bytes": (sz, [vp]),
     "fise_unet_ctxkv_bytes": (sz, [vp]),
     "fise_unet_workspace_bytes": (sz, [vp, i32, i32]),
+    "fise_unet_refresh_derived_workspace_bytes": (sz, [vp]),
+    "fise_unet_refresh_derived": (i32, [vp, vp, vp, vp, sz, vp]),
     "fise_unet_context_kv": (i32, [vp, vp, vp, vp, vp, sz, vp]),
     "fise_masked_unet_step": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), vp, sz, vp]),
     "fise_profile_enable": (i32, [i32]),
@@ -411,6 +413,15 @@ def fise_unet_ctxkv_bytes(u):
 
 def fise_unet_workspace_bytes(u, max_active_tiles, base_tile):
     return lib().fise_unet_workspace_bytes(u, max_active_tiles, base_tile)
+
+
+def fise_unet_refresh_derived_workspace_bytes(u):
+    return lib().fise_unet_refresh_derived_workspace_bytes(u)
+
+
+def fise_unet_refresh_derived(u, weights, cache, workspace, stream=None):
+    _ck(lib().fise_unet_refresh_derived(u, _p(weights), _p(cache), _p(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream(stream)))
 
 
 def fise_unet_context_kv(u, weights, ctx, ctxkv, stream=None):

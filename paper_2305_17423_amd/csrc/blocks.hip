@@ -36,10 +36,17 @@ static IgemmArgs conv_args(const void* a0, const void* a1, int C0, int C1, int B
     return g;
 }
 
+static void set_views(IgemmArgs& g, const GnView* views, int nview) {
+    g.nview = nview;
+    for (int i = 0; i < nview; ++i) g.view[i] = views[i];
+}
+
 int run_conv(const void* a0, int C0, int B, int Hin, int Win, int stride, int ups, const void* w, const void* bias, int N,
-             const int* idx, int n_active, int tile, void* out, const IgemmWorkspace* iw, hipStream_t st) {
+             const int* idx, int n_active, int tile, void* out, const IgemmWorkspace* iw, hipStream_t st, const GnView* views,
+             int nview) {
     const int Ho = ups ? 2 * Hin : Hin / stride, Wo = ups ? 2 * Win : Win / stride;
     IgemmArgs g = conv_args(a0, nullptr, C0, 0, B, Hin, Win, Ho, Wo, 3, stride, ups, w, bias, N, idx, n_active, tile, out);
+    set_views(g, views, nview);
     return launch_igemm(g, iw, st);
 }
 
@@ -55,23 +62,38 @@ size_t resnet_ws_bytes(const fise_resnet_args* a) {
     return resnet_gn_bytes(a) + resnet_act_bytes(a, a->C0 + a->C1) + resnet_act_bytes(a, a->Cout);
 }
 
-int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st) {
+// dv (may be null): where the block's activated inputs live between calls and who else wants the block's output
+// normalised.  Without it the activations go to the workspace and are recomputed by every call.
+int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st, const BlockDerived* dv) {
     const int Ci = a->C0 + a->C1, Co = a->Cout, B = a->B, H = a->H, W = a->W;
-    char* act1 = (char*)ws + resnet_gn_bytes(a);
-    char* act2 = act1 + resnet_act_bytes(a, Ci);
-    if (a->stats_fresh)
+    char* act1 = dv ? (char*)dv->act_in : (char*)ws + resnet_gn_bytes(a);
+    char* act2 = dv ? (char*)dv->act_mid : (char*)ws + resnet_gn_bytes(a) + resnet_act_bytes(a, Ci);
+    // With cached statistics and a trusted cache, the producers of x0 / x1 have already written this block's
+    // activated input at the active pixels (the ring outside them is unchanged), and conv1 writes conv2's.
+    const bool have_acts = dv && dv->trust && !a->stats_fresh;
+    if (a->stats_fresh) {
         if (int e = fise_groupnorm_stats(a->x0, a->x1, FISE_BF16, B, H, W, a->C0, a->C1, a->G, 1e-5f, a->gn1_mean, a->gn1_rstd, ws, st)) return e;
+        if (dv) if (int e = launch_gn_scale_shift(a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, B, Ci, a->G, dv->ss_in, st)) return e;
+    }
     // the normalised + activated input (active tiles and their ring) is written once, then convolved
-    if (int e = launch_gn_act_halo(a->x0, a->x1, a->C0, a->C1, B, H, W, a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, a->G, 1,
-                                   a->tile_idx, a->n_active, a->tile, act1, st)) return e;
+    if (!have_acts)
+        if (int e = launch_gn_act_halo(a->x0, a->x1, a->C0, a->C1, B, H, W, a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, a->G, 1,
+                                       a->tile_idx, a->n_active, a->tile, act1, st)) return e;
     IgemmArgs c1 = conv_args(act1, nullptr, Ci, 0, B, H, W, H, W, 3, 1, 0, a->conv1_w, a->conv1_b, Co, a->tile_idx,
                              a->n_active, a->tile, a->h1_cache);
     c1.temb = a->temb; c1.temb_stride = a->temb_stride;
+    if (dv && !a->stats_fresh) {       // conv2's input: SiLU(GN2(h1)) under the cached statistics, from conv1's epilogue
+        c1.nview = 1;
+        c1.view[0] = GnView{(bf16_t*)dv->act_mid, dv->ss_mid, Co, 0, 1, 0};
+    }
     if (int e = launch_igemm(c1, iw, st)) return e;
-    if (a->stats_fresh)
+    if (a->stats_fresh) {
         if (int e = fise_groupnorm_stats(a->h1_cache, nullptr, FISE_BF16, B, H, W, Co, 0, a->G, 1e-5f, a->gn2_mean, a->gn2_rstd, ws, st)) return e;
-    if (int e = launch_gn_act_halo(a->h1_cache, nullptr, Co, 0, B, H, W, a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, a->G, 1,
-                                   a->tile_idx, a->n_active, a->tile, act2, st)) return e;
+        if (dv) if (int e = launch_gn_scale_shift(a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, B, Co, a->G, dv->ss_mid, st)) return e;
+    }
+    if (!have_acts)
+        if (int e = launch_gn_act_halo(a->h1_cache, nullptr, Co, 0, B, H, W, a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, a->G, 1,
+                                       a->tile_idx, a->n_active, a->tile, act2, st)) return e;
     IgemmArgs c2 = conv_args(act2, nullptr, Co, 0, B, H, W, H, W, 3, 1, 0, a->conv2_w, a->conv2_b, Co, a->tile_idx,
                              a->n_active, a->tile, a->out_cache);
     if (a->sc_w) {            // 1x1 shortcut: extra K steps of the same GEMM, never stored
@@ -80,6 +102,7 @@ int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hi
     } else {
         c2.res = (const bf16_t*)a->x0;
     }
+    if (dv && !a->stats_fresh) set_views(c2, dv->out_view, dv->n_out_view);
     return launch_igemm(c2, iw, st);
 }
 
@@ -101,7 +124,7 @@ size_t transformer_ws_bytes(const fise_transformer_args* a) {
     return tr_ws(a->B, a->H, a->W, a->C, a->G, a->heads, a->n_active, a->tile).total;
 }
 
-int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st) {
+int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st, const BlockDerived* dv) {
     const int B = a->B, H = a->H, W = a->W, C = a->C, Ma = a->n_active * a->tile * a->tile;
     const TrWs wl = tr_ws(B, H, W, C, a->G, a->heads, a->n_active, a->tile);
     char* ws = (char*)workspace;
@@ -116,10 +139,18 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     };
     auto into_h = [&](IgemmArgs& g) { g.res = (const bf16_t*)hb; g.res_compact = 2; g.out[0] = (bf16_t*)hb; g.out_mode[0] = OUT_COMPACT_F32; };
 
-    if (a->stats_fresh)
+    if (a->stats_fresh) {
         if (int e = fise_groupnorm_stats(a->x, nullptr, FISE_BF16, B, H, W, C, 0, a->G, 1e-6f, a->gn_mean, a->gn_rstd, ws + wl.gn, st)) return e;
-    IgemmArgs pin = conv_args(a->x, nullptr, C, 0, B, H, W, H, W, 1, 1, 0, a->pin_w, a->pin_b, C, a->tile_idx, a->n_active, a->tile, hb);
-    set_gn(pin, a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, a->G, false);
+        if (dv) if (int e = launch_gn_scale_shift(a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, B, C, a->G, dv->ss_in, st)) return e;
+    }
+    // With a derived map the 1x1 in reads the normalised input (written by the producer of x under the cached
+    // statistics, or here); without one it normalises in its own prologue.
+    if (dv && !(dv->trust && !a->stats_fresh))
+        if (int e = launch_gn_act_halo(a->x, nullptr, C, 0, B, H, W, a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, a->G, 0,
+                                       a->tile_idx, a->n_active, a->tile, dv->act_in, st)) return e;
+    IgemmArgs pin = conv_args(dv ? dv->act_in : a->x, nullptr, C, 0, B, H, W, H, W, 1, 1, 0, a->pin_w, a->pin_b, C, a->tile_idx, a->n_active,
+                              a->tile, hb);
+    if (!dv) set_gn(pin, a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, a->G, false);
     pin.out_mode[0] = OUT_COMPACT_F32;
     // every GEMM that completes the residual stream also emits the LayerNorm the next sub-block starts with
     auto with_ln = [&](IgemmArgs& g, const void* gamma, const void* beta) {
@@ -152,6 +183,7 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     // 1x1 out + block input, scattered into the cached block output
     IgemmArgs po = lin(ws + wl.h16, C, a->pout_w, a->pout_b, C);
     po.res = (const bf16_t*)a->x; po.res_compact = 0; po.out[0] = (bf16_t*)a->out_cache; po.out_mode[0] = OUT_MAP;
+    if (dv && !a->stats_fresh) set_views(po, dv->out_view, dv->n_out_view);
     return launch_igemm(po, iw, st);
 }
 
@@ -190,7 +222,7 @@ extern "C" int fise_masked_resnet_block(const fise_resnet_args* a, void* workspa
     IgemmWorkspace iw;
     const size_t off = align256(resnet_ws_bytes(a));
     if (int e = igemm_workspace_init((char*)workspace + off, workspace_bytes - off, &iw, as_stream(stream))) return e;
-    return run_resnet(a, workspace, &iw, as_stream(stream));
+    return run_resnet(a, workspace, &iw, as_stream(stream), nullptr);
 }
 
 extern "C" size_t fise_masked_transformer_block_workspace_bytes(const fise_transformer_args* a) {
@@ -216,7 +248,7 @@ extern "C" int fise_masked_transformer_block(const fise_transformer_args* a, voi
     IgemmWorkspace iw;
     const size_t off = align256(transformer_ws_bytes(a));
     if (int e = igemm_workspace_init((char*)workspace + off, workspace_bytes - off, &iw, as_stream(stream))) return e;
-    return run_transformer(a, workspace, &iw, as_stream(stream));
+    return run_transformer(a, workspace, &iw, as_stream(stream), nullptr);
 }
 
 extern "C" size_t fise_context_kv_workspace_bytes(int B, int n_ctx, int Dc, int C) {

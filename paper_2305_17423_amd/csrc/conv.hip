@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
                                                           const T* __restrict__ gn_gamma, const T* __restrict__ gn_beta, int G,
                                                           int gn_silu, const float* __restrict__ temb, const T* residual,
                                                           const int* __restrict__ tile_idx, int Ma, int tile, int tile_w, int Ho,
-                                                          int Wo, T* y) {
+                                                          int Wo, T* y, int nview, GnView view0, GnView view1) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long total = (long long)B * Ma * Cout;
     if (i >= total) return;
@@ -54,6 +54,10 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
     const size_t o = (((size_t)b * Ho + oy) * Wo + ox) * Cout + co;
     if (residual) acc += Elem<T>::ld(residual + o);
     Elem<T>::st(y + o, acc);
+    if (nview) {                      // bf16 maps only (checked by the launcher)
+        const GnView views[2] = {view0, view1};
+        put_views1(views, nview, b, ((size_t)b * Ho + oy) * Wo + ox, co, acc);
+    }
 }
 
 // The 4-channel latent under a 3x3 kernel (the UNet's input convolution): the 36 input
@@ -62,7 +66,8 @@ __global__ __launch_bounds__(256) void conv_scalar_kernel(const T* __restrict__ 
 __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __restrict__ x, int B, int H, int W,
                                                              const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
                                                              int Cout, const float* __restrict__ temb, const bf16_t* residual,
-                                                             const int* __restrict__ tile_idx, int Ma, int tile, int tile_w, bf16_t* y) {
+                                                             const int* __restrict__ tile_idx, int Ma, int tile, int tile_w, bf16_t* y,
+                                                             int nview, GnView view0, GnView view1) {
     const int q4 = Cout >> 2;
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (long long)B * Ma * q4) return;
@@ -101,6 +106,10 @@ __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __res
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) Elem<bf16_t>::st(y + o + j, acc[j]);
+    if (nview) {
+        const GnView views[2] = {view0, view1};
+        put_views4(views, nview, b, (unsigned)(((size_t)b * H + oy) * W + ox), co, acc);
+    }
 }
 
 static int tile_cols(const fise_conv_args* a) { return a->tile_w > 0 ? a->tile_w : a->tile; }
@@ -140,16 +149,17 @@ static bool mfma_path(const fise_conv_args* a) {
 }
 
 template <typename T>
-static void launch_scalar(const fise_conv_args* a, int Ho, int Wo, hipStream_t st) {
+static void launch_scalar(const fise_conv_args* a, int Ho, int Wo, hipStream_t st, const GnView* views, int nview) {
     const int Ma = a->n_active * a->tile * tile_cols(a);
     const long long total = (long long)a->B * Ma * a->Cout;
     hipLaunchKernelGGL(conv_scalar_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a->x0,
                        (const T*)a->x1, a->C0, a->C1, a->B, a->H, a->W, (const T*)a->w, (const T*)a->bias, a->Cout, a->ksize,
                        a->stride, a->upsample ? 1 : 0, a->gn_mean, a->gn_rstd, (const T*)a->gn_gamma, (const T*)a->gn_beta,
-                       a->G, a->gn_silu, a->temb, (const T*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), Ho, Wo, (T*)a->y_cache);
+                       a->G, a->gn_silu, a->temb, (const T*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), Ho, Wo, (T*)a->y_cache,
+                       nview, nview > 0 ? views[0] : GnView{}, nview > 1 ? views[1] : GnView{});
 }
 
-int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st) {
+int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st, const GnView* views, int nview) {
     int Ho, Wo;
     if (int e = validate(a, Ho, Wo)) return e;
     if (a->n_active == 0) return FISE_OK;
@@ -160,12 +170,14 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
             const long long total = (long long)a->B * Ma * (a->Cout / 4);
             hipLaunchKernelGGL(conv_latent3x3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                                (const bf16_t*)a->x0, a->B, a->H, a->W, (const bf16_t*)a->w, (const bf16_t*)a->bias, a->Cout,
-                               a->temb, (const bf16_t*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), (bf16_t*)a->y_cache);
+                               a->temb, (const bf16_t*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), (bf16_t*)a->y_cache,
+                               nview, nview > 0 ? views[0] : GnView{}, nview > 1 ? views[1] : GnView{});
             FISE_CHECK_LAUNCH("fise_masked_conv(latent 3x3)");
             return FISE_OK;
         }
-        if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st);
-        else launch_scalar<bf16_t>(a, Ho, Wo, st);
+        if (nview && a->dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_masked_conv: normalised copies need bf16 maps");
+        if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st, nullptr, 0);
+        else launch_scalar<bf16_t>(a, Ho, Wo, st, views, nview);
         FISE_CHECK_LAUNCH("fise_masked_conv(scalar)");
         return FISE_OK;
     }
@@ -180,6 +192,8 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
     g.bias = (const bf16_t*)a->bias; g.temb = a->temb; g.temb_stride = a->Cout; g.res = (const bf16_t*)a->residual; g.res_compact = 0;
     g.nsect = 1; g.sect_n = a->Cout; g.out[0] = (bf16_t*)a->y_cache; g.out_mode[0] = OUT_MAP;
     g.splits = 1; g.partial = nullptr;
+    g.nview = nview;
+    for (int i = 0; i < nview; ++i) g.view[i] = views[i];
     IgemmWorkspace iw;
     if (int e = igemm_workspace_init(workspace, workspace_bytes, &iw, st)) return e;
     return launch_igemm(g, &iw, st);
@@ -195,7 +209,7 @@ extern "C" size_t fise_masked_conv_workspace_bytes(const fise_conv_args* a) {
 }
 
 extern "C" int fise_masked_conv(const fise_conv_args* a, void* workspace, size_t workspace_bytes, void* stream) {
-    return conv_dispatch(a, workspace, workspace_bytes, as_stream(stream));
+    return conv_dispatch(a, workspace, workspace_bytes, as_stream(stream), nullptr, 0);
 }
 
 extern "C" int fise_masked_conv3x3(const void* x, const void* w, const void* bias, int dtype, int B, int H, int W, int Cin,
@@ -209,5 +223,5 @@ extern "C" int fise_masked_conv3x3(const void* x, const void* w, const void* bia
     a.gn_mean = gn_mean; a.gn_rstd = gn_rstd; a.gn_gamma = gn_gamma; a.gn_beta = gn_beta; a.G = G; a.gn_silu = 1;
     a.temb = temb; a.residual = residual; a.tile_idx = tile_idx; a.n_active = n_active; a.tile = tile; a.y_cache = y_cache;
     a.dtype = dtype;
-    return conv_dispatch(&a, workspace, workspace_bytes, as_stream(stream));
+    return conv_dispatch(&a, workspace, workspace_bytes, as_stream(stream), nullptr, 0);
 }

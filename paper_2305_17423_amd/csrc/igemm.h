@@ -9,6 +9,12 @@ namespace fise {
 enum { PRO_NONE = 0, PRO_GN = 1, PRO_GN_SILU = 2 };
 enum { OUT_COMPACT = 0, OUT_MAP = 1, OUT_TOKENS_T = 2, OUT_COMPACT_F32 = 3 };
 
+// A second destination of a map-producing launch: the consumer's GroupNorm (+SiLU) of the value just stored,
+//   dst[pix, c_off + col] = act(x * ss[b, c_off + col].x + ss[b, c_off + col].y),   x = the bf16 value stored at (pix, col)
+// with ss the per-(batch element, channel) scale / shift table of that GroupNorm under its CACHED statistics.
+// The consumer then reads activations instead of normalising its input in a launch of its own.
+struct GnView { bf16_t* dst; const float2* ss; int dstC, c_off, silu, pad_; };
+
 struct IgemmArgs {
     // ---- A operand: rows = B * Ma active pixels (or compact rows) x K
     const bf16_t* a0; const bf16_t* a1; int C0, C1;    // map sources [B,Hin,Win,C*] (a1 unused when C1 == 0)
@@ -37,7 +43,58 @@ struct IgemmArgs {
     int splits; float* partial;
     int gx, gy;                                         // tile grid (row tiles, column tiles); set by the launcher
     int need_pix;                                       // set by the launcher: the epilogue addresses a map (else rows only)
+    // ---- optional normalised copies of the output map for its consumers (one OUT_MAP section, N % 4 == 0)
+    int nview; GnView view[2];
 };
+
+// What a block of the UNet step keeps in the per-step cache besides its stored maps (all derived from them and from
+// the cached statistics): the activated input of its first product (ResNet: SiLU(GN1(x)); transformer: GN(x)), for a
+// ResNet also conv2's activated input SiLU(GN2(h1)), the scale / shift tables of those GroupNorms, and the
+// normalised copies other blocks want of this block's output.  trust: the derived maps are up to date with the
+// stored maps except where this step's producers have just rewritten them (so consumers need not recompute them).
+struct BlockDerived {
+    void* act_in; void* act_mid; float2* ss_in; float2* ss_mid; int trust;
+    GnView out_view[2]; int n_out_view;
+};
+
+#if defined(__HIPCC__)
+// Four consecutive channels col .. col + 3 of pixel `pix` (batch element b): every view gets its activation.
+__device__ __forceinline__ void put_views4(const GnView* view, int nview, int b, unsigned pix, int col, const float (&v)[4]) {
+    typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    const unsigned p01 = f2bf2(v[0], v[1]), p23 = f2bf2(v[2], v[3]);      // the values as stored
+    const float x[4] = {__uint_as_float(p01 << 16), __uint_as_float(p01 & 0xffff0000u), __uint_as_float(p23 << 16),
+                        __uint_as_float(p23 & 0xffff0000u)};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        if (i >= nview) break;
+        const GnView w = view[i];
+        const int c = w.c_off + col;
+        auto sp = (const __attribute__((address_space(1))) f32x4v*)(w.ss + (size_t)b * w.dstC + c);
+        const f32x4v s01 = sp[0], s23 = sp[1];
+        float u[4] = {fmaf(x[0], s01[0], s01[1]), fmaf(x[1], s01[2], s01[3]), fmaf(x[2], s23[0], s23[1]), fmaf(x[3], s23[2], s23[3])};
+        if (w.silu) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) u[q] = silu_f(u[q]);
+        }
+        auto dp = (__attribute__((address_space(1))) u32x2v*)(w.dst + (size_t)pix * w.dstC + c);
+        *dp = u32x2v{f2bf2(u[0], u[1]), f2bf2(u[2], u[3])};
+    }
+}
+// One channel (the element-wise epilogue of the register-staged kernel).
+__device__ __forceinline__ void put_views1(const GnView* view, int nview, int b, size_t pix, int col, float v) {
+    const float x = bf2f(f2bf(v));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        if (i >= nview) break;
+        const GnView w = view[i];
+        const float2 s = w.ss[(size_t)b * w.dstC + w.c_off + col];
+        float u = fmaf(x, s.x, s.y);
+        if (w.silu) u = silu_f(u);
+        w.dst[pix * w.dstC + w.c_off + col] = f2bf(u);
+    }
+}
+#endif
 
 // Scratch of the launcher: GroupNorm (scale, shift) table and the parked partial sums of split-K launches.
 constexpr size_t IGEMM_PARTIAL_BYTES = 32u << 20;
@@ -53,11 +110,15 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st);
 // in_f32 != 0: compact float rows (tile_idx must be nullptr).
 int launch_ln_rows(const void* in, int in_f32, int rows, int C, const void* gamma, const void* beta, float eps, void* out,
                    const int* tile_idx, int tile, int tiles_w, int H, int W, int Ma, hipStream_t st);
-int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st);
+// views / nview: normalised copies of the output map for its consumers (nullptr / 0 = none)
+int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_bytes, hipStream_t st, const GnView* views, int nview);
 // out[b, n] = act(bias[n] + sum_k in[b, k] * W[n, k]) for a handful of rows b (float in/out, bf16 weights).
 int launch_small_linear(const float* in, int B, int K, const void* W, const void* bias, int N, int silu_out, float* out,
                         hipStream_t st);
 int launch_iota(int* p, int n, hipStream_t st);
+// ss[B, C] = (rstd * gamma, beta - mean * rstd * gamma): the scale / shift form of a GroupNorm with given statistics.
+int launch_gn_scale_shift(const float* mean, const float* rstd, const void* gamma, const void* beta, int B, int C, int G, float2* ss,
+                          hipStream_t st);
 // act[B,H,W,C0+C1] = GroupNorm(x0|x1) (+SiLU) with the given statistics at the active tiles and their one-pixel ring.
 int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, int H, int W, const float* mean, const float* rstd,
                        const void* gamma, const void* beta, int G, int silu, const int* tile_idx, int n_active, int tile, void* act,

@@ -130,6 +130,7 @@ __device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& 
         *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)gm * o.sect_n + scol)) = packed;
     } else {
         *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)p.pix * o.sect_n + scol)) = packed;
+        if (a.nview) put_views4(a.view, a.nview, p.b, p.pix, scol, v);
     }
 }
 
@@ -289,6 +290,7 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                 const size_t e4 = ((out_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it])) * a.N + colv[it]) >> 2;
                 if (out_f32) dst32[e4] = f32x4v_t{v0, v1, v2, v3};
                 if (put16) dst16[e4] = u32x2_t{f2bf2(v0, v1), f2bf2(v2, v3)};
+                if (out_map && a.nview) { const float vv[4] = {v0, v1, v2, v3}; put_views4(a.view, a.nview, pos[it].b, pos[it].pix, colv[it], vv); }
             }
             return;
         }
@@ -354,7 +356,9 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                 } else if (omode == OUT_COMPACT) {
                     as_global(outp)[gm * a.sect_n + scol] = f2bf(v);
                 } else if (omode == OUT_MAP) {
-                    as_global(outp)[(((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x) * a.sect_n + scol] = f2bf(v);
+                    const size_t pix = ((size_t)ri.b * a.Ho + ri.y) * a.Wo + ri.x;
+                    as_global(outp)[pix * a.sect_n + scol] = f2bf(v);
+                    if (a.nview) put_views1(a.view, a.nview, ri.b, pix, scol, v);
                 } else {
                     as_global(outp)[((size_t)ri.b * a.sect_n + scol) * HW + (size_t)ri.y * a.Wo + ri.x] = f2bf(v);
                 }
@@ -1421,6 +1425,11 @@ int launch_igemm(const IgemmArgs& a, const IgemmWorkspace* ws, hipStream_t st) {
     if (a.nsect < 1 || a.nsect > 3 || a.nsect * a.sect_n != a.N) return fail(FISE_ERR_SHAPE, "igemm: sections");
     if (a.K2 != a.S0 + a.S1 || a.S0 % 32 || a.S1 % 32 || (a.K2 > 0 && (!a.w2 || !a.s0 || a.a_compact || a.stride != 1 || a.ups)))
         return fail(FISE_ERR_SHAPE, "igemm: side product");
+    if (a.nview < 0 || a.nview > 2 || (a.nview > 0 && (a.nsect != 1 || a.out_mode[0] != OUT_MAP || a.N % 4 || a.geglu)))
+        return fail(FISE_ERR_SHAPE, "igemm: normalised copies need one map section with N %% 4 == 0");
+    for (int i = 0; i < a.nview; ++i)
+        if (!a.view[i].dst || !a.view[i].ss || a.view[i].dstC % 4 || a.view[i].c_off % 4 || a.view[i].c_off + a.N > a.view[i].dstC)
+            return fail(FISE_ERR_SHAPE, "igemm: normalised copy %d: channels %d + %d of %d", i, a.view[i].c_off, a.N, a.view[i].dstC);
     if (wsk_fits(a)) return launch_wsk_any(a, st);
     const bool wide = rows >= 4096 && a.N >= 128;          // dense-sized problems: 64x128 tiles, 8 waves
     if (a.geglu) {

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void gn_act_halo_kernel(const bf16_t* __restri
                 const float ga = q ? __uint_as_float(gw[e] & 0xffff0000u) : __uint_as_float(gw[e] << 16);
                 const float be = q ? __uint_as_float(bw[e] & 0xffff0000u) : __uint_as_float(bw[e] << 16);
                 const float sc = rs * ga;
-                float u = xv * sc + (be - mu * sc);
+                float u = fmaf(xv, sc, fmaf(-mu, sc, be));      // the same two operations as the scale / shift table form
                 if (silu) u = silu_f(u);
                 r[q] = u;
             }
@@ -132,6 +132,23 @@ __global__ __launch_bounds__(256) void gn_act_halo_kernel(const bf16_t* __restri
         }
         *reinterpret_cast<uint4*>(act + pix * C + c) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     }
+}
+
+__global__ void gn_scale_shift_kernel(const float* __restrict__ mean, const float* __restrict__ rstd, const bf16_t* __restrict__ gamma,
+                                      const bf16_t* __restrict__ beta, int B, int C, int G, float2* __restrict__ ss) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * C) return;
+    const int b = i / C, c = i - b * C, g = c / (C / G);
+    const float sc = rstd[b * G + g] * bf2f(gamma[c]);
+    ss[i] = make_float2(sc, fmaf(-mean[b * G + g], sc, bf2f(beta[c])));
+}
+
+int launch_gn_scale_shift(const float* mean, const float* rstd, const void* gamma, const void* beta, int B, int C, int G, float2* ss,
+                          hipStream_t st) {
+    hipLaunchKernelGGL(gn_scale_shift_kernel, dim3(ceil_div(B * C, 256)), dim3(256), 0, st, mean, rstd, (const bf16_t*)gamma,
+                       (const bf16_t*)beta, B, C, G, ss);
+    FISE_CHECK_LAUNCH("gn scale/shift table");
+    return FISE_OK;
 }
 
 int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, int H, int W, const float* mean, const float* rstd,

@@ -11,9 +11,10 @@
 namespace fise {
 IgemmArgs linear_args(const void* A, int rows_per_b, int B, int Cin, const void* W, const void* bias, int N);
 int run_conv(const void* a0, int C0, int B, int Hin, int Win, int stride, int ups, const void* w, const void* bias, int N,
-             const int* idx, int n_active, int tile, void* out, const IgemmWorkspace* iw, hipStream_t st);
-int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st);
-int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st);
+             const int* idx, int n_active, int tile, void* out, const IgemmWorkspace* iw, hipStream_t st, const GnView* views,
+             int nview);
+int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hipStream_t st, const BlockDerived* dv);
+int run_transformer(const fise_transformer_args* a, void* workspace, const IgemmWorkspace* iw, hipStream_t st, const BlockDerived* dv);
 size_t resnet_ws_bytes(const fise_resnet_args* a);
 size_t transformer_ws_bytes(const fise_transformer_args* a);
 }
@@ -23,18 +24,22 @@ using namespace fise;
 namespace {
 struct Tensor { std::string name; int64_t off; int64_t numel; };
 enum Kind { K_CONV_IN, K_RES, K_TR, K_DS, K_US, K_OUT };
+// A consumer of a module's output map that normalises it first: consumer module, and whether the map is the
+// consumer's skip source (second part of the channel concatenation).
+struct ViewSpec { int consumer; bool as_skip; };
 struct Module {
     Kind kind; std::string name; int lvl; int cin, cskip, cout;   // tr/ds/us: cin == cout == c
     std::string in_map, skip_map;                                 // cache tensors read ("" = latent)
     int temb_off;                                                 // column offset in the stacked time projection
+    std::vector<ViewSpec> views;                                  // who wants this module's output normalised
 };
 }  // namespace
 
 struct fise_unet {
     fise_unet_desc d;
     std::vector<Module> mods;
-    std::vector<Tensor> tensors[3];
-    std::map<std::string, int> index[3];
+    std::vector<Tensor> tensors[4];                  // 0 weights, 1 stored cache tensors, 2 context K/V, 3 derived cache tensors
+    std::map<std::string, int> index[4];
     int64_t weight_elems = 0; size_t cache_bytes = 0, ctxkv_bytes = 0;
     int temb_total = 0, n_stride = 0;
 
@@ -156,7 +161,29 @@ static void build_plan(fise_unet* u) {
         case K_OUT: stat("gn"); u->add(1, "eps", B * hw * m.cout * 2, cc, 256); break;
         }
     }
+    // ---- derived tensors, in the same buffer behind the stored ones (bytes): what the masked step would otherwise
+    // recompute from stored maps + cached statistics at every call.  ResNet: activated inputs of both convolutions
+    // and the scale / shift tables of both GroupNorms; transformer: the normalised input of the 1x1 in and its table.
+    for (const Module& m : mods) {
+        const std::string& n = m.name;
+        const int64_t hw = (int64_t)(d.H >> m.lvl) * (d.W >> m.lvl), ci = m.cin + m.cskip;
+        if (m.kind == K_RES) {
+            u->add(3, n + ".a1", B * hw * ci * 2, cc, 256); u->add(3, n + ".a2", B * hw * m.cout * 2, cc, 256);
+            u->add(3, n + ".gn1.ss", B * ci * 8, cc, 256);  u->add(3, n + ".gn2.ss", B * m.cout * 8, cc, 256);
+        } else if (m.kind == K_TR) {
+            u->add(3, n + ".gx", B * hw * m.cout * 2, cc, 256); u->add(3, n + ".gn.ss", B * m.cout * 8, cc, 256);
+        }
+    }
     u->cache_bytes = (size_t)((cc + 255) / 256 * 256);
+    // ---- who normalises whose output
+    std::map<std::string, int> producer;
+    for (int i = 0; i < (int)mods.size(); ++i) producer[mods[i].kind == K_OUT ? std::string("eps") : mods[i].name + ".out"] = i;
+    for (int i = 0; i < (int)mods.size(); ++i) {
+        const Module& m = mods[i];
+        if (m.kind != K_RES && m.kind != K_TR) continue;
+        if (!m.in_map.empty()) mods[producer.at(m.in_map)].views.push_back({i, false});
+        if (!m.skip_map.empty()) mods[producer.at(m.skip_map)].views.push_back({i, true});
+    }
 
     // ---- context K/V (bytes): per transformer block K[B,n_ctx,C], Vt[B,C,n_stride]
     u->n_stride = (d.n_ctx + 7) / 8 * 8;
@@ -190,8 +217,10 @@ extern "C" int fise_unet_create(const fise_unet_desc* desc, fise_unet** out) {
     fise_unet* u = new fise_unet();
     u->d = d;
     build_plan(u);
-    for (const Module& m : u->mods)
+    for (const Module& m : u->mods) {
         if (m.kind == K_RES && (m.cin + m.cskip) % d.groups) { delete u; return fail(FISE_ERR_SHAPE, "fise_unet_create: %s input width %d %% groups", m.name.c_str(), m.cin + m.cskip); }
+        if (m.views.size() > 2) { delete u; return fail(FISE_ERR_SHAPE, "fise_unet_create: %s feeds %zu normalising consumers", m.name.c_str(), m.views.size()); }
+    }
     *out = u;
     return FISE_OK;
 }
@@ -199,13 +228,13 @@ extern "C" int fise_unet_create(const fise_unet_desc* desc, fise_unet** out) {
 extern "C" void fise_unet_destroy(fise_unet* u) { delete u; }
 
 extern "C" int fise_unet_num_tensors(const fise_unet* u, int kind) {
-    if (!u || kind < 0 || kind > 2) return fail(FISE_ERR_NULL, "fise_unet_num_tensors: bad arguments");
+    if (!u || kind < 0 || kind > 3) return fail(FISE_ERR_NULL, "fise_unet_num_tensors: bad arguments");
     return (int)u->tensors[kind].size();
 }
 
 extern "C" int fise_unet_tensor_info(const fise_unet* u, int kind, int i, char* name, int64_t* offset, int64_t* numel) {
     if (!u || !name || !offset || !numel) return fail(FISE_ERR_NULL, "fise_unet_tensor_info: null pointer");
-    if (kind < 0 || kind > 2 || i < 0 || i >= (int)u->tensors[kind].size()) return fail(FISE_ERR_CAPACITY, "fise_unet_tensor_info: index");
+    if (kind < 0 || kind > 3 || i < 0 || i >= (int)u->tensors[kind].size()) return fail(FISE_ERR_CAPACITY, "fise_unet_tensor_info: index");
     const Tensor& t = u->tensors[kind][i];
     snprintf(name, 64, "%s", t.name.c_str());
     *offset = t.off; *numel = t.numel;
@@ -289,18 +318,30 @@ extern "C" int fise_unet_module_name(const fise_unet* u, int i, char* name) {
     return FISE_OK;
 }
 
+static int unet_run(const fise_unet* u, const void* weights, void* cache, const void* latent, const float* t_sin, const void* ctxkv,
+                    const int32_t* tile_idx, int n_active, int base_tile, int stats_mode, const int* level_dense, int first_module,
+                    int n_modules, int trust_derived, void* workspace, size_t workspace_bytes, void* stream);
+
 extern "C" int fise_masked_unet_step(const fise_unet* u, const void* weights, void* cache, const void* latent,
                                      const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
                                      int base_tile, int stats_mode, const int* level_dense, void* workspace,
                                      size_t workspace_bytes, void* stream) {
-    return fise_masked_unet_modules(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_active, base_tile, stats_mode,
-                                    level_dense, 0, u ? (int)u->mods.size() : 0, workspace, workspace_bytes, stream);
+    return unet_run(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_active, base_tile, stats_mode, level_dense, 0,
+                    u ? (int)u->mods.size() : 0, 1, workspace, workspace_bytes, stream);
 }
 
 extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights, void* cache, const void* latent,
                                         const float* t_sin, const void* ctxkv, const int32_t* tile_idx, int n_active,
                                         int base_tile, int stats_mode, const int* level_dense, int first_module,
                                         int n_modules, void* workspace, size_t workspace_bytes, void* stream) {
+    // module i reads its input MAPS as they stand: their normalised copies are recomputed, not trusted
+    return unet_run(u, weights, cache, latent, t_sin, ctxkv, tile_idx, n_active, base_tile, stats_mode, level_dense, first_module,
+                    n_modules, 0, workspace, workspace_bytes, stream);
+}
+
+static int unet_run(const fise_unet* u, const void* weights, void* cache, const void* latent, const float* t_sin, const void* ctxkv,
+                    const int32_t* tile_idx, int n_active, int base_tile, int stats_mode, const int* level_dense, int first_module,
+                    int n_modules, int trust_derived, void* workspace, size_t workspace_bytes, void* stream) {
     if (!u || !weights || !cache || !latent || !t_sin || !ctxkv) return fail(FISE_ERR_NULL, "fise_masked_unet_step: null pointer");
     const fise_unet_desc& d = u->d;
     const int nl = d.n_levels;
@@ -326,6 +367,31 @@ extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights,
     auto Wp = [&](const std::string& n) { return (const void*)(Wt + u->off(0, n)); };
     auto Cp = [&](const std::string& n) { return (void*)(cb + u->off(1, n)); };
     auto Cf = [&](const std::string& n) { return (float*)(cb + u->off(1, n)); };
+    auto Dp = [&](const std::string& n) { return (void*)(cb + u->off(3, n)); };
+    // the normalised copies the consumers of module m's output want, and m's own derived tensors
+    auto derived = [&](const Module& m) {
+        BlockDerived dv{};
+        if (m.kind == K_RES) {
+            dv.act_in = Dp(m.name + ".a1"); dv.act_mid = Dp(m.name + ".a2");
+            dv.ss_in = (float2*)Dp(m.name + ".gn1.ss"); dv.ss_mid = (float2*)Dp(m.name + ".gn2.ss");
+        } else if (m.kind == K_TR) {
+            dv.act_in = Dp(m.name + ".gx"); dv.ss_in = (float2*)Dp(m.name + ".gn.ss");
+        }
+        dv.trust = trust_derived;
+        for (const ViewSpec& v : m.views) {
+            const Module& c = u->mods[v.consumer];
+            GnView w{};
+            if (c.kind == K_RES) {
+                w.dst = (bf16_t*)Dp(c.name + ".a1"); w.ss = (const float2*)Dp(c.name + ".gn1.ss");
+                w.dstC = c.cin + c.cskip; w.c_off = v.as_skip ? c.cin : 0; w.silu = 1;
+            } else {
+                w.dst = (bf16_t*)Dp(c.name + ".gx"); w.ss = (const float2*)Dp(c.name + ".gn.ss");
+                w.dstC = c.cout; w.c_off = 0; w.silu = 0;
+            }
+            dv.out_view[dv.n_out_view++] = w;
+        }
+        return dv;
+    };
     int* idx_full = (int*)(ws + wl.idx_full);
     float* emb_a = (float*)(ws + wl.emb_a); float* emb_b = (float*)(ws + wl.emb_b); float* temb = (float*)(ws + wl.temb);
     void* blockws = ws + wl.block;
@@ -355,12 +421,14 @@ extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights,
         const std::string& n = m.name;
         const void* in0 = m.in_map.empty() ? latent : Cp(m.in_map);
         const void* in1 = m.skip_map.empty() ? nullptr : Cp(m.skip_map);
+        const BlockDerived dv = derived(m);
+        const int nview = fresh ? 0 : dv.n_out_view;       // with fresh statistics the consumers normalise for themselves
         switch (m.kind) {
         case K_CONV_IN: {
             fise_conv_args a{};
             a.x0 = latent; a.C0 = d.in_ch; a.B = B; a.H = H; a.W = W; a.w = Wp(n + ".w"); a.bias = Wp(n + ".b"); a.Cout = m.cout;
             a.ksize = 3; a.stride = 1; a.tile_idx = idx; a.n_active = nt; a.tile = tile; a.y_cache = Cp(n + ".out"); a.dtype = FISE_BF16;
-            if (int e = conv_dispatch(&a, nullptr, 0, st)) return e;
+            if (int e = conv_dispatch(&a, nullptr, 0, st, dv.out_view, nview)) return e;
         } break;
         case K_RES: {
             fise_resnet_args r{};
@@ -371,7 +439,7 @@ extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights,
             r.conv2_w = Wp(n + ".conv2.w"); r.conv2_b = Wp(n + ".conv2.b");
             if (m.cin + m.cskip != m.cout) { r.sc_w = Wp(n + ".sc.w"); r.sc_b = Wp(n + ".sc.b"); }
             r.tile_idx = idx; r.n_active = nt; r.tile = tile; r.h1_cache = Cp(n + ".h1"); r.out_cache = Cp(n + ".out"); r.stats_fresh = fresh;
-            if (int e = run_resnet(&r, blockws, iw, st)) return e;
+            if (int e = run_resnet(&r, blockws, iw, st, &dv)) return e;
         } break;
         case K_TR: {
             fise_transformer_args t{};
@@ -385,13 +453,13 @@ extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights,
             t.ff2_w = Wp(n + ".ff2.w"); t.ff2_b = Wp(n + ".ff2.b"); t.pout_w = Wp(n + ".pout.w"); t.pout_b = Wp(n + ".pout.b");
             t.K_cache = Cp(n + ".k"); t.Vt_cache = Cp(n + ".v"); t.out_cache = Cp(n + ".out");
             t.tile_idx = idx; t.n_active = nt; t.tile = tile; t.stats_fresh = fresh;
-            if (int e = run_transformer(&t, blockws, iw, st)) return e;
+            if (int e = run_transformer(&t, blockws, iw, st, &dv)) return e;
         } break;
         case K_DS:
-            if (int e = run_conv(in0, m.cin, B, 2 * H, 2 * W, 2, 0, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st)) return e;
+            if (int e = run_conv(in0, m.cin, B, 2 * H, 2 * W, 2, 0, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st, dv.out_view, nview)) return e;
             break;
         case K_US:
-            if (int e = run_conv(in0, m.cin, B, H / 2, W / 2, 1, 1, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st)) return e;
+            if (int e = run_conv(in0, m.cin, B, H / 2, W / 2, 1, 1, Wp(n + ".w"), Wp(n + ".b"), m.cout, idx, nt, tile, Cp(n + ".out"), iw, st, dv.out_view, nview)) return e;
             break;
         case K_OUT: {
             fise_conv_args a{};
@@ -401,8 +469,56 @@ extern "C" int fise_masked_unet_modules(const fise_unet* u, const void* weights,
             a.dtype = FISE_BF16;
             if (fresh)
                 if (int e = fise_groupnorm_stats(in0, nullptr, FISE_BF16, B, H, W, m.cin, 0, G, 1e-5f, Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), blockws, st)) return e;
-            if (int e = conv_dispatch(&a, ws + wl.igemm, igemm_workspace_bytes(), st)) return e;
+            if (int e = conv_dispatch(&a, ws + wl.igemm, igemm_workspace_bytes(), st, nullptr, 0)) return e;
         } break;
+        }
+    }
+    return FISE_OK;
+}
+
+// ---- derived tensors from the stored ones: scale / shift tables from the cached statistics, then every activated
+// map over the whole image (one tile per launch block row: the map's own tile grid at edge 2^(levels-1-level))
+extern "C" size_t fise_unet_refresh_derived_workspace_bytes(const fise_unet* u) {
+    if (!u) return 0;
+    const int t0 = 1 << (u->d.n_levels - 1);
+    return align256((size_t)(u->d.H / t0) * (u->d.W / t0) * sizeof(int));
+}
+
+extern "C" int fise_unet_refresh_derived(const fise_unet* u, const void* weights, void* cache, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+    const char* fn = "fise_unet_refresh_derived";
+    if (!u || !weights || !cache || !workspace) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    if (workspace_bytes < fise_unet_refresh_derived_workspace_bytes(u)) return fail(FISE_ERR_CAPACITY, "%s: workspace too small", fn);
+    if (!aligned16(weights) || !aligned16(cache) || !aligned16(workspace)) return fail(FISE_ERR_ALIGN, "%s: pointers must be 16-byte aligned", fn);
+    const fise_unet_desc& d = u->d;
+    hipStream_t st = as_stream(stream);
+    const bf16_t* Wt = (const bf16_t*)weights;
+    char* cb = (char*)cache;
+    auto Wp = [&](const std::string& n) { return (const void*)(Wt + u->off(0, n)); };
+    auto Cp = [&](const std::string& n) { return (void*)(cb + u->off(1, n)); };
+    auto Cf = [&](const std::string& n) { return (float*)(cb + u->off(1, n)); };
+    auto Dp = [&](const std::string& n) { return (void*)(cb + u->off(3, n)); };
+    const int t0 = 1 << (d.n_levels - 1);
+    const int ntiles = (d.H / t0) * (d.W / t0);
+    int* idx_full = (int*)workspace;
+    if (int e = launch_iota(idx_full, ntiles, st)) return e;
+    const int B = d.B, G = d.groups;
+    for (const Module& m : u->mods) {
+        const std::string& n = m.name;
+        const int H = d.H >> m.lvl, W = d.W >> m.lvl, tile = t0 >> m.lvl;
+        if (m.kind == K_RES) {
+            const int Ci = m.cin + m.cskip;
+            const void* in0 = Cp(m.in_map); const void* in1 = m.skip_map.empty() ? nullptr : Cp(m.skip_map);
+            if (int e = launch_gn_scale_shift(Cf(n + ".gn1.mean"), Cf(n + ".gn1.rstd"), Wp(n + ".gn1.g"), Wp(n + ".gn1.b"), B, Ci, G, (float2*)Dp(n + ".gn1.ss"), st)) return e;
+            if (int e = launch_gn_scale_shift(Cf(n + ".gn2.mean"), Cf(n + ".gn2.rstd"), Wp(n + ".gn2.g"), Wp(n + ".gn2.b"), B, m.cout, G, (float2*)Dp(n + ".gn2.ss"), st)) return e;
+            if (int e = launch_gn_act_halo(in0, in1, m.cin, m.cskip, B, H, W, Cf(n + ".gn1.mean"), Cf(n + ".gn1.rstd"), Wp(n + ".gn1.g"), Wp(n + ".gn1.b"), G, 1,
+                                           idx_full, ntiles, tile, Dp(n + ".a1"), st)) return e;
+            if (int e = launch_gn_act_halo(Cp(n + ".h1"), nullptr, m.cout, 0, B, H, W, Cf(n + ".gn2.mean"), Cf(n + ".gn2.rstd"), Wp(n + ".gn2.g"), Wp(n + ".gn2.b"), G, 1,
+                                           idx_full, ntiles, tile, Dp(n + ".a2"), st)) return e;
+        } else if (m.kind == K_TR) {
+            if (int e = launch_gn_scale_shift(Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), Wp(n + ".gn.g"), Wp(n + ".gn.b"), B, m.cout, G, (float2*)Dp(n + ".gn.ss"), st)) return e;
+            if (int e = launch_gn_act_halo(Cp(m.in_map), nullptr, m.cout, 0, B, H, W, Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), Wp(n + ".gn.g"), Wp(n + ".gn.b"), G, 0,
+                                           idx_full, ntiles, tile, Dp(n + ".gx"), st)) return e;
         }
     }
     return FISE_OK;

@@ -132,8 +132,9 @@ def _is_stat(name):
     return name.endswith(".mean") or name.endswith(".rstd")
 
 
-def pack_cache(fb, u, cache):
-    """Oracle cache dict -> device byte buffer in the library's layout (V caches transposed)."""
+def pack_cache(fb, u, cache, Wd):
+    """Oracle cache dict -> device byte buffer in the library's layout (V caches transposed); the library then fills
+    in the tensors it derives from the stored ones (Wd: the packed weights it needs for that)."""
     buf = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8)
     for name, off, nbytes in fb.fise_unet_tensors(u, 1):
         a = np.asarray(cache[name], np.float32)
@@ -145,7 +146,11 @@ def pack_cache(fb, u, cache):
             t = torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).view(torch.uint8)
         assert t.numel() == nbytes, (name, t.numel(), nbytes)
         buf[off:off + nbytes] = t.reshape(-1)
-    return buf.to(DEV)
+    buf = buf.to(DEV)
+    ws = torch.zeros(max(fb.fise_unet_refresh_derived_workspace_bytes(u), 256), dtype=torch.uint8, device=DEV)
+    fb.fise_unet_refresh_derived(u, Wd, buf, ws)
+    torch.cuda.synchronize()
+    return buf
 
 
 def unpack_cache(fb, u, buf, shapes):

@@ -75,7 +75,7 @@ def test_two_masked_steps_vs_oracle(fb, scratch, capsys):
     fb.fise_mask_detect(x0d, x0nd, 0.1, bt, pm, tm, idxd, nact)
     na = int(nact.item())
     assert na == idx.size and np.array_equal(idxd.cpu().numpy()[:na], idx)
-    c0, c1 = pack_cache(fb, u, cache0), pack_cache(fb, u, cache1)
+    c0, c1 = pack_cache(fb, u, cache0, Wd), pack_cache(fb, u, cache1, Wd)
     fb.fise_masked_unet_step(u, Wd, c0, x0nd, dev(ts[0]), kvd, idxd, na, bt, fb.FISE_STATS_CACHED, None, ws)
     got0 = unpack_cache(fb, u, c0, shapes)
     off, nbytes = next((o, n) for nm, o, n in fb.fise_unet_tensors(u, 1) if nm == "eps")

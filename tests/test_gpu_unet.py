@@ -112,7 +112,7 @@ def test_tiny_unet_step_vs_oracle(fb, seed):
     assert 0 < idx.size < ntiles
     want = {k: v.copy() for k, v in cache_old.items()}
     uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16")
-    cm = pack_cache(fb, u, cache_old)
+    cm = pack_cache(fb, u, cache_old, Wd)
     fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
     got = unpack_cache(fb, u, cm, shapes)
     compare_caches(d, got, want, cache_old, idx, bt, TOL["bf16"])
@@ -129,7 +129,7 @@ def test_tiny_unet_step_vs_oracle(fb, seed):
     want2 = {k: v.copy() for k, v in cache_old.items()}
     ld = [False, False, True, True]
     uo.unet_step(P, d, want2, lat_new, t_sin, kv_new, idx, bt, "bf16", level_dense=ld)
-    c5 = pack_cache(fb, u, cache_old)
+    c5 = pack_cache(fb, u, cache_old, Wd)
     fb.fise_masked_unet_step(u, Wd, c5, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, ld, ws)
     got5 = unpack_cache(fb, u, c5, shapes)
     assert rel_l2(got5["eps"], want2["eps"]) <= TOL["bf16"] and rel_l2(got5["mid.tr.0.out"], want2["mid.tr.0.out"]) <= TOL["bf16"]
@@ -172,7 +172,7 @@ def test_other_architectures_vs_oracle(fb, name, over, bt):
     assert 0 < idx.size < ntiles
     want = {k: v.copy() for k, v in cache_old.items()}
     uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16")
-    cm = pack_cache(fb, u, cache_old)
+    cm = pack_cache(fb, u, cache_old, Wd)
     fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), tsd, kvd_new, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
     compare_caches(d, unpack_cache(fb, u, cm, shapes), want, cache_old, idx, bt, TOL["bf16"])
     fb.fise_unet_destroy(u)
@@ -193,7 +193,7 @@ def test_tiny_unet_full_mask_fresh_equals_dense_of_new_inputs(fb):
     fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd)
     full = fo.full_index(H, W, bt)
     ws = torch.zeros(fb.fise_unet_workspace_bytes(u, full.size, bt), dtype=torch.uint8, device=DEV)
-    cm = pack_cache(fb, u, cache_old)
+    cm = pack_cache(fb, u, cache_old, Wd)
     fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), dev(t_sin), kvd, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
     got = unpack_cache(fb, u, cm, shapes)
     assert rel_l2(got["eps"], cache_new["eps"]) <= TOL["bf16"]
@@ -253,7 +253,7 @@ def run_module_by_module(fb, d, seed, std, bt, frac, say, tol=TOL["bf16"], scrat
     fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd)
     ws = torch.zeros(fb.fise_unet_workspace_bytes(u, ntiles, bt), dtype=torch.uint8, device=DEV)
     layout = {n: (off, nb) for n, off, nb in fb.fise_unet_tensors(u, 1)}
-    cm = pack_cache(fb, u, cache_old)
+    cm = pack_cache(fb, u, cache_old, Wd)
     chain = cm.clone()
     latd, tsd, idxd = dev(lat_new, "bf16"), dev(t_sin), idx_dev(idx)
     want = {k: v.copy() for k, v in cache_old.items()}
