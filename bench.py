@@ -31,11 +31,25 @@ KIND_NAMES = {0: "igemm_dma_kernel<64,64,2,2,3,*>", 1: "igemm_dma_kernel<64,128,
               2: "attention_kernel", 3: "igemm_dma_kernel<64,128,2,4,3,*>", 4: "igemm_reduce_kernel / igemm_reduce_ln_kernel",
               5: "igemm_dma_kernel<32,128,1,4,3,*>", 6: "igemm_kernel<...> (GroupNorm prologue)", 7: "attention_merge_kernel",
               8: "(empty bracket)", 9: "igemm_wsk_kernel<32|64,NW,3>"}
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this bench on the
-# headline workload, scaled by what the same counters read for a plain copy of known size; see profiles/.
-PMC_TRAFFIC_BYTES_PER_LAUNCH = {       # (FETCH_SIZE KiB x 2.0 copy factor + WRITE_SIZE KiB x 1.0) x 1024
-    "igemm_dma_kernel<64,64,2,2,3,*>": (5599.7 * 2.0 + 4347.5) * 1024,
-}
+# HBM bytes per launch (read + written) of the library's kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this bench on the headline workload: profiles/masked_unet_step_sd15_10pct_traffic.json, written by
+# `python -m paper_2305_17423_amd.profile_summary` together with the sha1 of the kernel sources it was measured
+# at.  When the sources have changed since, the figure is stale and the line reports null.
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "masked_unet_step_sd15_10pct_traffic.json")
+
+
+def measured_traffic(kernel):
+    """(bytes per launch or None, note) for a fise_profile_read kind name."""
+    try:
+        from paper_2305_17423_amd.profile_summary import kernel_sources_sha1
+        t = json.load(open(TRAFFIC_JSON))
+        if t.get("kernel_sources_sha1") != kernel_sources_sha1():
+            return None, "profiles/*_traffic.json was measured at other kernel sources"
+        e = t["per_kind"].get(kernel)
+        return (e["hbm_bytes_per_launch"], t.get("command")) if e else (None, "kernel not in profiles/*_traffic.json")
+    except Exception as ex:                      # missing or unreadable summary: no figure rather than a wrong one
+        return None, f"no traffic summary ({type(ex).__name__})"
+
 
 SD15 = dict(in_ch=4, out_ch=4, base=320, mults=(1, 2, 4, 4), layers=2, attn=(True, True, True, False),
             heads=8, ctx_dim=768, n_ctx=77, groups=32, H=64, W=64, B=2)
@@ -54,6 +68,97 @@ def sinusoid(t, dim):
     return np.concatenate([np.cos(a), np.sin(a)], 1).astype(np.float32)
 
 
+def run_sweeps(fb, wl, np, torch, dev, u, d, Wd, cache, lat_new, t_sin, kv_new, ws, bt, ntiles, full, args, gen, timed, step):
+    """Latency records for the other configurations: how the step scales with the mask (1-50 %), one module of each kind
+    at every level against the same kernels run dense (configs 2 and 4, with the crossover), the attention sub-layers at
+    2-20 % active queries on 4x4 tiles (config 3), and the single fp32 convolution (config 1)."""
+    B, H, W = d["B"], d["H"], d["W"]
+    out = {}
+
+    def us(fn, reps=20, warm=3):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    def tiles_of(frac, tile, HH, WW, seed):
+        px = wl.ellipse_pixels(np.random.default_rng(seed), HH, WW, frac)
+        tl = np.flatnonzero(px.reshape(HH // tile, tile, WW // tile, tile).any(axis=(1, 3)).reshape(-1)).astype(np.int32)
+        buf = torch.zeros((HH // tile) * (WW // tile), dtype=torch.int32, device=dev); buf[:tl.size] = torch.from_numpy(tl).to(dev)
+        return int(tl.size), buf
+
+    # ---- the whole step against the blob size
+    fracs = (0.01, 0.05, 0.10, 0.25, 0.50)
+    lists = [(f,) + tiles_of(f, bt, H, W, args.seed + int(f * 1000)) for f in fracs]
+    dens = []
+    for f, n, buf in lists:
+        for i in range(3):
+            step(i, n, buf)
+        dens.append({"pixel_fraction": f, "active_tiles": n, "tiles": ntiles, "ms_per_step": timed(10, n, buf)})
+    out["step_vs_mask_density"] = dens
+    log("[bench] step vs blob size: " + ", ".join(f"{r['pixel_fraction'] * 100:.0f} % -> {r['active_tiles']} tiles {r['ms_per_step']:.3f} ms" for r in dens))
+
+    # ---- one module of each kind per level, alone (config 2 = the first row; config 4 = levels 1 and 2)
+    names = fb.fise_unet_module_names(u)
+    picks = [("resnet_64x64_c320", "down.0.res.1"), ("resnet_32x32_c640", "down.1.res.1"), ("resnet_16x16_c1280", "down.2.res.1"),
+             ("resnet_8x8_c1280", "mid.res.0"), ("transformer_64x64_c320", "down.0.tr.1"), ("transformer_32x32_c640", "down.1.tr.1"),
+             ("transformer_16x16_c1280", "down.2.tr.1"), ("transformer_8x8_c1280", "mid.tr.0")]
+    mods = {}
+    for label, mod in picks:
+        mi = names.index(mod)
+        run = lambda n, buf: fb.fise_masked_unet_modules(u, Wd, cache, lat_new, t_sin, kv_new, buf, n, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
+        row = {f"{int(f * 100)}pct": us(lambda: run(n, buf)) for f, n, buf in lists}
+        row["dense"] = us(lambda: run(ntiles, full))
+        cross = next((f for f, _, _ in lists if row[f"{int(f * 100)}pct"] >= 0.95 * row["dense"]), None)
+        row["crossover_pixel_fraction"] = cross        # smallest blob at which masked is within 5 % of dense; None: masked wins up to 50 %
+        mods[label] = row
+        log(f"[bench] {label:26s} " + " ".join(f"{k}={v:.1f}" for k, v in row.items() if isinstance(v, float) and k != "crossover_pixel_fraction") + f" us; crossover {cross}")
+    out["module_us_by_blob_size"] = {"note": "one module alone through fise_masked_unet_modules (its inputs' normalised copies recomputed, as the "
+                                             "stand-alone block entry points do); 8x8 base tiles: 4x4 at 32x32, 2x2 at 16x16, 1x1 at 8x8", **mods}
+
+    # ---- config 3: the attention sub-layers at 64x64 tokens, C = 320, 8 heads, 4x4 tiles
+    C, heads, t3, n_ctx = d["base"], d["heads"], 4, d["n_ctx"]
+    rn = lambda *shape, std=1.0: (std * torch.randn(*shape, device=dev, generator=gen)).to(torch.bfloat16)
+    x = rn(B, H, W, C); y = torch.zeros_like(x)
+    g, b0 = torch.ones(C, dtype=torch.bfloat16, device=dev), torch.zeros(C, dtype=torch.bfloat16, device=dev)
+    wq, wk, wv, wo = (rn(C, C, std=0.02) for _ in range(4))
+    Kc, Vt = rn(B, H * W, C), rn(B, C, H * W)
+    Kx, Vx = rn(B, n_ctx, C), rn(B, C, (n_ctx + 7) // 8 * 8)
+    att = []
+    nt3 = (H // t3) * (W // t3)
+    for f in (0.02, 0.05, 0.10, 0.20, 1.0):
+        n, buf = (nt3, torch.arange(nt3, dtype=torch.int32, device=dev)) if f == 1.0 else tiles_of(f, t3, H, W, args.seed + 3000 + int(f * 100))
+        wsa = torch.zeros(fb.fise_masked_attention_workspace_bytes(B, C, n, t3), dtype=torch.uint8, device=dev)
+        t_self = us(lambda: fb.fise_masked_attention(x, g, b0, wq, wk, wv, wo, b0, heads, Kc, Vt, None, None, 0, buf, n, t3, y, wsa))
+        t_cross = us(lambda: fb.fise_masked_attention(x, g, b0, wq, None, None, wo, b0, heads, None, None, Kx, Vx, n_ctx, buf, n, t3, y, wsa))
+        att.append({"pixel_fraction": f, "active_queries_per_batch_element": n * t3 * t3, "self_attention_layer_us": t_self,
+                    "cross_attention_layer_us": t_cross})
+    out["attention_64x64_c320_4x4_tiles"] = att
+    log("[bench] attention sub-layers (self / cross, us): " + ", ".join(f"{r['pixel_fraction'] * 100:.0f} %: {r['self_attention_layer_us']:.1f} / {r['cross_attention_layer_us']:.1f}" for r in att))
+
+    # ---- config 1: one fp32 3x3 convolution, 32x32x64, an 8x8 rectangle of change, 4x4 tiles
+    rng1 = np.random.default_rng(1001)
+    xo = wl.normal(rng1, (1, 32, 32, 64)); xn = wl.perturb(rng1, xo, wl.rect_pixels(rng1, 32, 32, 8, 8))
+    xod, xnd = torch.from_numpy(xo).to(dev), torch.from_numpy(xn).to(dev)
+    w1 = torch.from_numpy(wl.normal(rng1, (64, 3, 3, 64), 1 / 24)).to(dev)
+    y1 = torch.zeros((1, 32, 32, 64), device=dev)
+    pm1 = torch.zeros((32, 32), dtype=torch.uint8, device=dev); tm1 = torch.zeros(64, dtype=torch.uint8, device=dev)
+    ix1 = torch.zeros(64, dtype=torch.int32, device=dev); n1 = torch.zeros(1, dtype=torch.int32, device=dev)
+    fb.fise_mask_detect(xod, xnd, 0.1, 4, pm1, tm1, ix1, n1)
+    na1 = int(n1.item())
+    t_det = us(lambda: fb.fise_mask_detect(xod, xnd, 0.1, 4, pm1, tm1, ix1, n1))
+    t_conv = us(lambda: fb.fise_masked_conv3x3(xnd, w1, None, 1, ix1, na1, 4, y1))
+    t_full = us(lambda: fb.fise_masked_conv3x3(xnd, w1, None, 1, torch.arange(64, dtype=torch.int32, device=dev), 64, 4, y1))
+    out["single_fp32_conv_32x32x64"] = {"active_tiles": na1, "tiles": 64, "mask_detect_us": t_det, "masked_conv_us": t_conv, "dense_conv_us": t_full}
+    log(f"[bench] fp32 conv 32x32x64: detect {t_det:.1f} us, masked conv ({na1}/64 tiles) {t_conv:.1f} us, all tiles {t_full:.1f} us")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,10 +174,9 @@ def main():
     ap.add_argument("--seed", type=int, default=5000)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB elementwise copy (for scaling FETCH_SIZE / WRITE_SIZE counter readings)")
-    ap.add_argument("--level-sweep", action="store_true",
-                    help="log per-module masked times by block kind, level and blob size, with the dense time (stderr)")
-    ap.add_argument("--density-sweep", action="store_true",
-                    help="log masked step time for blobs of 1/5/10/25/50 %% of the latent (stderr), then the normal run")
+    ap.add_argument("--no-sweeps", action="store_true",
+                    help="skip the `sweeps` records (density sweep of the step, configs 1-4: single conv, ResNet block, attention at "
+                         "2-20 %%, per-level modules with the crossover against dense)")
     ap.add_argument("--host-spill", action="store_true",
                     help="also time the masked step with the per-step caches in pinned host memory, streamed through three "
                          "device slots on two copy streams (reported beside the resident figure, never as `value`)")
@@ -158,47 +262,6 @@ def main():
         torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    if args.density_sweep:
-        idx_s = torch.zeros(ntiles, dtype=torch.int32, device=dev)
-        for frac in (0.01, 0.05, 0.10, 0.25, 0.50):
-            px = wl.ellipse_pixels(np.random.default_rng(args.seed + int(frac * 1000)), H, W, frac)
-            tiles = np.flatnonzero(px.reshape(H // bt, bt, W // bt, bt).any(axis=(1, 3)).reshape(-1)).astype(np.int32)
-            idx_s[:tiles.size] = torch.from_numpy(tiles).to(dev)
-            for i in range(3):
-                step(i, int(tiles.size), idx_s)
-            log(f"[bench] blob {frac * 100:4.0f} % of pixels -> {tiles.size:2d}/{ntiles} tiles: masked step "
-                f"{timed(max(5, args.steps // 2), int(tiles.size), idx_s):.3f} ms")
-    if args.level_sweep:
-        # One representative module per (kind, level): time it alone, teacher-forced on the cache, for blobs of growing
-        # size and for the full tile list.  Answers where masked stops paying at each level's shape.
-        names = fb.fise_unet_module_names(u)
-        picks = [("ResNet 64x64 C320", "down.0.res.1"), ("ResNet 32x32 C640", "down.1.res.1"), ("ResNet 16x16 C1280", "down.2.res.1"),
-                 ("ResNet 8x8 C1280", "mid.res.0"), ("transformer 64x64 C320", "down.0.tr.1"), ("transformer 32x32 C640", "down.1.tr.1"),
-                 ("transformer 16x16 C1280", "down.2.tr.1"), ("transformer 8x8 C1280", "mid.tr.0")]
-        fracs = (0.01, 0.05, 0.10, 0.25, 0.50)
-        lists = []
-        for frac in fracs:
-            px = wl.ellipse_pixels(np.random.default_rng(args.seed + int(frac * 1000)), H, W, frac)
-            tl = np.flatnonzero(px.reshape(H // bt, bt, W // bt, bt).any(axis=(1, 3)).reshape(-1)).astype(np.int32)
-            buf = torch.zeros(ntiles, dtype=torch.int32, device=dev); buf[:tl.size] = torch.from_numpy(tl).to(dev)
-            lists.append((f"{frac * 100:.0f}%->{tl.size}t", int(tl.size), buf))
-        lists.append(("dense", ntiles, full))
-
-        def time_module(mi, n_act, index, reps=20):
-            for _ in range(3):
-                fb.fise_masked_unet_modules(u, Wd, caches[0], lat_new, t_sin_all[0], kv_new, index, n_act, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                fb.fise_masked_unet_modules(u, Wd, caches[0], lat_new, t_sin_all[0], kv_new, index, n_act, bt, fb.FISE_STATS_CACHED, None, mi, 1, ws)
-            e1.record(); torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps * 1e3
-        log("[bench] module time in us by blob size (pixels -> active 8x8-base tiles of 64):")
-        log("[bench] " + " " * 26 + "".join(f"{lbl:>11s}" for lbl, _, _ in lists))
-        for label, mod in picks:
-            ts = [time_module(names.index(mod), n_act, index) for _, n_act, index in lists]
-            log(f"[bench] {label:26s}" + "".join(f"{t:11.1f}" for t in ts))
     if args.apsc_sweep:
         # The convolution the selection is defined for, on this step's own pixel mask: gathered pixels (its cost
         # function) and measured time for each of the 25 block shapes.
@@ -243,6 +306,41 @@ def main():
         for i in range(2):
             step(i, ntiles, full)
         ms_dense = timed(max(3, min(args.steps, 10)), ntiles, full)
+
+    # ---- records of the other configurations and of how the step scales with the mask (not part of `value`)
+    sweeps = None
+    if not args.no_sweeps and not args.small:
+        sweeps = run_sweeps(fb, wl, np, torch, dev, u, d, Wd, caches[0], lat_new, t_sin_all[0], kv_new, ws, bt, ntiles, full, args, gen,
+                            timed, step)
+
+    # ---- a whole edit: 50 denoising steps, each = mask detection + masked UNet step on that timestep's cache + the
+    # sampler update of the latent at the active pixels (harness arithmetic, a few torch kernels), timed end to end
+    edit = None
+    if not args.small:
+        act_pix = pm.bool()                                       # pixels inside active tiles of the detected mask
+        tiles_h = tm.reshape(H // bt, W // bt).bool()
+        act_pix = tiles_h.repeat_interleave(bt, 0).repeat_interleave(bt, 1)
+        off_eps, nb_eps = next((o, n) for nm, o, n in fb.fise_unet_tensors(u, 1) if nm == "eps")
+        coef = [wl.ddim_coeffs(int(ts[i]), int(ts[i + 1]) if i + 1 < T else -1) for i in range(T)]
+
+        def edit_run():
+            x = lat_new.clone()
+            for i in range(T):
+                c = caches[i % ncache]
+                fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)
+                fb.fise_masked_unet_step(u, Wd, c, x, t_sin_all[i], kv_new, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
+                eps = c[off_eps:off_eps + nb_eps].view(torch.bfloat16).reshape(B, H, W, d["out_ch"])
+                a_, b_ = coef[i]
+                x = torch.where(act_pix[None, :, :, None], (a_ * x.float() + b_ * eps.float()).to(torch.bfloat16), x)
+            return x
+        edit_run()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        edit_run()
+        torch.cuda.synchronize()
+        edit = {"steps": T, "ms_total": (time.time() - t0) * 1e3, "ms_per_step": (time.time() - t0) * 1e3 / T,
+                "note": "mask detection + masked step + sampler update at active pixels per step, wall clock around 50 steps"}
+        log(f"[bench] 50-step edit, end to end: {edit['ms_total']:.1f} ms ({edit['ms_per_step']:.3f} ms per step incl. the sampler update)")
 
     # ---- the same step with the caches spilled to pinned host memory (PCIe in the loop; context, not `value`)
     spill = None
@@ -313,7 +411,7 @@ def main():
     dom = max(kinds, key=lambda k: kinds[k]["ms_per_step"])
     dk = kinds[dom]
     f_mfma, f_hbm = dk["tflops"] / MFMA_BF16_PEAK_TFLOPS, dk["gbs"] / HBM_PEAK_GBS
-    traffic = PMC_TRAFFIC_BYTES_PER_LAUNCH.get(dom) if not args.small else None
+    traffic, traffic_note = measured_traffic(dom) if (not args.small and args.latent == 64 and abs(args.frac - 0.10) < 1e-9) else (None, "not the profiled workload")
     if f_hbm >= f_mfma:     # small masked problems stream their weights once: the HBM roof is the nearer one
         roofline = dict(bound="hbm", kernel=dom, achieved=dk["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", frac=f_hbm,
                         traffic=traffic, algorithmic_bytes_per_launch=dk["mbytes_per_launch"] * 1e6)
@@ -326,7 +424,7 @@ def main():
     del scratch
     roofline["empirical"] = dict(copy_gbs=copy_gbs, mfma_bf16_tflops=mfma_tf, hbm_frac_of_copy=dk["gbs"] / copy_gbs,
                                  mfma_frac_of_loop=dk["tflops"] / mfma_tf)
-    roofline.update(avg_launch_us=dk["avg_us"], avg_launch_us_raw=dk["avg_us_raw"], empty_bracket_us=empty_us,
+    roofline.update(traffic_source=traffic_note, avg_launch_us=dk["avg_us"], avg_launch_us_raw=dk["avg_us_raw"], empty_bracket_us=empty_us,
                     launches_per_step=dk["launches_per_step"], mfma_frac=f_mfma, hbm_frac=f_hbm)
 
     res = {
@@ -337,7 +435,9 @@ def main():
                                 f"config 5: SD-1.5-shaped UNet step, batch 2, latent {args.latent}x{args.latent}x4, context 77x768, "
                                 "seeded blob, 8x8 base tiles; mask detect + masked step per timed step"),
                    "pixel_fraction": float(pix.mean()), "active_tile_fraction": na / ntiles, "tile": bt, "caches_cycled": ncache},
-        "masked_ms": ms_masked, "dense_ms": ms_dense, "end_to_end_ms": ms_masked * args.steps, "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None,
+        "masked_ms": ms_masked, "dense_ms": ms_dense, "end_to_end_ms": ms_masked * args.steps,
+        "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None, "speedup_vs_dense_target": 4.0,
+        "frac_of_weight_floor": (nW * 2 / (HBM_PEAK_GBS * 1e6)) / ms_masked,
         "unet_calls_per_s": 1e3 / ms_masked, "useful_tflops": flops_masked / ms_masked / 1e9,
         "masked_gflop": flops_masked / 1e9, "dense_gflop": flops_dense / 1e9,
         "dense_tflops": (flops_dense / ms_dense / 1e9) if ms_dense else None,
@@ -346,6 +446,10 @@ def main():
     }
     if spill:
         res["host_spill"] = spill
+    if sweeps:
+        res["sweeps"] = sweeps
+    if edit:
+        res["edit_50_steps"] = edit
 
     # ---- the oracle, as it stands, on the host cores: one masked step of the same workload
     if not args.no_cpu_baseline:

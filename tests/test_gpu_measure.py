@@ -47,7 +47,7 @@ def test_profile_log_counts_launches(fb):
     fb.fise_profile_enable(False)
     fb.fise_profile_calibrate(20)
     torch.cuda.synchronize()
-    got = {k: fb.fise_profile_read(k) for k in range(9)}
+    got = {k: fb.fise_profile_read(k) for k in range(10)}
     fb.fise_profile_read(-1)
     gemm = [k for k in (0, 3, 5, 6) if got[k][3]]
     assert len(gemm) == 1 and got[gemm[0]][3] == 1
