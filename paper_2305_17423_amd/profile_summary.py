@@ -29,7 +29,8 @@ CSRC = os.path.join(HERE, "csrc")
 TRACE_CMD = ("rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/kt -o run -- "
              "python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --caches 1 --steps 20 --warmup 3")
 PMC_CMD = ("rocprofv3 --pmc {c} --output-format csv -d gpurun_out/{d} -o run -- "
-           "python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1 --calibrate-copy")
+           "python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1")
+COPY_KIB = 1048576.0        # bench.py ends with fise_calibrate_peaks on a 2 GiB scratch: each copy launch reads and writes 1 GiB
 
 
 def kernel_sources_sha1() -> str:
@@ -123,7 +124,15 @@ def summarize_trace(d, out):
     for k, v in sorted(by_kind.items(), key=lambda kv: -kv[1][1]):
         lines.append(f"| {k} | {v[0] / ns:.0f} | {v[1] / v[0]:.2f} |")
     open(out + "_kernel_trace.md", "w").write("\n".join(lines) + "\n")
-    return {k: v[1] / v[0] for k, v in by_kind.items()}
+    per_kernel = {k: v[1] / v[0] for k, v in agg.items()}
+    for r in rows:                                    # the calibration kernels run once, after the steps
+        if "calib_" in r["Kernel_Name"]:
+            e = per_kernel.setdefault("_n_" + short(r["Kernel_Name"]), [0, 0.0])
+            e[0] += 1; e[1] += (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+    for k in [k for k in per_kernel if k.startswith("_n_")]:
+        n, tot = per_kernel.pop(k)
+        per_kernel[k[3:]] = tot / n
+    return per_kernel
 
 
 def _pmc(d, counter):
@@ -133,18 +142,21 @@ def _pmc(d, counter):
     return rows
 
 
-def _after_copy(rows):
-    """Steady masked steps after the calibration copy kernel (bench.py --calibrate-copy), and that kernel's row."""
-    cal = [i for i, r in enumerate(rows) if "CUDAFunctor_add" in r["Kernel_Name"] or "AddFunctor" in r["Kernel_Name"] or
-           ("vectorized_elementwise_kernel" in r["Kernel_Name"] and int(r["Grid_Size"]) >= (64 << 20) // 8)]
-    if not cal:
-        raise RuntimeError("calibration copy kernel not found (run bench.py with --calibrate-copy)")
-    ci = cal[-1]
-    starts = [i for i, r in enumerate(rows) if "pixel_diff_kernel" in r["Kernel_Name"] and i > ci]
+def _steady_steps(rows):
+    """Index ranges of the steady-state masked steps (each begins with the mask-detection kernel; the most common
+    launch count is the masked step's)."""
+    starts = [i for i, r in enumerate(rows) if "pixel_diff_kernel" in r["Kernel_Name"]]
     steps = [(a, b) for a, b in zip(starts[:-1], starts[1:])]
-    sizes = collections.Counter(b - a for a, b in steps)
-    n_launch = sizes.most_common(1)[0][0]
-    return rows[ci], [(a, b) for a, b in steps if b - a == n_launch]
+    n_launch = collections.Counter(b - a for a, b in steps).most_common(1)[0][0]
+    return [(a, b) for a, b in steps if b - a == n_launch][1:]
+
+
+def _copy_scale(rows):
+    """What the counter reads for the library's own plain copy kernel of known size (median over its launches)."""
+    v = sorted(float(r["Counter_Value"]) for r in rows if "calib_copy_kernel" in r["Kernel_Name"])
+    if not v:
+        raise RuntimeError("fise::calib_copy_kernel not in the run (bench.py calls fise_calibrate_peaks at its end)")
+    return COPY_KIB / v[len(v) // 2]
 
 
 def summarize_traffic(df, dw, out):
@@ -153,8 +165,8 @@ def summarize_traffic(df, dw, out):
     nsteps = 0
     for counter, d in (("FETCH_SIZE", df), ("WRITE_SIZE", dw)):
         rows = _pmc(d, counter)
-        cal, steps = _after_copy(rows)
-        factors[counter] = 262144.0 / float(cal["Counter_Value"])          # the copy reads and writes 256 MiB = 262144 KiB
+        steps = _steady_steps(rows)
+        factors[counter] = _copy_scale(rows)
         nsteps = len(steps)
         for a, b in steps:
             for r in rows[a:b]:
@@ -165,9 +177,9 @@ def summarize_traffic(df, dw, out):
     lines = ["# HBM traffic of the masked UNet step's kernels (SD-1.5 shapes, 10 % blob): FETCH_SIZE / WRITE_SIZE", "",
              "Commands (two runs, one counter each; on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```",
              PMC_CMD.format(c="FETCH_SIZE", d="pmc_f"), PMC_CMD.format(c="WRITE_SIZE", d="pmc_w"), "```", "",
-             "`--calibrate-copy` adds one plain elementwise kernel that reads 256 MiB and writes 256 MiB (262144 KiB each): the counters are "
-             f"scaled by what they read for it (FETCH_SIZE x {factors['FETCH_SIZE']:.3f}, WRITE_SIZE x {factors['WRITE_SIZE']:.3f}).  "
-             f"Masked steps after that kernel ({nsteps}), scaled, per launch and per step:", "",
+             "bench.py ends with `fise_calibrate_peaks`, whose plain copy kernel (`fise::calib_copy_kernel`) reads 1 GiB and writes 1 GiB per "
+             f"launch: the counters are scaled by what they read for it (FETCH_SIZE x {factors['FETCH_SIZE']:.3f}, WRITE_SIZE x "
+             f"{factors['WRITE_SIZE']:.3f}).  Steady-state masked steps ({nsteps}), scaled, per launch and per step:", "",
              "| kernel | launches/step | fetched KiB/launch | written KiB/launch | fetched MiB/step | written MiB/step |", "|---|---:|---:|---:|---:|---:|"]
     tot_f = tot_w = 0.0
     for k, e in sorted(res.items(), key=lambda kv: -(kv[1]["FETCH_SIZE"] + kv[1]["WRITE_SIZE"])):
@@ -183,7 +195,7 @@ def summarize_traffic(df, dw, out):
             p = per_kind.setdefault(kd, {"launches": 0, "fetch_kib": 0.0, "write_kib": 0.0})
             p["launches"] += e["n"]["FETCH_SIZE"]; p["fetch_kib"] += e["FETCH_SIZE"]; p["write_kib"] += e["WRITE_SIZE"]
     js = {"workload": "config 5, SD-1.5 shapes, 64x64 latent, 10 % blob, 8x8 base tiles",
-          "command": "rocprofv3 --pmc FETCH_SIZE | WRITE_SIZE -- python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1 --calibrate-copy",
+          "command": "rocprofv3 --pmc FETCH_SIZE | WRITE_SIZE -- python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1",
           "kernel_sources_sha1": kernel_sources_sha1(), "scale": factors, "steps_counted": nsteps, "per_kind": {}}
     for kd, p in per_kind.items():
         n = max(p["launches"], 1)
@@ -194,18 +206,15 @@ def summarize_traffic(df, dw, out):
 
 
 def summarize_mfma(d, out, avg_us):
-    names = ("SQ_VALU_MFMA_BUSY_CYCLES", "SQ_INSTS_VALU_MFMA_MOPS_BF16", "SQ_BUSY_CYCLES", "GRBM_GUI_ACTIVE")
+    """avg_us: kernel name -> average duration from the kernel-trace run (the counter run serialises and slows kernels)."""
+    names = ("MfmaUtil", "SQ_INSTS_VALU_MFMA_MOPS_BF16", "GRBM_GUI_ACTIVE")
     per = {}
     nsteps = 0
     for c in names:
         rows = _pmc(d, c)
         if not rows:
             continue
-        starts = [i for i, r in enumerate(rows) if "pixel_diff_kernel" in r["Kernel_Name"]]
-        steps = [(a, b) for a, b in zip(starts[:-1], starts[1:])]
-        sizes = collections.Counter(b - a for a, b in steps)
-        n_launch = sizes.most_common(1)[0][0]
-        steps = [(a, b) for a, b in steps if b - a == n_launch][1:]
+        steps = _steady_steps(rows)
         nsteps = len(steps)
         for a, b in steps:
             for r in rows[a:b]:
@@ -213,22 +222,35 @@ def summarize_mfma(d, out, avg_us):
                     continue
                 e = per.setdefault(short(r["Kernel_Name"]), collections.defaultdict(float))
                 e[c] += float(r["Counter_Value"]); e["n_" + c] += 1
+        for r in rows:                                # reference rows: the calibration kernels at the end of the run
+            if "calib_" in r["Kernel_Name"]:
+                e = per.setdefault(short(r["Kernel_Name"]), collections.defaultdict(float))
+                e[c] += float(r["Counter_Value"]); e["n_" + c] += 1
     lines = ["# MFMA counters of the masked UNet step's kernels (SD-1.5 shapes, 10 % blob)", "",
              "Command (its own run: counters only; on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```",
-             "rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_BUSY_CYCLES GRBM_GUI_ACTIVE --output-format csv "
-             "-d gpurun_out/pmc_m -o run -- python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1", "```", "",
-             f"Per launch, averaged over {nsteps} masked steps.  `MFMA busy` = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x 1024 SIMDs): the share "
-             "of SIMD-cycles, while the kernel had the GPU, in which a matrix unit was executing (the profiler's MfmaUtil).  `GFLOP` = "
-             "SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 / 1e9, the bf16 matrix operations actually issued (padding included).", "",
-             "| kernel | launches/step | GPU-active cycles | MFMA busy % | MFMA GFLOP/launch | TFLOP/s while active (2.4 GHz) |", "|---|---:|---:|---:|---:|---:|"]
-    for k, e in sorted(per.items(), key=lambda kv: -kv[1]["GRBM_GUI_ACTIVE"]):
-        n = max(e["n_GRBM_GUI_ACTIVE"], 1)
-        act = e["GRBM_GUI_ACTIVE"] / n
-        busy = e["SQ_VALU_MFMA_BUSY_CYCLES"] / max(e["n_SQ_VALU_MFMA_BUSY_CYCLES"], 1)
+             PMC_CMD.format(c="MfmaUtil SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE", d="pmc_m"), "```", "",
+             f"Per launch, averaged over {nsteps} steady-state masked steps.  `MfmaUtil` is the profiler's derived counter "
+             "100 x SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x SIMDs): the share of SIMD-cycles, while the kernel had the GPU, in which a "
+             "matrix unit was executing.  `MFMA GFLOP` = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 / 1e9: the bf16 matrix operations actually issued "
+             "(tile padding included).  `TFLOP/s` divides it by the kernel's average duration in the kernel-trace run (the counter run "
+             "serialises dispatches and is slower); `% of peak` is against 2.5 PFLOP/s.  The last rows are bench.py's calibration kernels "
+             "(a register-resident MFMA loop and a plain copy) as a check of what the counters read at the two extremes.", "",
+             "| kernel | launches/step | MfmaUtil % | MFMA GFLOP/launch | average us | issued TFLOP/s | % of MFMA peak |", "|---|---:|---:|---:|---:|---:|---:|"]
+
+    def row(k, e, n_steps):
+        n = max(e["n_MfmaUtil"], 1)
+        util = e["MfmaUtil"] / n
         gflop = e["SQ_INSTS_VALU_MFMA_MOPS_BF16"] / max(e["n_SQ_INSTS_VALU_MFMA_MOPS_BF16"], 1) * 512 / 1e9
-        util = 100.0 * busy / (act * 1024) if act else 0.0
-        tf = gflop / (act / 2.4e9) / 1e3 if act else 0.0
-        lines.append(f"| `{k}` | {n / nsteps:.0f} | {act:.0f} | {util:.2f} | {gflop:.4f} | {tf:.1f} |")
+        us = avg_us.get(k)
+        tf = gflop / us * 1e3 if us else float("nan")
+        per_step = f"{n / n_steps:.0f}" if n_steps else "-"
+        return f"| `{k}` | {per_step} | {util:.2f} | {gflop:.4f} | {us if us is None else round(us, 2)} | {tf:.1f} | {tf / 2500 * 100:.2f} |"
+    main_rows = {k: e for k, e in per.items() if "calib_" not in k}
+    for k, e in sorted(main_rows.items(), key=lambda kv: -kv[1]["SQ_INSTS_VALU_MFMA_MOPS_BF16"]):
+        lines.append(row(k, e, nsteps))
+    for k, e in per.items():
+        if "calib_" in k:
+            lines.append(row(k, e, 0))
     open(out + "_mfma_counters.md", "w").write("\n".join(lines) + "\n")
 
 
