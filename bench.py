@@ -75,14 +75,27 @@ def run_sweeps(fb, wl, np, torch, dev, u, d, Wd, cache, lat_new, t_sin, kv_new, 
     B, H, W = d["B"], d["H"], d["W"]
     out = {}
 
+    side = torch.cuda.Stream()
+
     def us(fn, reps=20, warm=3):
+        """Device time of fn() in us: fn is captured into a HIP graph (the library allocates nothing and never
+        synchronises) and the graph replayed, so that the host's per-call cost stays out of the figure."""
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(reps):
+                    fn()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(reps):
-            fn()
+        graph.replay()
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e3
 

@@ -112,6 +112,127 @@ __global__ __launch_bounds__(256) void conv_latent3x3_kernel(const bf16_t* __res
     }
 }
 
+// fp32 convolution for channel counts that are multiples of 16 (one source, no GroupNorm prologue) on the fp32 matrix
+// instruction (v_mfma_f32_32x32x2f32: full float products and sums).  A workgroup owns a 32-row x 64-column output
+// tile; operands are staged through LDS in BK-wide K chunks with 16-byte loads (the next chunk is fetched into
+// registers while the current one is multiplied); each of the four waves multiplies its quarter of every chunk into
+// its own pair of 32x32 accumulators, and the four partial tiles are summed through LDS in wave order at the end.
+typedef float f32x16v __attribute__((ext_vector_type(16)));
+template <int BK>
+__global__ __launch_bounds__(256) void conv_f32_tile_kernel(const float* __restrict__ x, int Cin, int B, int Hin, int Win,
+                                                            const float* __restrict__ w, const float* __restrict__ bias, int Cout,
+                                                            int ksize, int stride, int ups, const float* __restrict__ temb,
+                                                            const float* residual, const int* __restrict__ tile_idx, int Ma, int tile,
+                                                            int tile_w, int Ho, int Wo, float* y) {
+    constexpr int BM = 32, BN = 64;
+    constexpr int KQ = BK / 4;                           // float4 pieces per row of a chunk
+    constexpr int BL = BN * KQ / 256;                    // weight pieces per thread
+    constexpr int A_THREADS = BM * KQ < 256 ? BM * KQ : 256;
+    __shared__ float As[BK][BM + 1];
+    __shared__ __attribute__((aligned(16))) float Bs[BK][BN];
+    __shared__ int rb[BM], ry[BM], rx[BM];
+    const int t = threadIdx.x, rows = B * Ma;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    if (t < BM) {
+        const int gm = m0 + t;
+        int b = -1, oy = 0, ox = 0;
+        if (gm < rows) { b = gm / Ma; active_pixel(tile_idx, gm % Ma, tile, tile_w, Wo / tile_w, oy, ox); }
+        rb[t] = b; ry[t] = oy; rx[t] = ox;
+    }
+    __syncthreads();
+    const int lane = t & 63, wave = t >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int pad = ksize >> 1;
+    f32x16v acc0 = {}, acc1 = {};                        // this wave's partial sums: columns 0..31 and 32..63 of the tile
+    const int la_row = (t / KQ) % BM, la_k = (t % KQ) * 4;        // A piece of this thread (threads below A_THREADS)
+    const int lb_col = t / KQ, lb_k = (t % KQ) * 4;              // B pieces: columns lb_col + j * (256 / KQ)
+    const int chunks = Cin / BK, total = ksize * ksize * chunks;
+    float4 ra[2], rbv[2][BL];                            // two chunks in flight
+    auto fetch = [&](int it, float4& a4, float4 (&b4)[BL]) {      // chunk `it` = (tap, channel offset) -> registers
+        const int tap = it / chunks, c0 = (it - tap * chunks) * BK;
+        const int ky = tap / ksize, kx = tap - ky * ksize;
+        a4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (t < A_THREADS && rb[la_row] >= 0) {
+            const int oy = ry[la_row], ox = rx[la_row], b = rb[la_row];
+            long long apix = -1;
+            if (ups) {
+                const int uy = oy + ky - pad, ux = ox + kx - pad;
+                if (uy >= 0 && uy < 2 * Hin && ux >= 0 && ux < 2 * Win) apix = ((long long)b * Hin + (uy >> 1)) * Win + (ux >> 1);
+            } else {
+                const int iy = oy * stride + ky - pad, ix = ox * stride + kx - pad;
+                if (iy >= 0 && iy < Hin && ix >= 0 && ix < Win) apix = ((long long)b * Hin + iy) * Win + ix;
+            }
+            if (apix >= 0) a4 = *reinterpret_cast<const float4*>(x + apix * Cin + c0 + la_k);
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int wcol = n0 + lb_col + j * (256 / KQ);
+            b4[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (wcol < Cout) b4[j] = *reinterpret_cast<const float4*>(w + ((size_t)wcol * ksize * ksize + tap) * Cin + c0 + lb_k);
+        }
+    };
+    // one chunk: registers of slot S -> LDS, refill the slot with the chunk two ahead, multiply
+    auto chunk = [&](int it, float4& a4, float4 (&b4)[BL]) {
+        if (t < A_THREADS) { As[la_k + 0][la_row] = a4.x; As[la_k + 1][la_row] = a4.y; As[la_k + 2][la_row] = a4.z; As[la_k + 3][la_row] = a4.w; }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int col = lb_col + j * (256 / KQ);
+            Bs[lb_k + 0][col] = b4[j].x; Bs[lb_k + 1][col] = b4[j].y; Bs[lb_k + 2][col] = b4[j].z; Bs[lb_k + 3][col] = b4[j].w;
+        }
+        __syncthreads();
+        if (it + 2 < total) fetch(it + 2, a4, b4);       // in flight during this chunk's and the next chunk's products
+        // wave w: K offsets [w * BK / 4, (w + 1) * BK / 4) of the chunk, two at a time (lane half hl takes the second)
+#pragma unroll
+        for (int kk = 0; kk < BK / 4; kk += 2) {
+            const int k = wave * (BK / 4) + kk + hl;
+            const float av = As[k][l32];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bs[k][l32], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bs[k][32 + l32], acc1, 0, 0, 0);
+        }
+        __syncthreads();
+    };
+    fetch(0, ra[0], rbv[0]);
+    if (total > 1) fetch(1, ra[1], rbv[1]);
+    for (int it = 0; it < total; it += 2) {
+        chunk(it, ra[0], rbv[0]);
+        if (it + 1 < total) chunk(it + 1, ra[1], rbv[1]);
+    }
+    // ---- the four partial tiles through LDS, summed in wave order; then four consecutive columns of one row per thread
+    __shared__ __attribute__((aligned(16))) float part[4][BM][BN + 4];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int r = (e >> 2) * 8 + hl * 4 + (e & 3);
+        part[wave][r][l32] = acc0[e]; part[wave][r][32 + l32] = acc1[e];
+    }
+    __syncthreads();
+    const int tr = t >> 4, tc = t & 15;                  // this thread: rows 2 tr, 2 tr + 1; columns 4 tc .. 4 tc + 3
+    float acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float v = 0.f;
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) v += part[w4][tr * 2 + i][tc * 4 + q];
+            acc[i][q] = v;
+        }
+    const int col = n0 + tc * 4;
+    if (col >= Cout) return;                             // Cout % 4 == 0: a group of four is inside or outside as a whole
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = tr * 2 + i;
+        if (rb[r] < 0) continue;
+        const size_t o = (((size_t)rb[r] * Ho + ry[r]) * Wo + rx[r]) * Cout + col;
+        float v[4] = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (bias) v[q] += bias[col + q];
+            if (temb) v[q] += temb[rb[r] * Cout + col + q];
+            if (residual) v[q] += residual[o + q];
+        }
+        *reinterpret_cast<float4*>(y + o) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
 static int tile_cols(const fise_conv_args* a) { return a->tile_w > 0 ? a->tile_w : a->tile; }
 
 static int validate(const fise_conv_args* a, int& Ho, int& Wo) {
@@ -176,6 +297,17 @@ int conv_dispatch(const fise_conv_args* a, void* workspace, size_t workspace_byt
             return FISE_OK;
         }
         if (nview && a->dtype != FISE_BF16) return fail(FISE_ERR_DTYPE, "fise_masked_conv: normalised copies need bf16 maps");
+        if (a->dtype == FISE_F32 && a->C1 == 0 && !a->gn_mean && a->C0 % 16 == 0 && a->Cout % 4 == 0) {
+            const int Ma = a->n_active * a->tile * tile_cols(a), rows = a->B * Ma;
+            const dim3 grid(ceil_div(rows, 32), ceil_div(a->Cout, 64));
+#define FISE_F32_CONV(BKV) hipLaunchKernelGGL(conv_f32_tile_kernel<BKV>, grid, dim3(256), 0, st, (const float*)a->x0, a->C0, a->B, a->H, a->W, \
+                               (const float*)a->w, (const float*)a->bias, a->Cout, a->ksize, a->stride, a->upsample ? 1 : 0, a->temb,            \
+                               (const float*)a->residual, a->tile_idx, Ma, a->tile, tile_cols(a), Ho, Wo, (float*)a->y_cache)
+            if (a->C0 % 32 == 0) FISE_F32_CONV(32); else FISE_F32_CONV(16);
+#undef FISE_F32_CONV
+            FISE_CHECK_LAUNCH("fise_masked_conv(fp32 tile)");
+            return FISE_OK;
+        }
         if (a->dtype == FISE_F32) launch_scalar<float>(a, Ho, Wo, st, nullptr, 0);
         else launch_scalar<bf16_t>(a, Ho, Wo, st, views, nview);
         FISE_CHECK_LAUNCH("fise_masked_conv(scalar)");

@@ -152,6 +152,42 @@ def test_bf16_conv_variants(fb, case):
         check_map(host(y2), oracle(ix), cache.astype(np.float64), active_mask(ix, t, Ho, Wo), TOL[dt], f"{name} unsplit n={ix.size}")
 
 
+F32_CASES = [
+    # name, B, H, W, Cin, Cout, k, stride, ups, tile(out), temb, res, frac  -- fp32 maps: the tiled float kernel (Cin % 16 == 0,
+    # Cout % 4 == 0) and, for the last two, the scalar kernel it falls back to
+    ("f32-c3", 2, 16, 16, 32, 64, 3, 1, 0, 4, True, True, 0.2),
+    ("f32-ragged-n-rows", 1, 12, 20, 48, 76, 3, 1, 0, 2, False, True, 0.13),
+    ("f32-c1-temb", 2, 16, 16, 64, 40, 1, 1, 0, 4, True, False, 0.2),
+    ("f32-ds", 2, 16, 16, 16, 32, 3, 2, 0, 2, False, False, 0.2),
+    ("f32-us-rect", 1, 8, 8, 32, 32, 3, 1, 1, (4, 2), False, True, 0.15),
+    ("f32-wide-n", 1, 8, 8, 16, 200, 3, 1, 0, 1, True, False, 0.3),
+    ("f32-scalar-cin12", 1, 8, 8, 12, 16, 3, 1, 0, 2, False, True, 0.3),
+    ("f32-scalar-cout6", 1, 8, 8, 16, 6, 3, 1, 0, 2, True, False, 0.3),
+]
+
+
+@pytest.mark.parametrize("case", F32_CASES, ids=[c[0] for c in F32_CASES])
+def test_f32_conv_variants(fb, case):
+    name, B, H, W, Ci, Co, k, stride, ups, t, use_temb, use_res, frac = case
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    Ho, Wo = (2 * H, 2 * W) if ups else (H // stride, W // stride)
+    x = wl.normal(rng, (B, H, W, Ci), 1.0, mean=0.2)
+    w = wl.normal(rng, (Co, k, k, Ci), 1 / math.sqrt(k * k * Ci)); bias = wl.normal(rng, (Co,), 0.1)
+    temb = wl.normal(rng, (B, Co), 0.3) if use_temb else None
+    res = wl.normal(rng, (B, Ho, Wo, Co), 1.0) if use_res else None
+    cache = wl.normal(rng, (B, Ho, Wo, Co), 1.0)
+    _, idx = fo.tiles_from_pixels(wl.ellipse_pixels(rng, Ho, Wo, frac), t)
+    th, tw = (t[0], t[1]) if isinstance(t, tuple) else (t, 0)
+    for ix in (idx, fo.full_index(Ho, Wo, t), np.zeros(0, np.int32)):
+        want = fo.masked_conv(x, w, bias, ix, t, cache.astype(np.float64).copy(), "f32", stride=stride, upsample=bool(ups), temb=temb, residual=res)
+        y = dev(cache)
+        a = fb.conv_args(dev(x), dev(w), dev(bias), idx_dev(ix), ix.size, th, y, ksize=k, stride=stride, upsample=ups,
+                         temb=dev(temb) if use_temb else None, residual=dev(res) if use_res else None, tile_w=tw)
+        fb.fise_masked_conv(a)
+        act = active_mask(ix, t, Ho, Wo) if ix.size else np.zeros((Ho, Wo), bool)
+        check_map(host(y), want, cache.astype(np.float64), act, TOL["f32"], name)
+
+
 def test_conv_residual_in_place(fb):
     """residual may alias y_cache (the ResNet shortcut is parked in the output map)."""
     rng = np.random.default_rng(77)
