@@ -260,12 +260,12 @@ def main():
         fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)          # a1 + a2 (device only)
         fb.fise_masked_unet_step(u, Wd, caches[i % ncache], lat_new, t_sin_all[i % T], kv_new, index, n_active, bt, mode, None, ws)
 
-    def timed(n, n_active, index):
+    def timed(n, n_active, index, mode=fb.FISE_STATS_CACHED):
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for i in range(n):
-            step(i, n_active, index)
+            step(i, n_active, index, mode)
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
@@ -314,11 +314,13 @@ def main():
     for i in range(args.warmup):
         step(i, na, idx)
     ms_masked = timed(args.steps, na, idx)
-    ms_dense = None
+    ms_dense = ms_dense_fresh = None
     if not args.no_dense:
         for i in range(2):
             step(i, ntiles, full)
         ms_dense = timed(max(3, min(args.steps, 10)), ntiles, full)
+        # what building one timestep's cache costs: the same pass with statistics computed from the maps
+        ms_dense_fresh = timed(max(3, min(args.steps, 10)), ntiles, full, fb.FISE_STATS_FRESH)
 
     # ---- records of the other configurations and of how the step scales with the mask (not part of `value`)
     sweeps = None
@@ -448,7 +450,7 @@ def main():
                                 f"config 5: SD-1.5-shaped UNet step, batch 2, latent {args.latent}x{args.latent}x4, context 77x768, "
                                 "seeded blob, 8x8 base tiles; mask detect + masked step per timed step"),
                    "pixel_fraction": float(pix.mean()), "active_tile_fraction": na / ntiles, "tile": bt, "caches_cycled": ncache},
-        "masked_ms": ms_masked, "dense_ms": ms_dense, "end_to_end_ms": ms_masked * args.steps,
+        "masked_ms": ms_masked, "dense_ms": ms_dense, "dense_fresh_stats_ms": ms_dense_fresh, "end_to_end_ms": ms_masked * args.steps,
         "speedup_vs_dense": (ms_dense / ms_masked) if ms_dense else None, "speedup_vs_dense_target": 4.0,
         "frac_of_weight_floor": (nW * 2 / (HBM_PEAK_GBS * 1e6)) / ms_masked,
         "unet_calls_per_s": 1e3 / ms_masked, "useful_tflops": flops_masked / ms_masked / 1e9,

@@ -3,6 +3,8 @@
 // (8 TB/s, 2.5 PFLOP/s dense bf16) are what fractions are quoted against; these two figures
 // say how much of them any kernel could see at all.
 #include "common.h"
+#include <algorithm>
+#include <cstdlib>
 
 namespace fise {
 
@@ -10,6 +12,23 @@ namespace fise {
 __global__ __launch_bounds__(256) void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+// The same copy with four loads in flight per lane before the first store (each a full 4 KiB per wave apart, so every
+// wave-wide access stays one contiguous kilobyte); the ceiling reported is the better of the two.
+__global__ __launch_bounds__(256) void calib_stream4_kernel(const uint4* __restrict__ src_, uint4* __restrict__ dst_, size_t n) {
+    typedef unsigned u32x4v __attribute__((ext_vector_type(4)));
+    const u32x4v* src = (const u32x4v*)src_;
+    u32x4v* dst = (u32x4v*)dst_;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const u32x4v v0 = __builtin_nontemporal_load(src + i), v1 = __builtin_nontemporal_load(src + i + stride);
+        const u32x4v v2 = __builtin_nontemporal_load(src + i + 2 * stride), v3 = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(v0, dst + i); __builtin_nontemporal_store(v1, dst + i + stride);
+        __builtin_nontemporal_store(v2, dst + i + 2 * stride); __builtin_nontemporal_store(v3, dst + i + 3 * stride);
+    }
+    for (; i < n; i += stride) dst[i] = src[i];
 }
 
 // Four independent 32x32 accumulators per wave, operands never reloaded: the matrix pipe
@@ -78,6 +97,11 @@ extern "C" int fise_calibrate_peaks(void* scratch, size_t scratch_bytes, double*
     uint4* dst = (uint4*)((char*)scratch + half);
     double ms = 0;
     if (int e = best_of([&] { hipLaunchKernelGGL(calib_copy_kernel, dim3(256 * 16), dim3(256), 0, st, src, dst, n16); }, 5, st, &ms)) return e;
+    double ms4 = 0;
+    if (int e = best_of([&] { hipLaunchKernelGGL(calib_stream4_kernel, dim3(256 * 8), dim3(256), 0, st, src, dst, n16); }, 5, st, &ms4)) return e;
+    if (std::getenv("FISE_DEBUG")) fprintf(stderr, "[fise] copy ceilings: plain %.0f GB/s, four in flight %.0f GB/s\n",
+                                           2.0 * half / (ms * 1e-3) / 1e9, 2.0 * half / (ms4 * 1e-3) / 1e9);
+    ms = std::min(ms, ms4);
     *copy_gbs = 2.0 * (double)half / (ms * 1e-3) / 1e9;              // bytes read + bytes written
     float* sink = (float*)scratch;
     static_assert(kSinkBytes <= (size_t(64) << 20), "sink fits the smallest scratch");

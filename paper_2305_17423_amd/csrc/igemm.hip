@@ -1270,13 +1270,10 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
         shmem = (size_t)span * std::min(Cin, per * BK) * sizeof(float2);
         constexpr size_t kMaxDyn = 64 * 1024;
         if (shmem > kMaxDyn) return fail(FISE_ERR_SHAPE, "igemm: GroupNorm table of %zu bytes does not fit in LDS", shmem);
-        static bool raised = false;                 // once per instantiation: static tiles + table may exceed 64 KB
-        if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN, BK, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDyn) != hipSuccess)
-                return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
-            raised = true;
-        }
+        // once per instantiation (static tiles + table may exceed 64 KB); a function-local static initialises thread-safely
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<BM, BN, WGM, WGN, BK, true>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDyn);
+        if (attr != hipSuccess) return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
     }
     const double flops = 2.0 * rows * (double)ncols * ((double)a.K + a.K2);
     const double bytes = 2.0 * ((double)ncols * ((double)a.K + a.K2) + (double)rows * (a.C0 + a.C1 + a.S0 + a.S1) + (double)rows * a.N);
@@ -1289,15 +1286,12 @@ static int launch_bk(IgemmArgs a, const IgemmWorkspace* ws, int prof_kind, hipSt
     if (dma) {
         constexpr int NST = NST_RING;
         constexpr int ring = NST * (BM + BN) * 128;
-        static bool raised = false;                     // once per instantiation
-        if (!raised && ring > 48 * 1024) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, ring) != hipSuccess ||
-                hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, ring) != hipSuccess)
-                return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
-            raised = true;
-        }
+        static const bool raised = ring <= 48 * 1024 ||        // once per instantiation, thread-safe
+            (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, ring) == hipSuccess &&
+             hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<BM, BN, WGM, WGN, NST, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, ring) == hipSuccess);
+        if (!raised) return fail(FISE_ERR_HIP, "igemm: cannot raise the dynamic LDS limit");
         ProfileScope prof(prof_kind, flops, bytes, st);      // brackets the GEMM launch alone
         if (a.a_compact && a.K2 == 0)
             hipLaunchKernelGGL((igemm_dma_kernel<BM, BN, WGM, WGN, NST, true>), grid, dim3(64 * WGM * WGN), ring, st, a);

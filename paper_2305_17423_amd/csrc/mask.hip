@@ -8,43 +8,56 @@ namespace fise {
 
 // ---------------------------------------------------------------------------
 // d = mean_{b,c} |fresh - cached| with a fixed summation order (b outermost, c
-// ascending, float adds), one pixel per thread.  A 64-pixel wave stages
-// [64 pixels x CH channels] slabs through LDS so that global reads are
-// coalesced along channels while each thread still adds its own pixel's
-// channels in ascending order.
+// ascending, float adds), one pixel per lane of the first wave.  The workgroup
+// stages [64 pixels x CH channels] slabs through LDS so that global reads are
+// coalesced along channels while each pixel's channels are still added in
+// ascending order by one lane.
 // ---------------------------------------------------------------------------
-constexpr int DET_PIX = 64;     // pixels per workgroup (one wave)
-constexpr int DET_CH = 64;      // channels staged per slab
+constexpr int DET_PIX = 64;         // pixels per workgroup
+constexpr int DET_CH = 64;          // channels staged per slab
+constexpr int DET_THREADS = 256;    // all four waves load the slab; the first sums it, one pixel per lane
 
 template <typename T>
-__global__ __launch_bounds__(DET_PIX) void pixel_diff_kernel(const T* __restrict__ cached, const T* __restrict__ fresh,
-                                                             int B, int HW, int C, float* __restrict__ d_out,
-                                                             int accumulate, float threshold, uint8_t* __restrict__ pix) {
+__global__ __launch_bounds__(DET_THREADS) void pixel_diff_kernel(const T* __restrict__ cached, const T* __restrict__ fresh,
+                                                                 int B, int HW, int C, float* __restrict__ d_out,
+                                                                 int accumulate, float threshold, uint8_t* __restrict__ pix) {
     __shared__ float slab[DET_PIX][DET_CH + 1];
     const int p0 = blockIdx.x * DET_PIX;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x;
     float s = 0.f;
+    auto absdiff = [&](int b, int pp, int c) {
+        const int p = p0 + pp;
+        if (p >= HW) return 0.f;
+        const size_t off = ((size_t)b * HW + p) * C + c;
+        return fabsf(Elem<T>::ld(fresh + off) - Elem<T>::ld(cached + off));
+    };
     for (int b = 0; b < B; ++b) {
         for (int c0 = 0; c0 < C; c0 += DET_CH) {
             const int nc = min(DET_CH, C - c0);
             // cooperative load: consecutive lanes walk channels of one pixel, then the next pixel
-            for (int e = lane; e < DET_PIX * nc; e += DET_PIX) {
-                const int pp = e / nc, cc = e % nc;
-                const int p = p0 + pp;
-                float v = 0.f;
-                if (p < HW) {
-                    const size_t off = ((size_t)b * HW + p) * C + c0 + cc;
-                    v = fabsf(Elem<T>::ld(fresh + off) - Elem<T>::ld(cached + off));
+            if (nc == DET_CH) {                 // full slab: constant trip count, all loads of a lane in flight together
+                float v[DET_PIX * DET_CH / DET_THREADS];
+#pragma unroll
+                for (int j = 0; j < DET_PIX * DET_CH / DET_THREADS; ++j) {
+                    const int e = tid + j * DET_THREADS;
+                    v[j] = absdiff(b, e / DET_CH, c0 + e % DET_CH);
                 }
-                slab[pp][cc] = v;
+#pragma unroll
+                for (int j = 0; j < DET_PIX * DET_CH / DET_THREADS; ++j) {
+                    const int e = tid + j * DET_THREADS;
+                    slab[e / DET_CH][e % DET_CH] = v[j];
+                }
+            } else {
+                for (int e = tid; e < DET_PIX * nc; e += DET_THREADS) slab[e / nc][e % nc] = absdiff(b, e / nc, c0 + e % nc);
             }
             __syncthreads();
-            for (int cc = 0; cc < nc; ++cc) s = s + slab[lane][cc];
+            if (tid < DET_PIX)
+                for (int cc = 0; cc < nc; ++cc) s = s + slab[tid][cc];
             __syncthreads();
         }
     }
-    const int p = p0 + lane;
-    if (p < HW) {
+    const int p = p0 + tid;
+    if (tid < DET_PIX && p < HW) {
         const float d = s / (float)(B * C);
         if (d_out) d_out[p] = accumulate ? d_out[p] + d : d;
         if (pix) pix[p] = d > threshold ? 1 : 0;
@@ -225,7 +238,7 @@ extern "C" int fise_mask_detect(const void* cached, const void* fresh, int dtype
     if (int e = check_tile("fise_mask_detect", H, W, tile)) return e;
     if (capacity < 0) return fail(FISE_ERR_CAPACITY, "fise_mask_detect: capacity %d", capacity);
     const int HW = H * W;
-    const dim3 grid(ceil_div(HW, DET_PIX)), block(DET_PIX);
+    const dim3 grid(ceil_div(HW, DET_PIX)), block(DET_THREADS);
     if (dtype == FISE_F32)
         hipLaunchKernelGGL(pixel_diff_kernel<float>, grid, block, 0, as_stream(stream), (const float*)cached,
                            (const float*)fresh, B, HW, C, (float*)nullptr, 0, threshold, pix_mask);
@@ -241,7 +254,7 @@ extern "C" int fise_diff_accumulate(const void* cached, const void* fresh, int d
     if (int e = check_map("fise_diff_accumulate", cached, fresh, dtype, B, H, W, C)) return e;
     if (!diff_acc) return fail(FISE_ERR_NULL, "fise_diff_accumulate: null diff_acc");
     const int HW = H * W;
-    const dim3 grid(ceil_div(HW, DET_PIX)), block(DET_PIX);
+    const dim3 grid(ceil_div(HW, DET_PIX)), block(DET_THREADS);
     if (dtype == FISE_F32)
         hipLaunchKernelGGL(pixel_diff_kernel<float>, grid, block, 0, as_stream(stream), (const float*)cached,
                            (const float*)fresh, B, HW, C, diff_acc, 1, 0.f, (uint8_t*)nullptr);
