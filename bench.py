@@ -362,33 +362,82 @@ def main():
     if args.host_spill:
         from paper_2305_17423_amd.cache_ring import CacheRing
         nsp = min(max(ncache, 4), 16)
-        t0 = time.time()
-        ring = CacheRing(nsp, cbytes, dev, host_spill=True, slots=3)
-        for i in range(nsp):
-            ring.store(i, caches[i % ncache])
-        log(f"[bench] host spill: {nsp} caches of {cbytes / 1e6:.0f} MB in pinned memory, set up in {time.time() - t0:.1f} s")
+        nmod = len(fb.fise_unet_module_names(u))
+        L = fb.fise_unet_cache_layout(u)
+        # what a masked step must see of a cache, counted from the layout and this mask (bytes per step)
+        lvl_px = []                                       # per level: (active pixels, active + ring pixels, all pixels)
+        tm_h = tm.reshape(H // bt, W // bt).bool().cpu().numpy()
+        for l in range(len(d["mults"])):
+            t = bt >> l
+            m = np.kron(tm_h, np.ones((t, t), bool))
+            p = np.pad(m, 1)
+            ring_m = np.logical_or.reduce([p[1 + dy:1 + dy + m.shape[0], 1 + dx:1 + dx + m.shape[1]] for dy in (-1, 0, 1) for dx in (-1, 0, 1)])
+            lvl_px.append((int(m.sum()), int(ring_m.sum()), m.size))
+        spill = {"caches": nsp, "slots": 3, "resident_ms": ms_masked, "cache_bytes": cbytes, "layout": L, "modes": {}}
+        # whole buffers by the copy engines; the active tiles (+ ring) by kernels; the tile rows holding active tiles by the
+        # copy engines - the last two with the K / V^T blocks at home in host memory or on the device
+        for mode in ("whole", "active-host", "active-device", "rows-host", "rows-device"):
+            t0 = time.time()
+            ring = (CacheRing(nsp, cbytes, dev, host_spill=True, slots=3) if mode == "whole" else
+                    CacheRing(nsp, cbytes, dev, host_spill=True, slots=3, unet=u, kv_home=mode.split("-")[1],
+                              transfer="kernel" if mode.startswith("active") else "dma"))
+            for i in range(nsp):
+                ring.store(i, caches[i % ncache])
+            ring.begin_edit(idx, na, bt)
+            log(f"[bench] host spill ({mode}): {nsp} caches in pinned memory, set up in {time.time() - t0:.1f} s")
 
-        def spill_steps(n, write_back):
-            for i in range(n):
-                c = ring.acquire(i)
+            def spill_steps(n, write_back):
+                for i in range(n):
+                    c = ring.acquire(i)
+                    fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)
+                    if ring.trust_derived:
+                        fb.fise_masked_unet_step(u, Wd, c, lat_new, t_sin_all[i % T], kv_new, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
+                    else:
+                        fb.fise_masked_unet_modules(u, Wd, c, lat_new, t_sin_all[i % T], kv_new, idx, na, bt, fb.FISE_STATS_CACHED,
+                                                    None, 0, nmod, ws)
+                    ring.release(i, write_back=write_back)
+
+            def spill_ms(write_back):
+                spill_steps(nsp, write_back)
+                torch.cuda.synchronize()
+                t1 = time.time()
+                spill_steps(args.steps, write_back)
+                torch.cuda.synchronize()
+                return (time.time() - t1) * 1e3 / args.steps
+            ms_spill, ms_in_only = spill_ms(True), spill_ms(False)
+            spill["modes"][mode] = {"ms_per_step": ms_spill, "ms_per_step_copy_in_only": ms_in_only}
+
+            def alone(fn):                  # the transfers of one step with nothing else running
+                torch.cuda.synchronize()
+                t1 = time.time()
+                for i in range(8):
+                    fn(i % nsp, i % ring.slots)
+                torch.cuda.synchronize()
+                return (time.time() - t1) * 1e3 / 8
+            with torch.cuda.stream(ring.h2d):
+                spill["modes"][mode]["copy_in_alone_ms"] = alone(ring._copy_in)
+            with torch.cuda.stream(ring.d2h):
+                spill["modes"][mode]["copy_out_alone_ms"] = alone(ring._copy_out)
+            log(f"[bench] host spill ({mode}): transfers alone: in {spill['modes'][mode]['copy_in_alone_ms']:.3f} ms, "
+                f"out {spill['modes'][mode]['copy_out_alone_ms']:.3f} ms per step")
+            log(f"[bench] host spill ({mode}): {ms_spill:.3f} ms per step with write-back, {ms_in_only:.3f} ms copy-in only, "
+                f"vs {ms_masked:.3f} ms resident")
+            del ring
+            torch.cuda.empty_cache()
+        if not args.no_dense:           # the untrusted walk alone (derived maps recomputed), caches resident: the compute the active modes hide behind
+            def walk(i):
                 fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm, tm, idx, nact)
-                fb.fise_masked_unet_step(u, Wd, c, lat_new, t_sin_all[i % T], kv_new, idx, na, bt, fb.FISE_STATS_CACHED, None, ws)
-                ring.release(i, write_back=write_back)
-
-        def spill_ms(write_back):
-            spill_steps(nsp, write_back)
+                fb.fise_masked_unet_modules(u, Wd, caches[i % ncache], lat_new, t_sin_all[i % T], kv_new, idx, na, bt, fb.FISE_STATS_CACHED,
+                                            None, 0, nmod, ws)
+            for i in range(3):
+                walk(i)
             torch.cuda.synchronize()
             t1 = time.time()
-            spill_steps(args.steps, write_back)
+            for i in range(args.steps):
+                walk(i)
             torch.cuda.synchronize()
-            return (time.time() - t1) * 1e3 / args.steps
-        ms_spill, ms_in_only = spill_ms(True), spill_ms(False)
-        spill = {"ms_per_step": ms_spill, "ms_per_step_copy_in_only": ms_in_only, "caches": nsp, "slots": 3,
-                 "bytes_each_way_per_step": cbytes, "link_gbs_each_way": cbytes / ms_spill / 1e6,
-                 "link_gbs_copy_in_only": cbytes / ms_in_only / 1e6}
-        log(f"[bench] host spill: {ms_spill:.3f} ms per step with write-back ({cbytes / ms_spill / 1e6:.1f} GB/s in and out at once), "
-            f"{ms_in_only:.3f} ms copy-in only ({cbytes / ms_in_only / 1e6:.1f} GB/s), vs {ms_masked:.3f} ms resident")
-        del ring
+            spill["resident_untrusted_walk_ms"] = (time.time() - t1) * 1e3 / args.steps
+        spill["pixels_per_level_active_ring_all"] = lvl_px
 
     # ---- per-kernel accounting with HIP events on the launch stream (separate passes: the events
     # widen the gaps between kernels, so these passes are not the timed ones)

@@ -318,6 +318,7 @@ typedef struct fise_unet fise_unet;   /* host-only plan: owns no device memory *
 
 int fise_unet_create(const fise_unet_desc* desc /* host */, fise_unet** out /* host */);
 void fise_unet_destroy(fise_unet* u);
+int fise_unet_desc_get(const fise_unet* u, fise_unet_desc* out /* host */);   /* the description the plan was made from */
 
 /* Flat buffers.  `kind` 0 = weights (bf16 elements; offset/numel in elements),
  * 1 = per-step cache, the tensors the method stores (offset/numel in BYTES; maps
@@ -343,6 +344,64 @@ size_t fise_unet_workspace_bytes(const fise_unet* u, int max_active_tiles, int b
 size_t fise_unet_refresh_derived_workspace_bytes(const fise_unet* u);
 int fise_unet_refresh_derived(const fise_unet* u, const void* weights, void* cache, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Moving a per-step cache between memories (section "Cache-based editing
+ * pipeline": the cached activations of every denoising step are kept between
+ * edits and moved between GPU and CPU memory by transfers that overlap the
+ * computation).  A masked step touches little of a cache: it READS the stored
+ * maps at the active tiles and the one-pixel ring around them, the K / V^T
+ * caches of the attention layers in full, and the statistics; it WRITES the
+ * stored maps at the active tiles and K rows / V^T columns at the active tokens.
+ * These calls move exactly that, so a cache that lives in pinned host memory
+ * (or in another device buffer) passes through a device slot at a fraction of
+ * its size per step.
+ *
+ * The cache buffer is laid out in contiguous groups (byte ranges below):
+ *   [maps_off, +maps_bytes)          stored maps (bf16 [B, H_l, W_l, C])
+ *   [kv_off, +kv_bytes)              K [B, H_l*W_l, C] and V^T [B, C, H_l*W_l] of every transformer block
+ *   [small_off, +small_bytes)        GroupNorm statistics, then the scale / shift tables
+ *   [derived_maps_off, +derived_maps_bytes)   normalised copies of maps (derived)
+ * stored_bytes = end of the statistics = everything the method stores.  The kv
+ * and small ranges are moved by the caller with plain copies (hipMemcpyAsync).
+ *
+ * fise_unet_cache_move_active copies, from `src` to `dst` (both laid out as a
+ * cache buffer; the same byte offsets are read and written), the pixels
+ *   halo = 0: inside the active tiles,  halo = 1: those and the ring of one pixel
+ * around them (clipped to the map; a pixel is moved once even where rings overlap),
+ * each at its own level's resolution, of the tensor groups named in `what`:
+ *   FISE_MOVE_MAPS  rows of the stored maps,  FISE_MOVE_K  rows of every K cache,
+ *   FISE_MOVE_VT  columns of every V^T cache.
+ * Fetch before a masked step: MAPS with halo 1 (+ plain copies of kv and small);
+ * write-back after it: MAPS | K | VT with halo 0.  A slot filled this way holds no
+ * valid derived maps: run the step with fise_masked_unet_modules over all modules,
+ * which recomputes them where it reads them.
+ * src and dst must be memory the GPU can address: device memory, or host memory
+ * allocated pinned by the HIP runtime (hipHostMalloc); anything else is refused
+ * (FISE_ERR_ALIGN) before a launch.  They must not overlap.  workspace (device):
+ * fise_unet_cache_move_workspace_bytes(u).  n_active == 0 moves nothing.
+ * Enqueued on `stream`; no allocation, no synchronisation. */
+typedef struct {
+    int64_t maps_off, maps_bytes, kv_off, kv_bytes, small_off, small_bytes, derived_maps_off, derived_maps_bytes;
+    int64_t stored_bytes;
+} fise_unet_cache_layout;
+enum { FISE_MOVE_MAPS = 1, FISE_MOVE_K = 2, FISE_MOVE_VT = 4 };
+int fise_unet_cache_layout_get(const fise_unet* u, fise_unet_cache_layout* out /* host */);
+size_t fise_unet_cache_move_workspace_bytes(const fise_unet* u);
+int fise_unet_cache_move_active(const fise_unet* u, const void* src, void* dst, const int32_t* tile_idx, int n_active,
+                                int base_tile, int halo, int what, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same move done by the copy engines instead of kernels: whole pixel rows.  tile_rows
+ * (HOST int32 pairs [first, last) of rows of the base tile grid, ascending, disjoint)
+ * names the tile rows that hold active tiles; for every stored map (FISE_MOVE_MAPS) and
+ * every K cache (FISE_MOVE_K) the pixel rows of those tile rows at the tensor's own
+ * level - plus one row above and below with halo = 1 - are copied in full width, one
+ * hipMemcpyAsync per (tensor, batch element, run of rows).  A superset of what
+ * fise_unet_cache_move_active moves (full rows instead of tiles), for transfers that
+ * must overlap a running step: no kernel is launched.  src / dst: any memory
+ * hipMemcpyAsync accepts (pinned host memory for a copy that is really asynchronous). */
+int fise_unet_cache_move_tile_rows(const fise_unet* u, const void* src, void* dst, const int32_t* tile_rows /* host */,
+                                   int n_ranges, int base_tile, int halo, int what, void* stream);
 
 /* Context K/V of every transformer block for one conditioning ctx[B,n_ctx,ctx_dim]. */
 int fise_unet_context_kv(const fise_unet* u, const void* weights, const void* ctx, void* ctxkv,

@@ -108,6 +108,11 @@ _SIGS = {
     "fise_unet_refresh_derived_workspace_bytes": (sz, [vp]),
     "fise_unet_refresh_derived": (i32, [vp, vp, vp, vp, sz, vp]),
     "fise_unet_context_kv": (i32, [vp, vp, vp, vp, vp, sz, vp]),
+    "fise_unet_cache_layout_get": (i32, [vp, vp]),
+    "fise_unet_desc_get": (i32, [vp, vp]),
+    "fise_unet_cache_move_workspace_bytes": (sz, [vp]),
+    "fise_unet_cache_move_active": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]),
+    "fise_unet_cache_move_tile_rows": (i32, [vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp]),
     "fise_masked_unet_step": (i32, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(i32), vp, sz, vp]),
     "fise_profile_enable": (i32, [i32]),
     "fise_profile_calibrate": (i32, [i32, vp]),
@@ -388,6 +393,16 @@ def fise_unet_destroy(u):
     lib().fise_unet_destroy(u)
 
 
+def fise_unet_desc_of(u):
+    """The description a plan was made from, as the dict make_desc() takes."""
+    s = fise_unet_desc()
+    _ck(lib().fise_unet_desc_get(u, C.byref(s)))
+    n = s.n_levels
+    return dict(in_ch=s.in_ch, out_ch=s.out_ch, base=s.base, mults=tuple(s.mults[i] for i in range(n)),
+                attn=tuple(bool(s.attn[i]) for i in range(n)), layers=s.layers, heads=s.heads, ctx_dim=s.ctx_dim,
+                n_ctx=s.n_ctx, groups=s.groups, H=s.H, W=s.W, B=s.B)
+
+
 def fise_unet_tensors(u, kind):
     """[(name, offset, numel)] of the flat weight (0), cache (1) or context-K/V (2) buffer."""
     out = []
@@ -422,6 +437,35 @@ def fise_unet_refresh_derived_workspace_bytes(u):
 def fise_unet_refresh_derived(u, weights, cache, workspace, stream=None):
     _ck(lib().fise_unet_refresh_derived(u, _p(weights), _p(cache), _p(workspace), workspace.numel() * workspace.element_size(),
                                         _stream(stream)))
+
+
+FISE_MOVE_MAPS, FISE_MOVE_K, FISE_MOVE_VT = 1, 2, 4
+_LAYOUT_FIELDS = ("maps_off", "maps_bytes", "kv_off", "kv_bytes", "small_off", "small_bytes", "derived_maps_off",
+                  "derived_maps_bytes", "stored_bytes")
+
+
+def fise_unet_cache_layout(u):
+    """{field: bytes} of the contiguous tensor groups of a per-step cache buffer."""
+    raw = (i64 * len(_LAYOUT_FIELDS))()
+    _ck(lib().fise_unet_cache_layout_get(u, raw))
+    return dict(zip(_LAYOUT_FIELDS, (int(v) for v in raw)))
+
+
+def fise_unet_cache_move_workspace_bytes(u):
+    return lib().fise_unet_cache_move_workspace_bytes(u)
+
+
+def fise_unet_cache_move_active(u, src, dst, tile_idx, n_active, base_tile, halo, what, workspace, stream=None):
+    """src / dst: cache-sized uint8 tensors in device memory or pinned host memory."""
+    _ck(lib().fise_unet_cache_move_active(u, _p(src), _p(dst), _p(tile_idx), n_active, base_tile, halo, what, _p(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fise_unet_cache_move_tile_rows(u, src, dst, tile_rows, base_tile, halo, what, stream=None):
+    """tile_rows: [(first, last), ...] rows of the base tile grid (host integers)."""
+    flat = [int(v) for r in tile_rows for v in r]
+    arr = (i32 * max(len(flat), 1))(*flat)
+    _ck(lib().fise_unet_cache_move_tile_rows(u, _p(src), _p(dst), arr, len(flat) // 2, base_tile, halo, what, _stream(stream)))
 
 
 def fise_unet_context_kv(u, weights, ctx, ctxkv, stream=None):

@@ -2,6 +2,7 @@
 // layouts) and the launch sequence.  Every module is a short chain of the gathered
 // GEMM, row LayerNorm and active-query attention kernels, all enqueued on the
 // caller's stream; nothing here allocates or synchronises.
+#include <algorithm>
 #include <cmath>
 #include <map>
 #include <string>
@@ -22,6 +23,9 @@ size_t transformer_ws_bytes(const fise_transformer_args* a);
 using namespace fise;
 
 namespace {
+// One pixel-addressed cache tensor for the cache-moving kernels.  rows: [B, H*W, row_bytes] (a map, or K);
+// vt: [B, C, H*W] two-byte elements (V transposed).
+struct MoveEntry { long long off; int row_bytes; short lvl; short vt; };
 struct Tensor { std::string name; int64_t off; int64_t numel; };
 enum Kind { K_CONV_IN, K_RES, K_TR, K_DS, K_US, K_OUT };
 // A consumer of a module's output map that normalises it first: consumer module, and whether the map is the
@@ -42,6 +46,8 @@ struct fise_unet {
     std::map<std::string, int> index[4];
     int64_t weight_elems = 0; size_t cache_bytes = 0, ctxkv_bytes = 0;
     int temb_total = 0, n_stride = 0;
+    fise_unet_cache_layout layout{};                 // byte ranges of the groups of cache tensors
+    std::vector<MoveEntry> move_maps, move_k, move_vt;   // pixel-addressed tensors of the stored part, by group
 
     int64_t add(int kind, const std::string& name, int64_t numel, int64_t& cursor, int64_t align) {
         cursor = (cursor + align - 1) / align * align;
@@ -139,42 +145,55 @@ static void build_plan(fise_unet* u) {
     }
     u->weight_elems = (wc + 7) / 8 * 8;
 
-    // ---- per-step cache (bytes, 256-byte aligned): maps bf16, statistics float
+    // ---- per-step cache (bytes, 256-byte aligned): maps bf16, statistics float.  Tensors are grouped so that each
+    // group is one contiguous byte range: [stored maps][K, V^T][statistics][scale / shift tables][derived maps].
+    // The first three groups are what the method stores, the last two are derived from them.
     int64_t cc = 0;
     const int64_t B = d.B, G = d.groups;
+    auto HW = [&](const Module& m) { return (int64_t)(d.H >> m.lvl) * (d.W >> m.lvl); };
+    auto map_entry = [&](int64_t off, const Module& m, int C) { u->move_maps.push_back({off, C * 2, (short)m.lvl, 0}); };
     for (const Module& m : mods) {
         const std::string& n = m.name;
-        const int64_t hw = (int64_t)(d.H >> m.lvl) * (d.W >> m.lvl);
-        auto stat = [&](const std::string& g) { u->add(1, n + "." + g + ".mean", B * G * 4, cc, 256); u->add(1, n + "." + g + ".rstd", B * G * 4, cc, 256); };
-        switch (m.kind) {
-        case K_CONV_IN: u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256); break;
-        case K_RES:
-            stat("gn1"); stat("gn2");
-            u->add(1, n + ".h1", B * hw * m.cout * 2, cc, 256); u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256);
-            break;
-        case K_TR:
-            stat("gn");
-            u->add(1, n + ".k", B * hw * m.cout * 2, cc, 256); u->add(1, n + ".v", B * hw * m.cout * 2, cc, 256);
-            u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256);
-            break;
-        case K_DS: case K_US: u->add(1, n + ".out", B * hw * m.cout * 2, cc, 256); break;
-        case K_OUT: stat("gn"); u->add(1, "eps", B * hw * m.cout * 2, cc, 256); break;
-        }
+        const int64_t hw = HW(m);
+        if (m.kind == K_RES) map_entry(u->add(1, n + ".h1", B * hw * m.cout * 2, cc, 256), m, m.cout);
+        map_entry(u->add(1, m.kind == K_OUT ? std::string("eps") : n + ".out", B * hw * m.cout * 2, cc, 256), m, m.cout);
     }
+    u->layout.maps_off = 0; u->layout.maps_bytes = cc = (cc + 255) / 256 * 256;
+    for (const Module& m : mods)
+        if (m.kind == K_TR) {
+            u->move_k.push_back({u->add(1, m.name + ".k", B * HW(m) * m.cout * 2, cc, 256), m.cout * 2, (short)m.lvl, 0});
+            u->move_vt.push_back({u->add(1, m.name + ".v", B * HW(m) * m.cout * 2, cc, 256), m.cout, (short)m.lvl, 1});
+        }
+    cc = (cc + 255) / 256 * 256;
+    u->layout.kv_off = u->layout.maps_bytes; u->layout.kv_bytes = cc - u->layout.kv_off;
+    u->layout.small_off = cc;
+    for (const Module& m : mods) {
+        const std::string& n = m.name;
+        auto stat = [&](const std::string& g) { u->add(1, n + "." + g + ".mean", B * G * 4, cc, 256); u->add(1, n + "." + g + ".rstd", B * G * 4, cc, 256); };
+        if (m.kind == K_RES) { stat("gn1"); stat("gn2"); }
+        else if (m.kind == K_TR || m.kind == K_OUT) stat("gn");
+    }
+    cc = (cc + 255) / 256 * 256;
+    u->layout.stored_bytes = cc;
     // ---- derived tensors, in the same buffer behind the stored ones (bytes): what the masked step would otherwise
     // recompute from stored maps + cached statistics at every call.  ResNet: activated inputs of both convolutions
     // and the scale / shift tables of both GroupNorms; transformer: the normalised input of the 1x1 in and its table.
     for (const Module& m : mods) {
         const std::string& n = m.name;
-        const int64_t hw = (int64_t)(d.H >> m.lvl) * (d.W >> m.lvl), ci = m.cin + m.cskip;
-        if (m.kind == K_RES) {
-            u->add(3, n + ".a1", B * hw * ci * 2, cc, 256); u->add(3, n + ".a2", B * hw * m.cout * 2, cc, 256);
-            u->add(3, n + ".gn1.ss", B * ci * 8, cc, 256);  u->add(3, n + ".gn2.ss", B * m.cout * 8, cc, 256);
-        } else if (m.kind == K_TR) {
-            u->add(3, n + ".gx", B * hw * m.cout * 2, cc, 256); u->add(3, n + ".gn.ss", B * m.cout * 8, cc, 256);
-        }
+        if (m.kind == K_RES) { u->add(3, n + ".gn1.ss", B * (m.cin + m.cskip) * 8, cc, 256);  u->add(3, n + ".gn2.ss", B * m.cout * 8, cc, 256); }
+        else if (m.kind == K_TR) u->add(3, n + ".gn.ss", B * m.cout * 8, cc, 256);
+    }
+    cc = (cc + 255) / 256 * 256;
+    u->layout.small_bytes = cc - u->layout.small_off;
+    u->layout.derived_maps_off = cc;
+    for (const Module& m : mods) {
+        const std::string& n = m.name;
+        const int64_t hw = HW(m), ci = m.cin + m.cskip;
+        if (m.kind == K_RES) { u->add(3, n + ".a1", B * hw * ci * 2, cc, 256); u->add(3, n + ".a2", B * hw * m.cout * 2, cc, 256); }
+        else if (m.kind == K_TR) u->add(3, n + ".gx", B * hw * m.cout * 2, cc, 256);
     }
     u->cache_bytes = (size_t)((cc + 255) / 256 * 256);
+    u->layout.derived_maps_bytes = (int64_t)u->cache_bytes - u->layout.derived_maps_off;
     // ---- who normalises whose output
     std::map<std::string, int> producer;
     for (int i = 0; i < (int)mods.size(); ++i) producer[mods[i].kind == K_OUT ? std::string("eps") : mods[i].name + ".out"] = i;
@@ -226,6 +245,12 @@ extern "C" int fise_unet_create(const fise_unet_desc* desc, fise_unet** out) {
 }
 
 extern "C" void fise_unet_destroy(fise_unet* u) { delete u; }
+
+extern "C" int fise_unet_desc_get(const fise_unet* u, fise_unet_desc* out) {
+    if (!u || !out) return fail(FISE_ERR_NULL, "fise_unet_desc_get: null pointer");
+    *out = u->d;
+    return FISE_OK;
+}
 
 extern "C" int fise_unet_num_tensors(const fise_unet* u, int kind) {
     if (!u || kind < 0 || kind > 3) return fail(FISE_ERR_NULL, "fise_unet_num_tensors: bad arguments");
@@ -519,6 +544,234 @@ extern "C" int fise_unet_refresh_derived(const fise_unet* u, const void* weights
             if (int e = launch_gn_scale_shift(Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), Wp(n + ".gn.g"), Wp(n + ".gn.b"), B, m.cout, G, (float2*)Dp(n + ".gn.ss"), st)) return e;
             if (int e = launch_gn_act_halo(Cp(m.in_map), nullptr, m.cout, 0, B, H, W, Cf(n + ".gn.mean"), Cf(n + ".gn.rstd"), Wp(n + ".gn.g"), Wp(n + ".gn.b"), G, 0,
                                            idx_full, ntiles, tile, Dp(n + ".gx"), st)) return e;
+        }
+    }
+    return FISE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Moving the part of a cache that a masked step reads or writes (see the header).
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int MOVE_BATCH = 64;          // entries per launch (they travel as kernel arguments)
+// Workgroups per entry; each lane strides over the entry's pieces.  Kept small on purpose: these kernels run beside
+// the step's own launches on another stream, and lanes waiting on the host link would otherwise fill every wave slot of
+// the device (64 workgroups per entry slowed the concurrent step by a third); 8 x 256 lanes x 16 bytes per entry and
+// ~60 entries in flight are far more than the link's bandwidth-delay product.
+constexpr int MOVE_GX = 8;
+struct MoveLevels { int list_off[FISE_MAX_LEVELS]; int hw[FISE_MAX_LEVELS]; };
+struct MoveArgs { MoveEntry e[MOVE_BATCH]; MoveLevels lv; int B; };
+
+// Workgroup l lists, ascending, the pixels of level l that lie in an active tile (halo 0) or within one pixel of
+// one (halo 1): tile flags in LDS, then an ordered compaction (wave ballot + popcount prefix) 256 pixels at a time.
+__global__ __launch_bounds__(256) void cache_pixel_list_kernel(const int* __restrict__ tile_idx, int n_active, int tiles_w, int tiles_h,
+                                                               int base_tile, int H, int W, int halo, const MoveLevels lv,
+                                                               int* __restrict__ lists, int* __restrict__ counts) {
+    extern __shared__ unsigned char tmask[];
+    __shared__ int wave_cnt[4];
+    const int l = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nt = tiles_w * tiles_h;
+    for (int i = tid; i < nt; i += 256) tmask[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_active; i += 256) {
+        const int t = tile_idx[i];
+        if ((unsigned)t < (unsigned)nt) tmask[t] = 1;
+    }
+    __syncthreads();
+    const int t = base_tile >> l, Hl = H >> l, Wl = W >> l, n = Hl * Wl;
+    int* list = lists + lv.list_off[l];
+    int base = 0;
+    for (int c0 = 0; c0 < n; c0 += 256) {
+        const int p = c0 + tid;
+        bool need = false;
+        if (p < n) {
+            const int y = p / Wl, x = p % Wl;
+            for (int dy = -halo; dy <= halo; ++dy)
+                for (int dx = -halo; dx <= halo; ++dx) {
+                    const int yy = y + dy, xx = x + dx;
+                    if (yy >= 0 && yy < Hl && xx >= 0 && xx < Wl) need |= tmask[(yy / t) * tiles_w + xx / t] != 0;
+                }
+        }
+        const unsigned long long bal = __ballot(need);
+        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave] = __popcll(bal);
+        __syncthreads();
+        int off = base, total = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) off += wave_cnt[w];
+            total += wave_cnt[w];
+        }
+        if (need) list[off + before] = p;
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) counts[l] = base;
+}
+
+// dst[addr] = src[addr] for every listed pixel of every entry: 16-byte pieces of a pixel's row (two-byte pieces when
+// the row is not a multiple of 16 bytes), or one two-byte element per (channel, pixel) of a transposed tensor.
+__global__ __launch_bounds__(256) void cache_move_kernel(const MoveArgs a, const int* __restrict__ lists, const int* __restrict__ counts,
+                                                         const unsigned char* __restrict__ src, unsigned char* __restrict__ dst) {
+    const MoveEntry e = a.e[blockIdx.y];
+    const unsigned cnt = (unsigned)counts[e.lvl], hw = (unsigned)a.lv.hw[e.lvl];
+    if (cnt == 0) return;
+    const int* list = lists + a.lv.list_off[e.lvl];
+    const unsigned stride = gridDim.x * 256u, w0 = blockIdx.x * 256u + threadIdx.x;
+    if (e.vt) {
+        const unsigned total = cnt * (unsigned)a.B * (unsigned)e.row_bytes;         // row_bytes = channels here
+        for (unsigned w = w0; w < total; w += stride) {
+            const unsigned pi = w % cnt, bc = w / cnt;
+            const size_t addr = (size_t)e.off + ((size_t)bc * hw + (unsigned)list[pi]) * 2;
+            *(unsigned short*)(dst + addr) = *(const unsigned short*)(src + addr);
+        }
+    } else if ((e.row_bytes & 15) == 0) {
+        const unsigned pieces = (unsigned)e.row_bytes >> 4, total = cnt * (unsigned)a.B * pieces;
+        for (unsigned w = w0; w < total; w += stride) {
+            const unsigned piece = w % pieces, pb = w / pieces, pi = pb % cnt, b = pb / cnt;
+            const size_t addr = (size_t)e.off + ((size_t)b * hw + (unsigned)list[pi]) * (unsigned)e.row_bytes + piece * 16u;
+            *(uint4*)(dst + addr) = *(const uint4*)(src + addr);
+        }
+    } else {
+        const unsigned pieces = (unsigned)e.row_bytes >> 1, total = cnt * (unsigned)a.B * pieces;
+        for (unsigned w = w0; w < total; w += stride) {
+            const unsigned piece = w % pieces, pb = w / pieces, pi = pb % cnt, b = pb / cnt;
+            const size_t addr = (size_t)e.off + ((size_t)b * hw + (unsigned)list[pi]) * (unsigned)e.row_bytes + piece * 2u;
+            *(unsigned short*)(dst + addr) = *(const unsigned short*)(src + addr);
+        }
+    }
+}
+
+// The address under which the GPU reaches p: device memory as it is, pinned host memory through its mapping.
+int gpu_address(const char* fn, const char* what, const void* p, void** out) {
+    hipPointerAttribute_t at{};
+    if (hipPointerGetAttributes(&at, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(FISE_ERR_ALIGN, "%s: %s %p is neither device memory nor pinned host memory", fn, what, p);
+    }
+    if (at.type == hipMemoryTypeDevice) { *out = const_cast<void*>(p); return FISE_OK; }
+    if (at.type == hipMemoryTypeHost && at.devicePointer) { *out = at.devicePointer; return FISE_OK; }
+    return fail(FISE_ERR_ALIGN, "%s: %s %p is neither device memory nor pinned host memory", fn, what, p);
+}
+
+size_t move_lists_ints(const fise_unet_desc& d) {
+    size_t n = 0;
+    for (int l = 0; l < d.n_levels; ++l) n += (size_t)(d.H >> l) * (d.W >> l);
+    return n;
+}
+}  // namespace
+
+extern "C" int fise_unet_cache_layout_get(const fise_unet* u, fise_unet_cache_layout* out) {
+    if (!u || !out) return fail(FISE_ERR_NULL, "fise_unet_cache_layout_get: null pointer");
+    *out = u->layout;
+    return FISE_OK;
+}
+
+extern "C" size_t fise_unet_cache_move_workspace_bytes(const fise_unet* u) {
+    if (!u) return 0;
+    return align256((move_lists_ints(u->d) + FISE_MAX_LEVELS) * sizeof(int));
+}
+
+extern "C" int fise_unet_cache_move_active(const fise_unet* u, const void* src, void* dst, const int32_t* tile_idx, int n_active,
+                                           int base_tile, int halo, int what, void* workspace, size_t workspace_bytes, void* stream) {
+    const char* fn = "fise_unet_cache_move_active";
+    if (!u || !src || !dst) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    const fise_unet_desc& d = u->d;
+    const int nl = d.n_levels;
+    if (base_tile < 1 || base_tile % (1 << (nl - 1)) || d.H % base_tile || d.W % base_tile)
+        return fail(FISE_ERR_SHAPE, "%s: base_tile %d must divide H, W and be a multiple of %d", fn, base_tile, 1 << (nl - 1));
+    const int tiles_w = d.W / base_tile, tiles_h = d.H / base_tile, tiles_total = tiles_w * tiles_h;
+    if (n_active < 0 || n_active > tiles_total) return fail(FISE_ERR_CAPACITY, "%s: n_active %d of %d tiles", fn, n_active, tiles_total);
+    if (halo != 0 && halo != 1) return fail(FISE_ERR_SHAPE, "%s: halo %d (0 or 1)", fn, halo);
+    if (what & ~(FISE_MOVE_MAPS | FISE_MOVE_K | FISE_MOVE_VT)) return fail(FISE_ERR_SHAPE, "%s: unknown bits in what = %d", fn, what);
+    if (n_active == 0 || what == 0) return FISE_OK;
+    if (!tile_idx || !workspace) return fail(FISE_ERR_NULL, "%s: null tile_idx or workspace", fn);
+    if (workspace_bytes < fise_unet_cache_move_workspace_bytes(u)) return fail(FISE_ERR_CAPACITY, "%s: workspace too small", fn);
+    if (tiles_total > 48 * 1024) return fail(FISE_ERR_CAPACITY, "%s: %d tiles exceed the tile-flag table of 48 K entries", fn, tiles_total);
+    int cmax = std::max(d.in_ch, d.out_ch);
+    for (int l = 0; l < nl; ++l) cmax = std::max(cmax, d.base * d.mults[l]);
+    if ((size_t)d.B * d.H * d.W * cmax >= ((size_t)1 << 32))          // the kernels count pieces in 32 bits
+        return fail(FISE_ERR_CAPACITY, "%s: maps too large for 32-bit piece counters", fn);
+    if (!aligned16(src) || !aligned16(dst) || !aligned16(workspace)) return fail(FISE_ERR_ALIGN, "%s: pointers must be 16-byte aligned", fn);
+    const char* sb = (const char*)src; const char* db = (const char*)dst;
+    if (sb < db + u->cache_bytes && db < sb + u->cache_bytes) return fail(FISE_ERR_SHAPE, "%s: src and dst overlap", fn);
+    void* gsrc = nullptr; void* gdst = nullptr;
+    if (int e = gpu_address(fn, "src", src, &gsrc)) return e;
+    if (int e = gpu_address(fn, "dst", dst, &gdst)) return e;
+
+    hipStream_t st = as_stream(stream);
+    MoveArgs args{};
+    int off = 0;
+    for (int l = 0; l < nl; ++l) { args.lv.list_off[l] = off; args.lv.hw[l] = (d.H >> l) * (d.W >> l); off += args.lv.hw[l]; }
+    args.B = d.B;
+    int* lists = (int*)workspace;
+    int* counts = lists + off;
+    hipLaunchKernelGGL(cache_pixel_list_kernel, dim3(nl), dim3(256), (size_t)tiles_total, st, tile_idx, n_active, tiles_w, tiles_h, base_tile,
+                       d.H, d.W, halo, args.lv, lists, counts);
+    FISE_CHECK_LAUNCH("cache pixel lists");
+    const std::vector<MoveEntry>* groups[3] = {&u->move_maps, &u->move_k, &u->move_vt};
+    for (int g = 0; g < 3; ++g) {
+        if (!(what & (1 << g))) continue;
+        const std::vector<MoveEntry>& v = *groups[g];
+        for (size_t i0 = 0; i0 < v.size(); i0 += MOVE_BATCH) {
+            const int n = (int)std::min<size_t>(MOVE_BATCH, v.size() - i0);
+            for (int i = 0; i < n; ++i) args.e[i] = v[i0 + i];
+            hipLaunchKernelGGL(cache_move_kernel, dim3(MOVE_GX, n), dim3(256), 0, st, args, lists, counts, (const unsigned char*)gsrc,
+                               (unsigned char*)gdst);
+            FISE_CHECK_LAUNCH("cache move");
+        }
+    }
+    return FISE_OK;
+}
+
+// The same move by the copy engines: whole pixel rows of the map levels, one asynchronous copy per (tensor, batch
+// element, run of rows).  No kernel runs, so nothing competes with the step's launches for the compute units or sits
+// in front of their end-of-kernel cache maintenance (measured: lanes of a concurrent kernel waiting on the host link
+// make every launch of the step 2-3x longer while they are in flight; copy-engine transfers do not).
+extern "C" int fise_unet_cache_move_tile_rows(const fise_unet* u, const void* src, void* dst, const int32_t* tile_rows, int n_ranges,
+                                              int base_tile, int halo, int what, void* stream) {
+    const char* fn = "fise_unet_cache_move_tile_rows";
+    if (!u || !src || !dst) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    const fise_unet_desc& d = u->d;
+    const int nl = d.n_levels;
+    if (base_tile < 1 || base_tile % (1 << (nl - 1)) || d.H % base_tile || d.W % base_tile)
+        return fail(FISE_ERR_SHAPE, "%s: base_tile %d must divide H, W and be a multiple of %d", fn, base_tile, 1 << (nl - 1));
+    if (halo != 0 && halo != 1) return fail(FISE_ERR_SHAPE, "%s: halo %d (0 or 1)", fn, halo);
+    if (what & ~(FISE_MOVE_MAPS | FISE_MOVE_K)) return fail(FISE_ERR_SHAPE, "%s: what = %d (maps and K rows only; V^T is not row-addressed)", fn, what);
+    if (n_ranges < 0) return fail(FISE_ERR_CAPACITY, "%s: n_ranges %d", fn, n_ranges);
+    if (n_ranges == 0 || what == 0) return FISE_OK;
+    if (!tile_rows) return fail(FISE_ERR_NULL, "%s: null tile_rows", fn);
+    const int tiles_h = d.H / base_tile;
+    for (int r = 0; r < n_ranges; ++r) {
+        const int a = tile_rows[2 * r], b = tile_rows[2 * r + 1];
+        if (a < 0 || b <= a || b > tiles_h || (r > 0 && a < tile_rows[2 * r - 1]))
+            return fail(FISE_ERR_SHAPE, "%s: range %d = [%d, %d) must be non-empty, ascending, disjoint and inside %d tile rows", fn, r, a, b, tiles_h);
+    }
+    const char* sb = (const char*)src; char* db = (char*)dst;
+    if (sb < db + u->cache_bytes && db < sb + u->cache_bytes) return fail(FISE_ERR_SHAPE, "%s: src and dst overlap", fn);
+    hipStream_t st = as_stream(stream);
+    // runs of pixel rows per level (ranges that touch after the ring is added are merged)
+    std::vector<std::pair<int, int>> runs[FISE_MAX_LEVELS];
+    for (int l = 0; l < nl; ++l) {
+        const int t = base_tile >> l, Hl = d.H >> l;
+        for (int r = 0; r < n_ranges; ++r) {
+            const int y0 = std::max(0, tile_rows[2 * r] * t - halo), y1 = std::min(Hl, tile_rows[2 * r + 1] * t + halo);
+            if (!runs[l].empty() && y0 <= runs[l].back().second) runs[l].back().second = std::max(runs[l].back().second, y1);
+            else runs[l].push_back({y0, y1});
+        }
+    }
+    const std::vector<MoveEntry>* groups[2] = {&u->move_maps, &u->move_k};
+    for (int g = 0; g < 2; ++g) {
+        if (!(what & (1 << g))) continue;
+        for (const MoveEntry& e : *groups[g]) {
+            const size_t Hl = (size_t)(d.H >> e.lvl), row = (size_t)(d.W >> e.lvl) * e.row_bytes;
+            for (int b = 0; b < d.B; ++b)
+                for (const auto& run : runs[e.lvl]) {
+                    const size_t off = (size_t)e.off + ((size_t)b * Hl + run.first) * row;
+                    if (hipMemcpyAsync(db + off, sb + off, (size_t)(run.second - run.first) * row, hipMemcpyDefault, st) != hipSuccess) {
+                        (void)hipGetLastError();
+                        return fail(FISE_ERR_HIP, "%s: hipMemcpyAsync failed", fn);
+                    }
+                }
         }
     }
     return FISE_OK;

@@ -5,7 +5,8 @@ Old generation, on the oracle: dense step at t0, deterministic sampler update, d
 timestep.  New generation, on both sides from those caches: the latent is perturbed inside a blob, the mask is
 detected once, masked step at t0 with the new conditioning, the sampler update applied at active pixels only (the
 rest of the latent follows the old trajectory), masked step at t1 on the second cache.  Every stored tensor of both
-caches and the intermediate latent are compared with the oracle."""
+caches and the intermediate latent are compared with the oracle.  The same two steps are then run with the caches in
+pinned host memory, passing through device slots that receive only what a masked step reads: bit-identical results."""
 import numpy as np
 import pytest
 import torch
@@ -75,17 +76,50 @@ def test_two_masked_steps_vs_oracle(fb, scratch, capsys):
     fb.fise_mask_detect(x0d, x0nd, 0.1, bt, pm, tm, idxd, nact)
     na = int(nact.item())
     assert na == idx.size and np.array_equal(idxd.cpu().numpy()[:na], idx)
-    c0, c1 = pack_cache(fb, u, cache0, Wd), pack_cache(fb, u, cache1, Wd)
-    fb.fise_masked_unet_step(u, Wd, c0, x0nd, dev(ts[0]), kvd, idxd, na, bt, fb.FISE_STATS_CACHED, None, ws)
-    got0 = unpack_cache(fb, u, c0, shapes)
     off, nbytes = next((o, n) for nm, o, n in fb.fise_unet_tensors(u, 1) if nm == "eps")
-    eps_d = c0[off:off + nbytes].view(torch.bfloat16).reshape(B, H, W, d["out_ch"]).float()
     actd = torch.from_numpy(act).to(DEV)
-    x1nd = dev(x1, "bf16").clone()
-    upd = (a * x0nd.float() + b * eps_d).to(torch.bfloat16)              # the harness' update, float32 then stored
-    x1nd[:, actd] = upd[:, actd]
-    fb.fise_masked_unet_step(u, Wd, c1, x1nd, dev(ts[1]), kvd, idxd, na, bt, fb.FISE_STATS_CACHED, None, ws)
-    got1 = unpack_cache(fb, u, c1, shapes)
+    nmod = len(fb.fise_unet_module_names(u))
+
+    def run_device(residency):
+        """The two steps with both caches resident, or living in pinned host memory and passing through device slots
+        that receive only what a masked step reads (K / V^T home in host memory or on the device)."""
+        from paper_2305_17423_amd.cache_ring import CacheRing
+        c0, c1 = pack_cache(fb, u, cache0, Wd), pack_cache(fb, u, cache1, Wd)
+        if residency == "resident":
+            ring = CacheRing(2, c0.numel(), DEV)
+        else:
+            _, home, transfer = residency.split("-")
+            ring = CacheRing(2, c0.numel(), DEV, host_spill=True, slots=2, unet=u, kv_home=home, transfer=transfer)
+        ring.store(0, c0); ring.store(1, c1)
+        del c0, c1
+        ring.begin_edit(idxd, na, bt)
+
+        def step(c, lat, t_sin):
+            if ring.trust_derived:
+                fb.fise_masked_unet_step(u, Wd, c, lat, t_sin, kvd, idxd, na, bt, fb.FISE_STATS_CACHED, None, ws)
+            else:       # a slot holds no derived maps: the module walk recomputes them where it reads them
+                fb.fise_masked_unet_modules(u, Wd, c, lat, t_sin, kvd, idxd, na, bt, fb.FISE_STATS_CACHED, None, 0, nmod, ws)
+        c = ring.acquire(0)
+        step(c, x0nd, dev(ts[0]))
+        eps_d = c[off:off + nbytes].view(torch.bfloat16).reshape(B, H, W, d["out_ch"]).float()
+        x1nd = dev(x1, "bf16").clone()
+        upd = (a * x0nd.float() + b * eps_d).to(torch.bfloat16)              # the harness' update, float32 then stored
+        x1nd[:, actd] = upd[:, actd]
+        ring.release(0)
+        c = ring.acquire(1)
+        step(c, x1nd, dev(ts[1]))
+        ring.release(1)
+        g0, g1 = unpack_cache(fb, u, ring.fetch(0), shapes), unpack_cache(fb, u, ring.fetch(1), shapes)
+        return g0, g1, x1nd
+
+    got0, got1, x1nd = run_device("resident")
+    for residency in ("spill-host-kernel", "spill-device-kernel", "spill-host-dma", "spill-device-dma"):
+        s0, s1, sx = run_device(residency)
+        assert torch.equal(sx, x1nd), residency
+        for k in shapes:
+            assert np.array_equal(s0[k], got0[k]), f"{residency}: {k} of the first cache differs from the resident run"
+            assert np.array_equal(s1[k], got1[k]), f"{residency}: {k} of the second cache differs from the resident run"
+        say(f"{residency}: both caches bit-identical to the resident run")
     torch.cuda.synchronize()
 
     sm = scratch == "bf16"
