@@ -23,11 +23,14 @@ Residency modes behind one interface:
   fise_masked_unet_modules over all modules (`ring.trust_derived` is False).
   `kv_home="device"` keeps every step's K / V^T block in HBM (21 % of a cache)
   and moves it slot <-> home with device copies, so the link carries maps only.
-  `transfer="dma"` (default) moves whole pixel rows of the tile rows that hold
-  active tiles with the copy engines (fise_unet_cache_move_tile_rows: no kernel,
-  so the step's own launches are not disturbed); `transfer="kernel"` moves
-  exactly the active tiles (+ ring) with kernels, less data but the kernels'
-  accesses to host memory slow every concurrent launch of the step.
+  `transfer="kernel"` moves exactly the active tiles (+ ring) with kernels:
+  least data, but while their accesses to host memory are in flight every
+  concurrent launch of the step runs 2-3x longer.  `transfer="dma"` moves whole
+  pixel rows of the tile rows that hold active tiles with the copy engines
+  (fise_unet_cache_move_tile_rows: no kernel, the step's launches are not
+  disturbed), about twice the data in ~150 copies per direction, and the K / V^T
+  block whole.  Default: "dma" with kv_home="device", "kernel" otherwise (the
+  faster of the two in each case, measured on SD-1.5 shapes).
 
 Memory and stream plumbing around the library (torch tensors, streams, events);
 the only kernels are the library's own cache-moving ones.
@@ -39,16 +42,16 @@ import torch
 
 class CacheRing:
     def __init__(self, n_steps: int, cache_bytes: int, device="cuda:0", host_spill: bool = False, slots: int = 3,
-                 unet=None, kv_home: str = "host", transfer: str = "dma"):
+                 unet=None, kv_home: str = "host", transfer: str | None = None):
         if n_steps < 1 or cache_bytes < 1:
             raise ValueError("n_steps and cache_bytes must be positive")
         if host_spill and slots < 2:
             raise ValueError("host spill needs at least two device slots (one computing, one in flight)")
         if kv_home not in ("host", "device"):
             raise ValueError("kv_home is 'host' or 'device'")
-        if transfer not in ("dma", "kernel"):
-            raise ValueError("transfer is 'dma' or 'kernel'")
-        self.transfer = transfer
+        if transfer not in (None, "dma", "kernel"):
+            raise ValueError("transfer is 'dma', 'kernel' or None (pick by kv_home)")
+        self.transfer = transfer or ("dma" if kv_home == "device" else "kernel")
         self.n_steps, self.cache_bytes, self.device, self.host_spill = n_steps, cache_bytes, device, host_spill
         self.sparse = bool(host_spill and unet is not None)
         self.trust_derived = not self.sparse
