@@ -33,32 +33,24 @@ def level_of(name, nl):
     return 0            # conv_in.out, eps
 
 
-@pytest.mark.parametrize("halo", [0, 1])
-@pytest.mark.parametrize("where", ["device", "host_to_device", "device_to_host"])
-def test_cache_move_active_moves_exactly_the_named_bytes(fb, halo, where):
-    d = uo.tiny_desc(H=32, W=32, base=64)
-    u = fb.fise_unet_create(d)
-    H, W, B, bt, nl = d["H"], d["W"], d["B"], 8, len(d["mults"])
+def check_move_active(fb, u, d, bt, tiles, halo, where, whats, seed):
+    """fise_unet_cache_move_active against the definition written out: dst == src on the named bytes, untouched elsewhere."""
+    H, W, B, nl = d["H"], d["W"], d["B"], len(d["mults"])
     cb = fb.fise_unet_cache_bytes(u)
-    L = fb.fise_unet_cache_layout(u)
-    assert 0 == L["maps_off"] < L["kv_off"] == L["maps_bytes"] and L["kv_off"] + L["kv_bytes"] == L["small_off"]
-    assert L["small_off"] < L["stored_bytes"] < L["small_off"] + L["small_bytes"] == L["derived_maps_off"]
-    assert L["derived_maps_off"] + L["derived_maps_bytes"] == cb
-    g = torch.Generator(device="cpu").manual_seed(17)
+    g = torch.Generator(device="cpu").manual_seed(seed)
     src_h = torch.randint(1, 256, (cb,), dtype=torch.uint8, generator=g)          # no zero byte: a moved byte shows
-    tiles = np.array([0, 5, 6, 10, 15], np.int32)          # corners (ring clipped at the border), neighbours (rings overlap)
     idx = idx_dev(tiles)
     ws = torch.zeros(fb.fise_unet_cache_move_workspace_bytes(u), dtype=torch.uint8, device=DEV)
     src = src_h.pin_memory() if where == "host_to_device" else src_h.to(DEV)
     dst = torch.zeros(cb, dtype=torch.uint8, pin_memory=True) if where == "device_to_host" else torch.zeros(cb, dtype=torch.uint8, device=DEV)
-    for what in (fb.FISE_MOVE_MAPS, fb.FISE_MOVE_K | fb.FISE_MOVE_VT, fb.FISE_MOVE_MAPS | fb.FISE_MOVE_K | fb.FISE_MOVE_VT):
+    srcn = src_h.numpy()
+    for what in whats:
         dst.zero_()
         torch.cuda.synchronize()
         fb.fise_unet_cache_move_active(u, src, dst, idx, tiles.size, bt, halo, what, ws)
         torch.cuda.synchronize()
         got = dst.cpu().numpy()
         want = np.zeros(cb, np.uint8)
-        srcn = src_h.numpy()
         for name, off, nbytes in fb.fise_unet_tensors(u, 1):
             if name.endswith((".mean", ".rstd")):
                 continue
@@ -81,6 +73,33 @@ def test_cache_move_active_moves_exactly_the_named_bytes(fb, halo, where):
             want[off:off + nbytes][sel] = srcn[off:off + nbytes][sel]
         assert np.array_equal(got, want), f"what={what}: {np.count_nonzero(got != want)} bytes differ"
         assert np.count_nonzero(want) > 0
+    return src, dst, idx, ws
+
+
+def test_cache_move_active_at_sd15_size(fb):
+    """The bench's configuration: SD-1.5 shapes, 64x64 latent, 12 of 64 tiles, pinned host memory -> device slot."""
+    d = uo.sd15_desc()
+    u = fb.fise_unet_create(d)
+    tiles = np.array([18, 19, 20, 26, 27, 28, 29, 34, 35, 36, 37, 43], np.int32)
+    check_move_active(fb, u, d, 8, tiles, 1, "host_to_device", [fb.FISE_MOVE_MAPS], 29)
+    check_move_active(fb, u, d, 8, tiles, 0, "device_to_host", [fb.FISE_MOVE_MAPS | fb.FISE_MOVE_K | fb.FISE_MOVE_VT], 31)
+    fb.fise_unet_destroy(u)
+
+
+@pytest.mark.parametrize("halo", [0, 1])
+@pytest.mark.parametrize("where", ["device", "host_to_device", "device_to_host"])
+def test_cache_move_active_moves_exactly_the_named_bytes(fb, halo, where):
+    d = uo.tiny_desc(H=32, W=32, base=64)
+    u = fb.fise_unet_create(d)
+    bt = 8
+    cb = fb.fise_unet_cache_bytes(u)
+    L = fb.fise_unet_cache_layout(u)
+    assert 0 == L["maps_off"] < L["kv_off"] == L["maps_bytes"] and L["kv_off"] + L["kv_bytes"] == L["small_off"]
+    assert L["small_off"] < L["stored_bytes"] < L["small_off"] + L["small_bytes"] == L["derived_maps_off"]
+    assert L["derived_maps_off"] + L["derived_maps_bytes"] == cb
+    tiles = np.array([0, 5, 6, 10, 15], np.int32)          # corners (ring clipped at the border), neighbours (rings overlap)
+    src, dst, idx, ws = check_move_active(fb, u, d, bt, tiles, halo, where,
+                                          (fb.FISE_MOVE_MAPS, fb.FISE_MOVE_K | fb.FISE_MOVE_VT, fb.FISE_MOVE_MAPS | fb.FISE_MOVE_K | fb.FISE_MOVE_VT), 17)
     # nothing to move, and arguments refused before any launch
     dst.zero_(); torch.cuda.synchronize()
     fb.fise_unet_cache_move_active(u, src, dst, idx, 0, bt, halo, fb.FISE_MOVE_MAPS, ws)
