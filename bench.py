@@ -68,7 +68,8 @@ def sinusoid(t, dim):
     return np.concatenate([np.cos(a), np.sin(a)], 1).astype(np.float32)
 
 
-def run_sweeps(fb, wl, np, torch, dev, u, d, Wd, cache, lat_new, t_sin, kv_new, ws, bt, ntiles, full, args, gen, timed, step):
+def run_sweeps(fb, wl, np, torch, dev, u, d, Wd, cache, lat_new, t_sin, kv_new, ws, bt, ntiles, full, args, gen, timed, step,
+               session_caches=(), lat_old=None, n_det=0):
     """Latency records for the other configurations: how the step scales with the mask (1-50 %), one module of each kind
     at every level against the same kernels run dense (configs 2 and 4, with the crossover), the attention sub-layers at
     2-20 % active queries on 4x4 tiles (config 3), and the single fp32 convolution (config 1)."""
@@ -115,6 +116,50 @@ def run_sweeps(fb, wl, np, torch, dev, u, d, Wd, cache, lat_new, t_sin, kv_new, 
         dens.append({"pixel_fraction": f, "active_tiles": n, "tiles": ntiles, "ms_per_step": timed(10, n, buf)})
     out["step_vs_mask_density"] = dens
     log("[bench] step vs blob size: " + ", ".join(f"{r['pixel_fraction'] * 100:.0f} % -> {r['active_tiles']} tiles {r['ms_per_step']:.3f} ms" for r in dens))
+
+    # ---- independent edit sessions side by side (one stream, workspace, mask and cache each; the weights shared): how much
+    # of the device one session's chain of short dependent launches leaves to others.  Each session is a HIP graph of
+    # `reps` steps (detect + masked step), the graphs are replayed together.
+    if args.sessions and len(session_caches) >= 2:
+        reps, conc = 8, []
+        f10, n10, _ = lists[2]
+        sess = []
+        for j in range(min(max(args.sessions), len(session_caches))):
+            st_j = torch.cuda.Stream()
+            ws_j = torch.zeros_like(ws)
+            pm_j = torch.zeros((H, W), dtype=torch.uint8, device=dev); tm_j = torch.zeros(ntiles, dtype=torch.uint8, device=dev)
+            ix_j = torch.zeros(ntiles, dtype=torch.int32, device=dev); na_j = torch.zeros(1, dtype=torch.int32, device=dev)
+
+            def one(c=session_caches[j], ws_j=ws_j, pm_j=pm_j, tm_j=tm_j, ix_j=ix_j, na_j=na_j):
+                fb.fise_mask_detect(lat_old, lat_new, 0.1, bt, pm_j, tm_j, ix_j, na_j)
+                fb.fise_masked_unet_step(u, Wd, c, lat_new, t_sin, kv_new, ix_j, n_det, bt, fb.FISE_STATS_CACHED, None, ws_j)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(st_j):
+                one()
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph, stream=st_j):
+                    for _ in range(reps):
+                        one()
+            torch.cuda.synchronize()
+            sess.append((st_j, graph, (ws_j, pm_j, tm_j, ix_j, na_j)))
+        for n in args.sessions:
+            if n > len(sess):
+                continue
+            best = None
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for st_j, graph, _ in sess[:n]:
+                    with torch.cuda.stream(st_j):
+                        graph.replay()
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) * 1e3
+                best = dt if best is None else min(best, dt)
+            conc.append({"sessions": n, "ms_per_step_of_each_session": best / reps, "aggregate_steps_per_s": n * reps / best * 1e3})
+        out["concurrent_edit_sessions"] = conc
+        log("[bench] independent sessions side by side: " + ", ".join(f"{r['sessions']} -> {r['ms_per_step_of_each_session']:.3f} ms per step each, "
+                                                                       f"{r['aggregate_steps_per_s']:.0f} steps/s" for r in conc))
+        del sess
 
     # ---- one module of each kind per level, alone (config 2 = the first row; config 4 = levels 1 and 2)
     names = fb.fise_unet_module_names(u)
@@ -184,6 +229,8 @@ def main():
     ap.add_argument("--latent", type=int, default=64, help="latent edge (64 = the headline workload; 96 = 768x768 images)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--sessions", type=int, nargs="*", default=[1, 2, 4, 8],
+                    help="sweep: independent edit sessions run side by side on streams of their own")
     ap.add_argument("--seed", type=int, default=5000)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB elementwise copy (for scaling FETCH_SIZE / WRITE_SIZE counter readings)")
@@ -326,7 +373,7 @@ def main():
     sweeps = None
     if not args.no_sweeps and not args.small:
         sweeps = run_sweeps(fb, wl, np, torch, dev, u, d, Wd, caches[0], lat_new, t_sin_all[0], kv_new, ws, bt, ntiles, full, args, gen,
-                            timed, step)
+                            timed, step, session_caches=caches[:8], lat_old=lat_old, n_det=na)
 
     # ---- a whole edit: 50 denoising steps, each = mask detection + masked UNet step on that timestep's cache + the
     # sampler update of the latent at the active pixels (harness arithmetic, a few torch kernels), timed end to end
