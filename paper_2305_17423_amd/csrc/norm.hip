@@ -47,14 +47,65 @@ __global__ __launch_bounds__(256) void gn_partial_kernel(const T* __restrict__ x
     }
 }
 
-// stage 2: one thread per (b, g), chunks summed in index order.
-__global__ void gn_finish_kernel(const double2* __restrict__ partial, int nchunk, int BG, int G, double count, float eps,
-                                 float* __restrict__ mean, float* __restrict__ rstd) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// stage 1 for bf16 maps whose channel counts are multiples of 8: 16-byte loads, and the chunk's pixels dealt to as
+// many pixel stripes as 256 lanes allow (lane = (stripe, 8-channel piece)), so that a lane's loads do not wait for one
+// another.  Stripe sums are float (a dozen terms each), added per channel in stripe order in double.
+__global__ __launch_bounds__(256) void gn_partial_vec_kernel(const bf16_t* __restrict__ x0, const bf16_t* __restrict__ x1, int HW,
+                                                             int C0, int C1, int G, double2* __restrict__ partial) {
+    extern __shared__ double2 chan[];                    // [C0 + C1], then the stripe sums of one pass
+    const int C = C0 + C1, cpg = C / G, CH8 = C / 8, tid = threadIdx.x;
+    float2* stripe = reinterpret_cast<float2*>(chan + C);        // [stripes][pieces of the pass][8]
+    const int b = blockIdx.y, chunk = blockIdx.x, nchunk = gridDim.x;
+    const int p0 = chunk * GS_PIX, p1 = min(HW, p0 + GS_PIX);
+    for (int pc = 0; pc < CH8; pc += 256) {
+        const int CH = min(256, CH8 - pc), PS = 256 / CH;
+        const int cc = tid % CH, ps = tid / CH;
+        if (ps < PS) {
+            const int c = (pc + cc) * 8;
+            const bf16_t* src = c < C0 ? x0 + (size_t)b * HW * C0 + c : x1 + (size_t)b * HW * C1 + (c - C0);
+            const size_t pitch = c < C0 ? C0 : C1;
+            float s[8], q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { s[j] = 0.f; q[j] = 0.f; }
+            for (int p = p0 + ps; p < p1; p += PS) {
+                const uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)p * pitch);
+                const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float lo = __uint_as_float(w[j] << 16), hi = __uint_as_float(w[j] & 0xffff0000u);
+                    s[2 * j] += lo; q[2 * j] += lo * lo; s[2 * j + 1] += hi; q[2 * j + 1] += hi * hi;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) stripe[(ps * CH + cc) * 8 + j] = make_float2(s[j], q[j]);
+        }
+        __syncthreads();
+        for (int i = tid; i < CH * 8; i += 256) {
+            double ds = 0, dq = 0;
+            for (int k = 0; k < PS; ++k) { const float2 v = stripe[k * CH * 8 + i]; ds += (double)v.x; dq += (double)v.y; }
+            chan[pc * 8 + i] = make_double2(ds, dq);
+        }
+        __syncthreads();
+    }
+    for (int g = tid; g < G; g += 256) {
+        double s = 0, q = 0;
+        for (int c = g * cpg; c < (g + 1) * cpg; ++c) { s += chan[c].x; q += chan[c].y; }
+        partial[((size_t)b * nchunk + chunk) * G + g] = make_double2(s, q);
+    }
+}
+
+// stage 2: one wave per (b, g); lane k adds chunks k, k + 64, ... in that order, the 64 lane sums are added in a
+// fixed tree.
+__global__ __launch_bounds__(64) void gn_finish_kernel(const double2* __restrict__ partial, int nchunk, int BG, int G, double count,
+                                                       float eps, float* __restrict__ mean, float* __restrict__ rstd) {
+    const int i = blockIdx.x, lane = threadIdx.x;
     if (i >= BG) return;
     const int b = i / G, g = i % G;
     double s = 0, q = 0;
-    for (int k = 0; k < nchunk; ++k) { const double2 v = partial[((size_t)b * nchunk + k) * G + g]; s += v.x; q += v.y; }
+    for (int k = lane; k < nchunk; k += 64) { const double2 v = partial[((size_t)b * nchunk + k) * G + g]; s += v.x; q += v.y; }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { s += __shfl_down(s, off); q += __shfl_down(q, off); }
+    if (lane != 0) return;
     const double m = s / count;
     double var = q / count - m * m;
     if (var < 0) var = 0;
@@ -345,13 +396,19 @@ static int gn_stats_run(const char* fn, const void* x, const void* x1, int dtype
     const int C = C0 + C1;
     const int HW = H * W, nchunk = ceil_div(HW, GS_PIX);
     const size_t shmem = (size_t)C * sizeof(double2);
+    constexpr size_t kStripeBytes = 256 * 8 * sizeof(float2);
     if (shmem > 64 * 1024) return fail(FISE_ERR_SHAPE, "%s: C=%d too large", fn, C);
-    if (dtype == FISE_F32)
+    const bool vec = dtype == FISE_BF16 && C0 % 8 == 0 && C1 % 8 == 0 && shmem + kStripeBytes <= 64 * 1024 && aligned16(x) &&
+                     (C1 == 0 || aligned16(x1));
+    if (vec)
+        hipLaunchKernelGGL(gn_partial_vec_kernel, dim3(nchunk, B), dim3(256), shmem + kStripeBytes, st, (const bf16_t*)x, (const bf16_t*)x1,
+                           HW, C0, C1, G, partial);
+    else if (dtype == FISE_F32)
         hipLaunchKernelGGL(gn_partial_kernel<float>, dim3(nchunk, B), dim3(256), shmem, st, (const float*)x, (const float*)x1, HW, C0, C1, G, partial);
     else
         hipLaunchKernelGGL(gn_partial_kernel<bf16_t>, dim3(nchunk, B), dim3(256), shmem, st, (const bf16_t*)x, (const bf16_t*)x1, HW, C0, C1, G, partial);
     FISE_CHECK_LAUNCH("fise_groupnorm_stats(partial)");
-    hipLaunchKernelGGL(gn_finish_kernel, dim3(ceil_div(B * G, 64)), dim3(64), 0, st, partial, nchunk, B * G, G,
+    hipLaunchKernelGGL(gn_finish_kernel, dim3(B * G), dim3(64), 0, st, partial, nchunk, B * G, G,
                        (double)HW * (C / G), eps, mean, rstd);
     FISE_CHECK_LAUNCH("fise_groupnorm_stats(finish)");
     return FISE_OK;

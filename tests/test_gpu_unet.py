@@ -42,7 +42,10 @@ def stored_maps(d):
 # One call of the whole step chains ~200 products (116 normalised branches) whose operands the device rounds to bf16, so
 # the device and the float64 oracle drift apart with depth (helpers.py states the law and where it comes from).  Every
 # stored tensor is held
-#   * in relative L2 to min(tol, 3.0e-3 * sqrt(branches upstream)) (cap=False: to the law alone),
+#   * in relative L2 to min(tol, 3.0e-3 * sqrt(branches upstream)); cap=False holds it to the law alone, for passes
+#     whose inputs already carry drift: a second step on an updated cache, and dense passes with FRESH statistics
+#     (every GroupNorm's mean and rstd are then recomputed from maps that have drifted, which feeds the drift back
+#     into every later branch: measured up to 2.7e-3 per sqrt(branch) there, 2.0e-2 at 62 branches),
 #   * elementwise to max(tol, 10 x its own relative L2): the difference is noise of the drift's size everywhere, never
 #     an isolated wrong element (a bad halo or tile edge is wrong by O(1)),
 #   * bitwise at every position the step may not write.
@@ -96,7 +99,7 @@ def test_tiny_unet_step_vs_oracle(fb, seed):
     fb.fise_masked_unet_step(u, Wd, cd, dev(lat, "bf16"), tsd, kvd_old, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
     got = unpack_cache(fb, u, cd, shapes)
     zero = {k: np.zeros_like(v) for k, v in cache_old.items()}
-    worst = compare_caches(d, got, cache_old, zero, full, bt, TOL["bf16"])
+    worst = compare_caches(d, got, cache_old, zero, full, bt, TOL["bf16"], cap=False)       # recomputed statistics: the law alone
     # statistics of the first GroupNorms see (almost) identical inputs; deeper ones inherit the drift above
     for k in ("down.0.res.0.gn1", "down.0.res.0.gn2", "down.0.tr.0.gn"):
         assert np.abs(got[k + ".mean"] - cache_old[k + ".mean"]).max() < 5e-3, k
@@ -166,7 +169,7 @@ def test_other_architectures_vs_oracle(fb, name, over, bt):
     cd = torch.zeros(fb.fise_unet_cache_bytes(u), dtype=torch.uint8, device=DEV)
     fb.fise_masked_unet_step(u, Wd, cd, dev(lat, "bf16"), tsd, kvd_old, idx_dev(full), full.size, bt, fb.FISE_STATS_FRESH, None, ws)
     zero = {k: np.zeros_like(v) for k, v in cache_old.items()}
-    compare_caches(d, unpack_cache(fb, u, cd, shapes), cache_old, zero, full, bt, TOL["bf16"])
+    compare_caches(d, unpack_cache(fb, u, cd, shapes), cache_old, zero, full, bt, TOL["bf16"], cap=False)
     lat_new = wl.perturb(rng, lat, wl.rect_pixels(rng, H, W, 5, 7), 1.0, "bf16")
     _, _, idx = fo.mask_detect(lat, lat_new, 0.1, bt)
     assert 0 < idx.size < ntiles
