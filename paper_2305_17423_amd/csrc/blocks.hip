@@ -72,8 +72,10 @@ int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hi
     // activated input at the active pixels (the ring outside them is unchanged), and conv1 writes conv2's.
     const bool have_acts = dv && dv->trust && !a->stats_fresh;
     if (a->stats_fresh) {
-        if (int e = fise_groupnorm_stats(a->x0, a->x1, FISE_BF16, B, H, W, a->C0, a->C1, a->G, 1e-5f, a->gn1_mean, a->gn1_rstd, ws, st)) return e;
-        if (dv) if (int e = launch_gn_scale_shift(a->gn1_mean, a->gn1_rstd, a->gn1_gamma, a->gn1_beta, B, Ci, a->G, dv->ss_in, st)) return e;
+        if (dv) {
+            if (int e = launch_gn_stats_table(a->x0, a->x1, B, H, W, a->C0, a->C1, a->G, 1e-5f, a->gn1_mean, a->gn1_rstd, a->gn1_gamma,
+                                              a->gn1_beta, dv->ss_in, ws, st)) return e;
+        } else if (int e = fise_groupnorm_stats(a->x0, a->x1, FISE_BF16, B, H, W, a->C0, a->C1, a->G, 1e-5f, a->gn1_mean, a->gn1_rstd, ws, st)) return e;
     }
     // the normalised + activated input (active tiles and their ring) is written once, then convolved
     if (!have_acts)
@@ -88,8 +90,10 @@ int run_resnet(const fise_resnet_args* a, void* ws, const IgemmWorkspace* iw, hi
     }
     if (int e = launch_igemm(c1, iw, st)) return e;
     if (a->stats_fresh) {
-        if (int e = fise_groupnorm_stats(a->h1_cache, nullptr, FISE_BF16, B, H, W, Co, 0, a->G, 1e-5f, a->gn2_mean, a->gn2_rstd, ws, st)) return e;
-        if (dv) if (int e = launch_gn_scale_shift(a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, B, Co, a->G, dv->ss_mid, st)) return e;
+        if (dv) {
+            if (int e = launch_gn_stats_table(a->h1_cache, nullptr, B, H, W, Co, 0, a->G, 1e-5f, a->gn2_mean, a->gn2_rstd, a->gn2_gamma,
+                                              a->gn2_beta, dv->ss_mid, ws, st)) return e;
+        } else if (int e = fise_groupnorm_stats(a->h1_cache, nullptr, FISE_BF16, B, H, W, Co, 0, a->G, 1e-5f, a->gn2_mean, a->gn2_rstd, ws, st)) return e;
     }
     if (!have_acts)
         if (int e = launch_gn_act_halo(a->h1_cache, nullptr, Co, 0, B, H, W, a->gn2_mean, a->gn2_rstd, a->gn2_gamma, a->gn2_beta, a->G, 1,
@@ -140,8 +144,10 @@ int run_transformer(const fise_transformer_args* a, void* workspace, const Igemm
     auto into_h = [&](IgemmArgs& g) { g.res = (const bf16_t*)hb; g.res_compact = 2; g.out[0] = (bf16_t*)hb; g.out_mode[0] = OUT_COMPACT_F32; };
 
     if (a->stats_fresh) {
-        if (int e = fise_groupnorm_stats(a->x, nullptr, FISE_BF16, B, H, W, C, 0, a->G, 1e-6f, a->gn_mean, a->gn_rstd, ws + wl.gn, st)) return e;
-        if (dv) if (int e = launch_gn_scale_shift(a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta, B, C, a->G, dv->ss_in, st)) return e;
+        if (dv) {
+            if (int e = launch_gn_stats_table(a->x, nullptr, B, H, W, C, 0, a->G, 1e-6f, a->gn_mean, a->gn_rstd, a->gn_gamma, a->gn_beta,
+                                              dv->ss_in, ws + wl.gn, st)) return e;
+        } else if (int e = fise_groupnorm_stats(a->x, nullptr, FISE_BF16, B, H, W, C, 0, a->G, 1e-6f, a->gn_mean, a->gn_rstd, ws + wl.gn, st)) return e;
     }
     // With a derived map the 1x1 in reads the normalised input (written by the producer of x under the cached
     // statistics, or here); without one it normalises in its own prologue.

@@ -119,6 +119,10 @@ int launch_iota(int* p, int n, hipStream_t st);
 // ss[B, C] = (rstd * gamma, beta - mean * rstd * gamma): the scale / shift form of a GroupNorm with given statistics.
 int launch_gn_scale_shift(const float* mean, const float* rstd, const void* gamma, const void* beta, int B, int C, int G, float2* ss,
                           hipStream_t st);
+// mean / rstd [B, G] of the bf16 map x0 | x1 and the scale / shift table built from them (workspace as for
+// fise_groupnorm_stats).
+int launch_gn_stats_table(const void* x0, const void* x1, int B, int H, int W, int C0, int C1, int G, float eps, float* mean, float* rstd,
+                          const void* gamma, const void* beta, float2* ss, void* workspace, hipStream_t st);
 // act[B,H,W,C0+C1] = GroupNorm(x0|x1) (+SiLU) with the given statistics at the active tiles and their one-pixel ring.
 int launch_gn_act_halo(const void* x0, const void* x1, int C0, int C1, int B, int H, int W, const float* mean, const float* rstd,
                        const void* gamma, const void* beta, int G, int silu, const int* tile_idx, int n_active, int tile, void* act,

@@ -51,9 +51,12 @@ __global__ __launch_bounds__(256) void gn_partial_kernel(const T* __restrict__ x
 // many pixel stripes as 256 lanes allow (lane = (stripe, 8-channel piece)), so that a lane's loads do not wait for one
 // another.  Stripe sums are float (a dozen terms each), added per channel in stripe order in double.
 __global__ __launch_bounds__(256) void gn_partial_vec_kernel(const bf16_t* __restrict__ x0, const bf16_t* __restrict__ x1, int HW,
-                                                             int C0, int C1, int G, double2* __restrict__ partial) {
-    extern __shared__ double2 chan[];                    // [C0 + C1], then the stripe sums of one pass
-    const int C = C0 + C1, cpg = C / G, CH8 = C / 8, tid = threadIdx.x;
+                                                             int C0, int C1, int G, int gps, double2* __restrict__ partial) {
+    extern __shared__ double2 chan[];                    // [channels of the slab], then the stripe sums of one pass
+    const int C = C0 + C1, cpg = C / G, tid = threadIdx.x;
+    // blockIdx.z: a slab of gps whole groups (its channel range starts and ends on a multiple of 8)
+    const int g0 = blockIdx.z * gps, g1 = min(G, g0 + gps);
+    const int c_lo = g0 * cpg, CH8 = (g1 - g0) * cpg / 8;
     float2* stripe = reinterpret_cast<float2*>(chan + C);        // [stripes][pieces of the pass][8]
     const int b = blockIdx.y, chunk = blockIdx.x, nchunk = gridDim.x;
     const int p0 = chunk * GS_PIX, p1 = min(HW, p0 + GS_PIX);
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(256) void gn_partial_vec_kernel(const bf16_t* __res
         const int CH = min(256, CH8 - pc), PS = 256 / CH;
         const int cc = tid % CH, ps = tid / CH;
         if (ps < PS) {
-            const int c = (pc + cc) * 8;
+            const int c = c_lo + (pc + cc) * 8;
             const bf16_t* src = c < C0 ? x0 + (size_t)b * HW * C0 + c : x1 + (size_t)b * HW * C1 + (c - C0);
             const size_t pitch = c < C0 ? C0 : C1;
             float s[8], q[8];
@@ -87,17 +90,21 @@ __global__ __launch_bounds__(256) void gn_partial_vec_kernel(const bf16_t* __res
         }
         __syncthreads();
     }
-    for (int g = tid; g < G; g += 256) {
+    for (int g = g0 + tid; g < g1; g += 256) {
         double s = 0, q = 0;
-        for (int c = g * cpg; c < (g + 1) * cpg; ++c) { s += chan[c].x; q += chan[c].y; }
+        for (int c = g * cpg - c_lo; c < (g + 1) * cpg - c_lo; ++c) { s += chan[c].x; q += chan[c].y; }
         partial[((size_t)b * nchunk + chunk) * G + g] = make_double2(s, q);
     }
 }
 
 // stage 2: one wave per (b, g); lane k adds chunks k, k + 64, ... in that order, the 64 lane sums are added in a
 // fixed tree.
+// With ss the wave also writes the group's channels of the (scale, shift) table, from the rounded statistics it has
+// just stored: ss[b, c] = (rstd * gamma[c], beta[c] - mean * rstd * gamma[c]).
 __global__ __launch_bounds__(64) void gn_finish_kernel(const double2* __restrict__ partial, int nchunk, int BG, int G, double count,
-                                                       float eps, float* __restrict__ mean, float* __restrict__ rstd) {
+                                                       float eps, float* __restrict__ mean, float* __restrict__ rstd,
+                                                       const bf16_t* __restrict__ gamma, const bf16_t* __restrict__ beta, int C,
+                                                       float2* __restrict__ ss) {
     const int i = blockIdx.x, lane = threadIdx.x;
     if (i >= BG) return;
     const int b = i / G, g = i % G;
@@ -105,12 +112,19 @@ __global__ __launch_bounds__(64) void gn_finish_kernel(const double2* __restrict
     for (int k = lane; k < nchunk; k += 64) { const double2 v = partial[((size_t)b * nchunk + k) * G + g]; s += v.x; q += v.y; }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) { s += __shfl_down(s, off); q += __shfl_down(q, off); }
-    if (lane != 0) return;
+    s = __shfl(s, 0); q = __shfl(q, 0);
     const double m = s / count;
     double var = q / count - m * m;
     if (var < 0) var = 0;
-    mean[i] = (float)m;
-    rstd[i] = (float)(1.0 / sqrt(var + (double)eps));
+    const float mf = (float)m, rf = (float)(1.0 / sqrt(var + (double)eps));
+    if (lane == 0) { mean[i] = mf; rstd[i] = rf; }
+    if (ss) {
+        const int cpg = C / G;
+        for (int c = g * cpg + lane; c < (g + 1) * cpg; c += 64) {
+            const float sc = rf * bf2f(gamma[c]);
+            ss[(size_t)b * C + c] = make_float2(sc, fmaf(-mf, sc, bf2f(beta[c])));
+        }
+    }
 }
 
 template <typename T>
@@ -391,8 +405,10 @@ extern "C" size_t fise_groupnorm_stats_workspace_bytes(int B, int H, int W, int 
 }
 
 // Both entry points below: argument checks, then the two launches with the partial sums in `partial`.
+// gamma / beta / ss (all or none): the finish launch also writes the GroupNorm's (scale, shift) table.
 static int gn_stats_run(const char* fn, const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
-                        float eps, float* mean, float* rstd, double2* partial, hipStream_t st) {
+                        float eps, float* mean, float* rstd, double2* partial, hipStream_t st, const void* gamma = nullptr,
+                        const void* beta = nullptr, float2* ss = nullptr) {
     const int C = C0 + C1;
     const int HW = H * W, nchunk = ceil_div(HW, GS_PIX);
     const size_t shmem = (size_t)C * sizeof(double2);
@@ -400,16 +416,26 @@ static int gn_stats_run(const char* fn, const void* x, const void* x1, int dtype
     if (shmem > 64 * 1024) return fail(FISE_ERR_SHAPE, "%s: C=%d too large", fn, C);
     const bool vec = dtype == FISE_BF16 && C0 % 8 == 0 && C1 % 8 == 0 && shmem + kStripeBytes <= 64 * 1024 && aligned16(x) &&
                      (C1 == 0 || aligned16(x1));
-    if (vec)
-        hipLaunchKernelGGL(gn_partial_vec_kernel, dim3(nchunk, B), dim3(256), shmem + kStripeBytes, st, (const bf16_t*)x, (const bf16_t*)x1,
-                           HW, C0, C1, G, partial);
+    if (vec) {
+        // small maps have few pixel chunks: the groups are dealt to slabs as well (whole groups whose channel range
+        // is a multiple of 8 wide), aiming at ~512 workgroups
+        const int cpg = C / G;
+        const int unit = cpg % 8 == 0 ? 1 : cpg % 4 == 0 ? 2 : cpg % 2 == 0 ? 4 : 8;       // 8 / gcd(cpg, 8) groups
+        int gps = G;
+        if (G % unit == 0) {
+            const int want = std::max(1, 512 / (nchunk * B));
+            gps = std::max(unit, ceil_div(ceil_div(G, want), unit) * unit);
+        }
+        hipLaunchKernelGGL(gn_partial_vec_kernel, dim3(nchunk, B, ceil_div(G, gps)), dim3(256), shmem + kStripeBytes, st, (const bf16_t*)x,
+                           (const bf16_t*)x1, HW, C0, C1, G, gps, partial);
+    }
     else if (dtype == FISE_F32)
         hipLaunchKernelGGL(gn_partial_kernel<float>, dim3(nchunk, B), dim3(256), shmem, st, (const float*)x, (const float*)x1, HW, C0, C1, G, partial);
     else
         hipLaunchKernelGGL(gn_partial_kernel<bf16_t>, dim3(nchunk, B), dim3(256), shmem, st, (const bf16_t*)x, (const bf16_t*)x1, HW, C0, C1, G, partial);
     FISE_CHECK_LAUNCH("fise_groupnorm_stats(partial)");
     hipLaunchKernelGGL(gn_finish_kernel, dim3(B * G), dim3(64), 0, st, partial, nchunk, B * G, G,
-                       (double)HW * (C / G), eps, mean, rstd);
+                       (double)HW * (C / G), eps, mean, rstd, (const bf16_t*)gamma, (const bf16_t*)beta, C, ss);
     FISE_CHECK_LAUNCH("fise_groupnorm_stats(finish)");
     return FISE_OK;
 }
@@ -421,6 +447,15 @@ static int gn_stats_check(const char* fn, const void* x, const void* x1, int dty
     if (C1 < 0 || (C1 > 0 && !x1)) return fail(FISE_ERR_NULL, "%s: second source missing", fn);
     if (B < 1 || H < 1 || W < 1 || C0 < 1 || G < 1 || (C0 + C1) % G) return fail(FISE_ERR_SHAPE, "%s: B%d H%d W%d C%d G%d", fn, B, H, W, C0 + C1, G);
     return FISE_OK;
+}
+
+// Statistics of a bf16 map (or two concatenated ones) and, in the same two launches, the GroupNorm's scale / shift table.
+int fise::launch_gn_stats_table(const void* x0, const void* x1, int B, int H, int W, int C0, int C1, int G, float eps, float* mean, float* rstd,
+                          const void* gamma, const void* beta, float2* ss, void* workspace, hipStream_t st) {
+    const char* fn = "groupnorm statistics + table";
+    if (!workspace || !gamma || !beta || !ss) return fail(FISE_ERR_NULL, "%s: null pointer", fn);
+    if (int e = gn_stats_check(fn, x0, x1, FISE_BF16, B, H, W, C0, C1, G, mean, rstd)) return e;
+    return gn_stats_run(fn, x0, x1, FISE_BF16, B, H, W, C0, C1, G, eps, mean, rstd, (double2*)workspace, st, gamma, beta, ss);
 }
 
 extern "C" int fise_groupnorm_stats(const void* x, const void* x1, int dtype, int B, int H, int W, int C0, int C1, int G,
