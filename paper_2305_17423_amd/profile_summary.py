@@ -26,9 +26,9 @@ import re
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 
-TRACE_CMD = ("rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/kt -o run -- "
+TRACE_CMD = ("rocprofv3 --kernel-trace --stats --output-format csv -d {d} -o run -- "
              "python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --caches 1 --steps 20 --warmup 3")
-PMC_CMD = ("rocprofv3 --pmc {c} --output-format csv -d gpurun_out/{d} -o run -- "
+PMC_CMD = ("rocprofv3 --pmc {c} --output-format csv -d {d} -o run -- "
            "python3 bench.py --no-cpu-baseline --no-dense --no-sweeps --steps 3 --warmup 1 --caches 1")
 COPY_KIB = 1048576.0        # bench.py ends with fise_calibrate_peaks on a 2 GiB scratch: each copy launch reads and writes 1 GiB
 
@@ -106,7 +106,7 @@ def summarize_trace(d, out):
     ns = len(steady)
     total = sum(v[1] for v in agg.values()) / ns
     lines = ["# Masked UNet step (SD-1.5 shapes, batch 2, 64x64 latent, 10 % blob = 12 of 64 tiles): per-kernel times", "",
-             "Command (on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```", TRACE_CMD, "```", "",
+             "Command (on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```", TRACE_CMD.format(d=os.path.normpath(d)), "```", "",
              f"Steady state: {ns} consecutive masked steps of `run_kernel_trace.csv`, {n_launch} launches per step "
              f"(mask detection + UNet step), summed kernel durations {total / 1e3:.3f} ms per step, start-to-start "
              f"{span / ns / 1e3:.3f} ms per step under the profiler.", "",
@@ -176,7 +176,7 @@ def summarize_traffic(df, dw, out):
                 e["n"][counter] += 1; e[counter] += float(r["Counter_Value"]) * factors[counter]
     lines = ["# HBM traffic of the masked UNet step's kernels (SD-1.5 shapes, 10 % blob): FETCH_SIZE / WRITE_SIZE", "",
              "Commands (two runs, one counter each; on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```",
-             PMC_CMD.format(c="FETCH_SIZE", d="pmc_f"), PMC_CMD.format(c="WRITE_SIZE", d="pmc_w"), "```", "",
+             PMC_CMD.format(c="FETCH_SIZE", d=os.path.normpath(df)), PMC_CMD.format(c="WRITE_SIZE", d=os.path.normpath(dw)), "```", "",
              "bench.py ends with `fise_calibrate_peaks`, whose plain copy kernel (`fise::calib_copy_kernel`) reads 1 GiB and writes 1 GiB per "
              f"launch: the counters are scaled by what they read for it (FETCH_SIZE x {factors['FETCH_SIZE']:.3f}, WRITE_SIZE x "
              f"{factors['WRITE_SIZE']:.3f}).  Steady-state masked steps ({nsteps}), scaled, per launch and per step:", "",
@@ -228,7 +228,7 @@ def summarize_mfma(d, out, avg_us):
                 e[c] += float(r["Counter_Value"]); e["n_" + c] += 1
     lines = ["# MFMA counters of the masked UNet step's kernels (SD-1.5 shapes, 10 % blob)", "",
              "Command (its own run: counters only; on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```",
-             PMC_CMD.format(c="MfmaUtil SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE", d="pmc_m"), "```", "",
+             PMC_CMD.format(c="MfmaUtil SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE", d=os.path.normpath(d)), "```", "",
              f"Per launch, averaged over {nsteps} steady-state masked steps.  `MfmaUtil` is the profiler's derived counter "
              "100 x SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x SIMDs): the share of SIMD-cycles, while the kernel had the GPU, in which a "
              "matrix unit was executing.  `MFMA GFLOP` = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 / 1e9: the bf16 matrix operations actually issued "
