@@ -96,6 +96,58 @@ def test_unet_plan_matches_oracle_tables():
         fb.fise_unet_create(bad)
 
 
+def test_cache_layout_groups_and_move_argument_checks():
+    """The cache buffer's tensor groups are contiguous byte ranges that hold exactly the tensors they name, and the
+    cache-moving entry points refuse bad arguments before they touch the GPU."""
+    import ctypes
+    from oracle import fise_unet_oracle as uo
+    for d in (uo.sd15_desc(), uo.tiny_desc(), uo.tiny_desc(H=32, W=32, base=64)):
+        u = fb.fise_unet_create(d)
+        assert fb.fise_unet_desc_of(u)["H"] == d["H"] and fb.fise_unet_desc_of(u)["mults"] == tuple(d["mults"])
+        L = fb.fise_unet_cache_layout(u)
+        cb = fb.fise_unet_cache_bytes(u)
+        assert L["maps_off"] == 0 and L["kv_off"] == L["maps_bytes"] and L["small_off"] == L["kv_off"] + L["kv_bytes"]
+        assert L["derived_maps_off"] == L["small_off"] + L["small_bytes"] and L["derived_maps_off"] + L["derived_maps_bytes"] == cb
+        assert L["small_off"] < L["stored_bytes"] <= L["derived_maps_off"]
+        for n, off, nbytes in fb.fise_unet_tensors(u, 1):
+            if n.endswith((".mean", ".rstd")):
+                lo, hi = L["small_off"], L["stored_bytes"]
+            elif n.endswith((".k", ".v")):
+                lo, hi = L["kv_off"], L["kv_off"] + L["kv_bytes"]
+            else:
+                lo, hi = 0, L["maps_bytes"]
+            assert lo <= off and off + nbytes <= hi, n
+        for n, off, nbytes in fb.fise_unet_tensors(u, 3):
+            if n.endswith(".ss"):
+                assert L["stored_bytes"] <= off and off + nbytes <= L["derived_maps_off"], n
+            else:
+                assert L["derived_maps_off"] <= off and off + nbytes <= cb, n
+        fb.fise_unet_destroy(u)
+    d = uo.tiny_desc(H=32, W=32, base=64)
+    u = fb.fise_unet_create(d)
+    lib, a, b = fb.lib(), 0x10000000, 0x40000000
+    assert fb.fise_unet_cache_move_workspace_bytes(u) >= (32 * 32 + 16 * 16 + 8 * 8 + 4 * 4) * 4
+    mv = lambda *x: lib.fise_unet_cache_move_active(u, *x)
+    assert mv(a, b, a, 0, 8, 1, 1, a, 1 << 20, None) == 0                      # empty mask: nothing to do
+    assert mv(a, b, a, 3, 8, 2, 1, a, 1 << 20, None) == -2                     # halo
+    assert mv(a, b, a, 3, 8, 1, 8, a, 1 << 20, None) == -2                     # unknown group
+    assert mv(a, b, a, 3, 6, 1, 1, a, 1 << 20, None) == -2                     # base tile must divide the map
+    assert mv(a, b, a, 17, 8, 1, 1, a, 1 << 20, None) == -5                    # more active tiles than tiles
+    assert mv(a, b, a, 3, 8, 1, 1, a, 16, None) == -5                          # workspace too small
+    assert mv(a, a + 256, a, 3, 8, 1, 1, a, 1 << 20, None) == -2               # overlapping buffers
+    assert mv(None, b, a, 3, 8, 1, 1, a, 1 << 20, None) == -1
+    rows = lambda *r: (ctypes.c_int * len(r))(*r)
+    tr = lambda rr, n, *x: lib.fise_unet_cache_move_tile_rows(u, a, b, rr, n, *x)
+    assert tr(rows(0, 1), 0, 8, 1, 1, None) == 0                               # no ranges
+    assert tr(rows(1, 1), 1, 8, 1, 1, None) == -2                              # empty range
+    assert tr(rows(2, 3, 0, 1), 2, 8, 1, 1, None) == -2                        # not ascending
+    assert tr(rows(0, 2, 1, 3), 2, 8, 1, 1, None) == -2                        # overlapping
+    assert tr(rows(0, 5), 1, 8, 1, 1, None) == -2                              # beyond the 4 tile rows
+    assert tr(rows(0, 1), 1, 8, 1, 4, None) == -2                              # V^T is not row-addressed
+    assert tr(rows(0, 1), 1, 8, 3, 1, None) == -2                              # halo
+    fb.fise_unet_destroy(u)
+
+
 def test_apsc_select_is_the_oracle_argmin():
     """The host argmin over the 25 candidate block sizes against the oracle's selection, counts taken from the oracle."""
     import numpy as np
