@@ -312,6 +312,16 @@ def test_sd15_unet_module_by_module(fb, capsys):
     run_module_by_module(fb, uo.sd15_desc(), 5020, 0.02, 8, 0.1, say)
 
 
+def test_sd15_96x96_unet_module_by_module(fb, capsys):
+    """The same check at the latent size of 768x768 images: SD-1.5 widths, 96x96 latent (144 tiles of 8x8; levels
+    96 / 48 / 24 / 12, none a power of two), batch 2, 10 % blob.  Every module of the plan against the oracle, its
+    inputs identical on both sides."""
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    run_module_by_module(fb, uo.sd15_desc(H=96, W=96), 5030, 0.02, 8, 0.1, say)
+
+
 def test_masked_step_under_graph_capture(fb):
     """The step allocates nothing, clears nothing with a memset node and never synchronises, so a caller can capture
     it into a HIP graph.  Each replay (with eager work and synchronisations of the test in between, and the cache
