@@ -629,3 +629,26 @@ def test_rectangular_tiles_bruteforce_and_library():
     assert fo.tiles_from_pixels(np.zeros((H, W), np.uint8), (2, 4))[1].size == 0
     with pytest.raises(ValueError):
         fo.tiles_from_pixels(np.zeros((H, W), np.uint8), (3, 4))
+
+
+def test_printed_constants_of_the_paper():
+    """The two index sets the paper prints (tests/golden/, each file cites its passage): the block sizes the adaptive
+    selection searches, and the step range the automatic mask may accumulate over."""
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    read = lambda f: [int(v) for l in open(os.path.join(here, f)) if not l.startswith("#") for v in l.split()]
+    sizes = read("apsc_block_sizes.txt")
+    assert sizes == [2, 4, 8, 16, 32]
+    # the oracle's search visits exactly these sizes: a mask that only the largest / smallest block shape serves best
+    pix = np.zeros((32, 32), np.uint8); pix[:, :] = 1
+    assert fo.apsc_block_size(pix)[:2] == (sizes[-1], sizes[-1])             # everything active: the largest block wins
+    one = np.zeros((32, 32), np.uint8); one[5, 7] = 1
+    assert fo.apsc_block_size(one)[:2] == (sizes[0], sizes[0])               # one pixel: the smallest
+    assert all(fo.apsc_cost(pix, h, w) is not None for h in sizes for w in sizes)
+    t1, t2 = read("mask_accumulation_steps.txt")
+    rng = np.random.default_rng(3)
+    xs = [rng.standard_normal((1, 4, 4, 2)) for _ in range(t2 - t1 + 1)]
+    ys = [rng.standard_normal((1, 4, 4, 2)) for _ in range(t2 - t1 + 1)]
+    acc = fo.accumulate_diff(xs, ys)                                         # any sub-range of the printed range is allowed
+    assert acc.shape == (4, 4) and np.all(acc >= 0)
+    assert np.allclose(acc, sum(np.abs(x - y).mean(axis=(0, 3)) for x, y in zip(xs, ys)))
