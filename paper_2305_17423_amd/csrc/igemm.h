@@ -59,9 +59,26 @@ struct BlockDerived {
 
 #if defined(__HIPCC__)
 // Four consecutive channels col .. col + 3 of pixel `pix` (batch element b): every view gets its activation.
-__device__ __forceinline__ void put_views4(const GnView* view, int nview, int b, unsigned pix, int col, const float (&v)[4]) {
-    typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+// In two halves, so that an epilogue can request the table entries of all its items together with its other
+// operands and use them later (loaded where they are used, each item pays a round trip of its own in front of
+// its stores): view_ss_load fetches the four (scale, shift) pairs per view, put_views4 applies them.
+struct ViewSS { float s[2][8]; };
+__device__ __forceinline__ void view_ss_load(const GnView* view, int nview, int b, int col, ViewSS& o) {
     typedef float f32x4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        f32x4v s01 = {0.f, 0.f, 0.f, 0.f}, s23 = s01;
+        if (i < nview) {
+            const GnView w = view[i];
+            auto sp = (const __attribute__((address_space(1))) f32x4v*)(w.ss + (size_t)b * w.dstC + w.c_off + col);
+            s01 = sp[0]; s23 = sp[1];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { o.s[i][q] = s01[q]; o.s[i][4 + q] = s23[q]; }
+    }
+}
+__device__ __forceinline__ void put_views4(const GnView* view, int nview, unsigned pix, int col, const float (&v)[4], const ViewSS& ss) {
+    typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
     const unsigned p01 = f2bf2(v[0], v[1]), p23 = f2bf2(v[2], v[3]);      // the values as stored
     const float x[4] = {__uint_as_float(p01 << 16), __uint_as_float(p01 & 0xffff0000u), __uint_as_float(p23 << 16),
                         __uint_as_float(p23 & 0xffff0000u)};
@@ -69,17 +86,21 @@ __device__ __forceinline__ void put_views4(const GnView* view, int nview, int b,
     for (int i = 0; i < 2; ++i) {
         if (i >= nview) break;
         const GnView w = view[i];
-        const int c = w.c_off + col;
-        auto sp = (const __attribute__((address_space(1))) f32x4v*)(w.ss + (size_t)b * w.dstC + c);
-        const f32x4v s01 = sp[0], s23 = sp[1];
-        float u[4] = {fmaf(x[0], s01[0], s01[1]), fmaf(x[1], s01[2], s01[3]), fmaf(x[2], s23[0], s23[1]), fmaf(x[3], s23[2], s23[3])};
+        float u[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) u[q] = fmaf(x[q], ss.s[i][2 * q], ss.s[i][2 * q + 1]);
         if (w.silu) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) u[q] = silu_f(u[q]);
         }
-        auto dp = (__attribute__((address_space(1))) u32x2v*)(w.dst + (size_t)pix * w.dstC + c);
+        auto dp = (__attribute__((address_space(1))) u32x2v*)(w.dst + (size_t)pix * w.dstC + w.c_off + col);
         *dp = u32x2v{f2bf2(u[0], u[1]), f2bf2(u[2], u[3])};
     }
+}
+__device__ __forceinline__ void put_views4(const GnView* view, int nview, int b, unsigned pix, int col, const float (&v)[4]) {
+    ViewSS ss;
+    view_ss_load(view, nview, b, col, ss);
+    put_views4(view, nview, pix, col, v, ss);
 }
 // One channel (the element-wise epilogue of the register-staged kernel).
 __device__ __forceinline__ void put_views1(const GnView* view, int nview, int b, size_t pix, int col, float v) {

@@ -108,7 +108,9 @@ __device__ __forceinline__ OutSel out_sel(const IgemmArgs& a) {
 }
 
 // Four consecutive columns col .. col + 3 of one section (col % 4 == 0, section widths are multiples of 4).
-__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& o, int gm, const OutPos& p, int col, const float (&v)[4]) {
+// vss: the view tables of this item when the caller has fetched them ahead (null: fetched here)
+__device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& o, int gm, const OutPos& p, int col, const float (&v)[4],
+                                              const ViewSS* vss = nullptr) {
     // at most three sections: two compares instead of a division
     const bool s1 = col >= o.sect_n, s2 = col >= 2 * o.sect_n;
     const int scol = col - ((int)s1 + (int)s2) * o.sect_n;
@@ -130,7 +132,10 @@ __device__ __forceinline__ void epilogue_put4(const IgemmArgs& a, const OutSel& 
         *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)gm * o.sect_n + scol)) = packed;
     } else {
         *as_global(reinterpret_cast<u32x2_t*>(outp + (size_t)p.pix * o.sect_n + scol)) = packed;
-        if (a.nview) put_views4(a.view, a.nview, p.b, p.pix, scol, v);
+        if (a.nview) {
+            if (vss) put_views4(a.view, a.nview, p.pix, scol, v, *vss);
+            else put_views4(a.view, a.nview, p.b, p.pix, scol, v);
+        }
     }
 }
 
@@ -276,6 +281,14 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                     rf[it] = src[ok[it] ? e4 : 0];
                 }
             }
+            // the consumers' scale / shift entries of every item, requested with the residuals (tiles of four items per
+            // thread on four waves: the others have no registers to spare and fetch them item by item)
+            constexpr bool kViewsAhead = NT <= 256 && MAXI <= 4;
+            ViewSS vss[kViewsAhead ? MAXI : 1];
+            if (kViewsAhead && out_map && a.nview) {
+#pragma unroll
+                for (int it = 0; it < MAXI; ++it) view_ss_load(a.view, a.nview, ok[it] ? pos[it].b : 0, ok[it] ? colv[it] : 0, vss[it]);
+            }
             auto dst16 = as_global(reinterpret_cast<u32x2_t*>(out_f32 ? reinterpret_cast<unsigned long long>(a.mirror) : osel.base));
             auto dst32 = as_global(reinterpret_cast<f32x4v_t*>(osel.base));
             const bool put16 = !out_f32 || a.mirror != nullptr;
@@ -290,7 +303,11 @@ __device__ __forceinline__ void finish_tile(const IgemmArgs& a, f32x16_t (&acc)[
                 const size_t e4 = ((out_map ? (size_t)pos[it].pix : (size_t)(m0 + rowv[it])) * a.N + colv[it]) >> 2;
                 if (out_f32) dst32[e4] = f32x4v_t{v0, v1, v2, v3};
                 if (put16) dst16[e4] = u32x2_t{f2bf2(v0, v1), f2bf2(v2, v3)};
-                if (out_map && a.nview) { const float vv[4] = {v0, v1, v2, v3}; put_views4(a.view, a.nview, pos[it].b, pos[it].pix, colv[it], vv); }
+                if (out_map && a.nview) {
+                    const float vv[4] = {v0, v1, v2, v3};
+                    if (kViewsAhead) put_views4(a.view, a.nview, pos[it].pix, colv[it], vv, vss[it]);
+                    else put_views4(a.view, a.nview, pos[it].b, pos[it].pix, colv[it], vv);
+                }
             }
             return;
         }
@@ -939,6 +956,7 @@ __global__ __launch_bounds__(64 * NW) void igemm_wsk_kernel(const IgemmArgs a) {
     constexpr int ITEMS = (BM * BN / 4 + NT - 1) / NT;
     int e_r[ITEMS], e_c[ITEMS]; bool e_ok[ITEMS]; OutPos e_pos[ITEMS];
     u32x2_t e_bias[ITEMS], e_bias2[ITEMS], e_gate[ITEMS], e_res16[ITEMS]; f32x4v_t e_res32[ITEMS], e_temb[ITEMS];
+    ViewSS e_vss[ITEMS];
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         const int item = tid + it * NT;
@@ -960,6 +978,7 @@ __global__ __launch_bounds__(64 * NW) void igemm_wsk_kernel(const IgemmArgs a) {
             if (a.res_compact == 2) e_res32[it] = *as_global(reinterpret_cast<const f32x4v_t*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col));
             else e_res16[it] = *as_global(reinterpret_cast<const u32x2_t*>(a.res + (a.res_compact ? (size_t)gm : (size_t)e_pos[it].pix) * a.N + col));
         }
+        if (a.nview) view_ss_load(a.view, a.nview, e_pos[it].b, col, e_vss[it]);
     }
 
     unsigned soff = (unsigned)kc_begin * 128u;
@@ -1061,7 +1080,7 @@ __global__ __launch_bounds__(64 * NW) void igemm_wsk_kernel(const IgemmArgs a) {
         }
         v[0] += e_temb[it][0] + (e_res32[it][0] + lo(e_res16[it][0])); v[1] += e_temb[it][1] + (e_res32[it][1] + hi(e_res16[it][0]));
         v[2] += e_temb[it][2] + (e_res32[it][2] + lo(e_res16[it][1])); v[3] += e_temb[it][3] + (e_res32[it][3] + hi(e_res16[it][1]));
-        epilogue_put4(a, osel, m0 + r, e_pos[it], by * OW + c, v);
+        epilogue_put4(a, osel, m0 + r, e_pos[it], by * OW + c, v, a.nview ? &e_vss[it] : nullptr);
     }
 #endif
 }
@@ -1105,6 +1124,8 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
     if (pix) tile_id = a.tile_idx[m / tt];
     if (a.res && a.res_compact == 2) res_v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + (size_t)gm * a.N + col);
     else if (a.res && a.res_compact) res_raw = *reinterpret_cast<const uint2*>(a.res + (size_t)gm * a.N + col);
+    ViewSS vss;
+    if (a.nview) view_ss_load(a.view, a.nview, b, col, vss);       // (normalised copies: one map section, so col is its column)
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f), g = v;
 #pragma unroll 4
     for (int z = 0; z < a.splits; ++z) {                  // split order: deterministic; four splits in flight
@@ -1135,7 +1156,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a) {
                            temb_v.z + (res_v.z + lo(res_raw.y)), temb_v.w + (res_v.w + hi(res_raw.y))};
 #pragma unroll
     for (int q = 0; q < 4; ++q) r[q] += post[q];
-    epilogue_put4(a, osel, gm, pos, col, r);
+    epilogue_put4(a, osel, gm, pos, col, r, a.nview ? &vss : nullptr);
 }
 
 // Split-K reduce fused with the LayerNorm that follows a residual-stream GEMM: LPR lanes share a row of
