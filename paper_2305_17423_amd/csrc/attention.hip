@@ -109,6 +109,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
     for (int e = tid; e < AT_BKV * KP / 8; e += 256) reinterpret_cast<uint4*>(&Ks[0][0])[e] = make_uint4(0, 0, 0, 0);
     for (int e = tid; e < DB * 32 * VP / 8; e += 256) reinterpret_cast<uint4*>(&Vs[0][0])[e] = make_uint4(0, 0, 0, 0);
     __syncthreads();
+    // The query fragments must have ARRIVED before the key loop is entered: while their loads are still counted as
+    // outstanding at the loop head, the compiler's wait-count bookkeeping (merged over the loop's paths) puts a
+    // wait for ALL loads in front of the first MFMA of every iteration, i.e. right behind the prefetch of the next
+    // key block, which then never overlaps anything.  Naming the fragments as operands here places that wait once.
+#pragma unroll
+    for (int ks = 0; ks < KD; ++ks) asm volatile("" ::"v"(qf[ks]));
     auto fetch = [&](int blk, int slot) {
         const int k0 = blk * AT_BKV;
         if (k0 + AT_BKV <= n_keys) {                     // uniform: a block of existing keys
