@@ -286,7 +286,8 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __res
     const float* ml0 = part_ml + (((size_t)b * heads + h) * M + m) * 2;
     const float* o0 = part_o + ((size_t)b * M + m) * C + c;
     float mx = -INFINITY;
-    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml0[s * ml_stride]);
+#pragma unroll 8
+    for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml0[s * ml_stride]);     // unrolled: the loads go out together, not one round trip each
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
     float den = 0.f;
 #pragma unroll 4

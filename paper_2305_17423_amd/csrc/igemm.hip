@@ -1173,18 +1173,36 @@ __global__ __launch_bounds__(256) void igemm_reduce_ln_kernel(const IgemmArgs a)
     const int l = threadIdx.x % LPR;
     if (row >= rows) return;                      // whole LPR-lane groups leave together
     const size_t off = (size_t)row * C + l * 20;
+    // LayerNorm scale and shift of this lane's channels: requested here with everything else (read in the store loop
+    // they would each wait behind the previous store, which the compiler must assume may alias them)
+    uint2 gv[5], bv[5];
+    {
+        const uint2* g2 = reinterpret_cast<const uint2*>(a.ln_gamma + l * 20);
+        const uint2* b2 = reinterpret_cast<const uint2*>(a.ln_beta + l * 20);
+#pragma unroll
+        for (int j = 0; j < 5; ++j) { gv[j] = g2[j]; bv[j] = b2[j]; }
+    }
     float4 v[5];
     {
-        const uint2* b2 = a.bias ? reinterpret_cast<const uint2*>(a.bias + l * 20) : nullptr;
-        const float4* r4 = a.res ? reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + off) : nullptr;
+        // residual and bias: each as one batch of loads behind one uniform test (tested per element they became
+        // five load - wait - add rounds)
+        uint2 bb[5];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) { v[j] = make_float4(0.f, 0.f, 0.f, 0.f); bb[j] = make_uint2(0u, 0u); }
+        if (a.res) {
+            const float4* r4 = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.res) + off);
+#pragma unroll
+            for (int j = 0; j < 5; ++j) v[j] = r4[j];
+        }
+        if (a.bias) {
+            const uint2* b2 = reinterpret_cast<const uint2*>(a.bias + l * 20);
+#pragma unroll
+            for (int j = 0; j < 5; ++j) bb[j] = b2[j];
+        }
 #pragma unroll
         for (int j = 0; j < 5; ++j) {
-            v[j] = r4 ? r4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
-            if (b2) {
-                const uint2 bv = b2[j];
-                v[j].x += __uint_as_float(bv.x << 16); v[j].y += __uint_as_float(bv.x & 0xffff0000u);
-                v[j].z += __uint_as_float(bv.y << 16); v[j].w += __uint_as_float(bv.y & 0xffff0000u);
-            }
+            v[j].x += __uint_as_float(bb[j].x << 16); v[j].y += __uint_as_float(bb[j].x & 0xffff0000u);
+            v[j].z += __uint_as_float(bb[j].y << 16); v[j].w += __uint_as_float(bb[j].y & 0xffff0000u);
         }
     }
     const float4* P = reinterpret_cast<const float4*>(a.partial + off);
@@ -1218,16 +1236,13 @@ __global__ __launch_bounds__(256) void igemm_reduce_ln_kernel(const IgemmArgs a)
 #pragma unroll
     for (int o = LPR / 2; o > 0; o >>= 1) q += __shfl_xor(q, o);
     const float rs = rsqrtf(q / C + a.ln_eps);
-    const uint2* g2 = reinterpret_cast<const uint2*>(a.ln_gamma + l * 20);
-    const uint2* b2 = reinterpret_cast<const uint2*>(a.ln_beta + l * 20);
     uint2* o2 = reinterpret_cast<uint2*>(a.ln_out + off);
 #pragma unroll
     for (int j = 0; j < 5; ++j) {
-        const uint2 gv = g2[j], bv = b2[j];
-        const float y0 = (v[j].x - mu) * rs * __uint_as_float(gv.x << 16) + __uint_as_float(bv.x << 16);
-        const float y1 = (v[j].y - mu) * rs * __uint_as_float(gv.x & 0xffff0000u) + __uint_as_float(bv.x & 0xffff0000u);
-        const float y2 = (v[j].z - mu) * rs * __uint_as_float(gv.y << 16) + __uint_as_float(bv.y << 16);
-        const float y3 = (v[j].w - mu) * rs * __uint_as_float(gv.y & 0xffff0000u) + __uint_as_float(bv.y & 0xffff0000u);
+        const float y0 = (v[j].x - mu) * rs * __uint_as_float(gv[j].x << 16) + __uint_as_float(bv[j].x << 16);
+        const float y1 = (v[j].y - mu) * rs * __uint_as_float(gv[j].x & 0xffff0000u) + __uint_as_float(bv[j].x & 0xffff0000u);
+        const float y2 = (v[j].z - mu) * rs * __uint_as_float(gv[j].y << 16) + __uint_as_float(bv[j].y << 16);
+        const float y3 = (v[j].w - mu) * rs * __uint_as_float(gv[j].y & 0xffff0000u) + __uint_as_float(bv[j].y & 0xffff0000u);
         o2[j] = make_uint2(f2bf2(y0, y1), f2bf2(y2, y3));
     }
 }
