@@ -147,6 +147,38 @@ ARCHS = [
 ]
 
 
+@pytest.mark.parametrize("tiles", [[0], [3, 12, 15], [1, 4, 7, 13], [5, 10], list(range(16))],
+                         ids=["corner", "three-corners", "edges", "diagonal-neighbours", "all-tiles-cached-stats"])
+def test_tiny_unet_masks_at_the_border(fb, tiles):
+    """Tile lists chosen for their geometry, not drawn: tiles in the corners and on the edges of the map (the ring of
+    every level is clipped by the zero padding there, down to the 1x1 tiles of the coarsest level), tiles that touch
+    only at a corner (each other's ring), and the full list under cached statistics."""
+    d = uo.tiny_desc(H=32, W=32, base=64)
+    rng, P, lat, ctx_old, ctx_new, t_sin = problem(d, 5050, 0.04)
+    H, W, bt = d["H"], d["W"], 8
+    shapes = uo.cache_shapes(d)
+    kv_old = uo.context_kv_all(P, d, ctx_old, "bf16"); kv_new = uo.context_kv_all(P, d, ctx_new, "bf16")
+    _, cache_old = uo.unet_dense(P, d, lat, t_sin, kv_old, "bf16")
+    idx = np.asarray(tiles, np.int32)
+    act = active_mask(idx, bt, H, W)
+    lat_new = np.asarray(lat, np.float64).copy()
+    lat_new[:, act] += rng.standard_normal(lat_new[:, act].shape)          # the whole active area changes
+    lat_new = fo.round_store(lat_new, "bf16")
+    want = {k: v.copy() for k, v in cache_old.items()}
+    uo.unet_step(P, d, want, lat_new, t_sin, kv_new, idx, bt, "bf16")
+    u = fb.fise_unet_create(d)
+    Wd = pack_weights(fb, u, P)
+    kvd = torch.zeros(fb.fise_unet_ctxkv_bytes(u), dtype=torch.uint8, device=DEV)
+    fb.fise_unet_context_kv(u, Wd, dev(ctx_new, "bf16"), kvd)
+    ws = torch.zeros(fb.fise_unet_workspace_bytes(u, 16, bt), dtype=torch.uint8, device=DEV)
+    cm = pack_cache(fb, u, cache_old, Wd)
+    fb.fise_masked_unet_step(u, Wd, cm, dev(lat_new, "bf16"), dev(t_sin), kvd, idx_dev(idx), idx.size, bt, fb.FISE_STATS_CACHED, None, ws)
+    # With the full list nothing a branch reads is an exact cached value any more (no untouched ring, no untouched
+    # keys and values to dilute the drift), as in a dense pass: that case is held to the drift law alone.
+    compare_caches(d, unpack_cache(fb, u, cm, shapes), want, cache_old, idx, bt, TOL["bf16"], cap=idx.size < 16)
+    fb.fise_unet_destroy(u)
+
+
 @pytest.mark.parametrize("name,over,bt", ARCHS, ids=[a[0] for a in ARCHS])
 def test_other_architectures_vs_oracle(fb, name, over, bt):
     """The plan is parametric: other depths, widths, attention placements, head counts, context sizes, batch sizes
